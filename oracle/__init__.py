@@ -1,0 +1,177 @@
+"""CPU oracle for the device-state snapshot path -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s cpu_baseline
+leg may import this package.  The product (``paper_2202_07848_amd``) never
+does, and this package never imports the product.
+
+The arithmetic lives in ``ckpt_oracle.c`` (plain C, built with gcc into
+``libckpt_oracle.so`` next to it).  This module only marshals NumPy arrays
+into that library: every function takes a list of ``uint8`` arrays (one per
+live buffer, list order = global chunk order) and the chunk size.
+
+Operation names follow the Singularity paper: content checksums of live
+buffers and their comparison (sec. 5.2.1, sec. 6), swap-out of what is not
+de-duplicated (sec. 5.2.1, sec. 4.6) and restore to the same addresses
+(sec. 4.5).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ckpt_oracle.c")
+_LIB = os.path.join(_HERE, "libckpt_oracle.so")
+
+ENTRY_DTYPE = np.dtype(
+    [("buf", "<u4"), ("len", "<u4"), ("buf_off", "<u8"), ("stage_off", "<u8"), ("digest", "<u8")]
+)
+assert ENTRY_DTYPE.itemsize == 32
+
+
+class _Buf(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
+
+
+class _Counts(ctypes.Structure):
+    _fields_ = [("ndirty", ctypes.c_uint64), ("staged_bytes", ctypes.c_uint64),
+                ("overflow", ctypes.c_uint64)]
+
+
+def build(force: bool = False) -> str:
+    """Compile ckpt_oracle.c with gcc.  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread",
+               _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u64, vp = ctypes.c_uint64, ctypes.c_void_p
+        lib.ora_xxh64.restype = u64
+        lib.ora_xxh64.argtypes = [vp, u64, u64]
+        lib.ora_nchunks.restype = u64
+        lib.ora_nchunks.argtypes = [vp, u64, u64]
+        lib.ora_chunk_lens.restype = None
+        lib.ora_chunk_lens.argtypes = [vp, u64, u64, vp]
+        lib.ora_fingerprint.restype = ctypes.c_int
+        lib.ora_fingerprint.argtypes = [vp, u64, u64, vp, ctypes.c_int]
+        lib.ora_diff.restype = None
+        lib.ora_diff.argtypes = [vp, u64, u64, vp, vp, vp, vp]
+        lib.ora_compact.restype = None
+        lib.ora_compact.argtypes = [vp, u64, u64, vp, vp, vp, u64, vp, u64, vp]
+        lib.ora_restore.restype = ctypes.c_int64
+        lib.ora_restore.argtypes = [vp, u64, vp, u64, vp, u64]
+        _lib = lib
+    return _lib
+
+
+def _desc(bufs: Sequence[np.ndarray]):
+    """ctypes descriptor array over a list of contiguous uint8 arrays."""
+    arr = (_Buf * max(1, len(bufs)))()
+    for i, b in enumerate(bufs):
+        if b.dtype != np.uint8 or not b.flags["C_CONTIGUOUS"] or b.ndim != 1:
+            raise TypeError("oracle buffers must be 1-D contiguous uint8 arrays")
+        arr[i].ptr = b.ctypes.data if b.size else None
+        arr[i].nbytes = b.size
+    return arr
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def xxh64(data: bytes | np.ndarray, seed: int = 0) -> int:
+    """XXH64 of a byte string."""
+    a = np.frombuffer(bytes(data), dtype=np.uint8) if not isinstance(data, np.ndarray) else data
+    a = np.ascontiguousarray(a.view(np.uint8).reshape(-1))
+    return int(_load().ora_xxh64(_p(a) if a.size else None, a.size, seed))
+
+
+def nchunks(bufs: Sequence[np.ndarray], chunk: int) -> int:
+    return int(_load().ora_nchunks(_desc(bufs), len(bufs), chunk))
+
+
+def chunk_lens(bufs: Sequence[np.ndarray], chunk: int) -> np.ndarray:
+    n = nchunks(bufs, chunk)
+    lens = np.zeros(n, dtype=np.uint32)
+    _load().ora_chunk_lens(_desc(bufs), len(bufs), chunk, _p(lens))
+    return lens
+
+
+def fingerprint(bufs: Sequence[np.ndarray], chunk: int, nthreads: int = 1) -> np.ndarray:
+    """dig[k] = XXH64(chunk k, seed 0) for every chunk in global order."""
+    n = nchunks(bufs, chunk)
+    dig = np.zeros(n, dtype=np.uint64)
+    rc = _load().ora_fingerprint(_desc(bufs), len(bufs), chunk, _p(dig), int(nthreads))
+    if rc != 0:
+        raise RuntimeError("oracle: could not start worker threads")
+    return dig
+
+
+def diff(bufs: Sequence[np.ndarray], chunk: int, dig: np.ndarray,
+         ref: Optional[np.ndarray]) -> Tuple[np.ndarray, dict]:
+    """Positional comparison of checksums; ref=None marks every chunk."""
+    n = nchunks(bufs, chunk)
+    dig = np.ascontiguousarray(dig, dtype=np.uint64)
+    if dig.size != n:
+        raise ValueError("digest count does not match the buffer list")
+    if ref is not None:
+        ref = np.ascontiguousarray(ref, dtype=np.uint64)
+        if ref.size != n:
+            raise ValueError("reference has a different chunk geometry")
+    mask = np.zeros(n, dtype=np.uint8)
+    c = _Counts()
+    _load().ora_diff(_desc(bufs), len(bufs), chunk, _p(dig), _p(ref), _p(mask), ctypes.byref(c))
+    return mask, {"ndirty": c.ndirty, "staged_bytes": c.staged_bytes, "overflow": c.overflow}
+
+
+def compact(bufs: Sequence[np.ndarray], chunk: int, mask: np.ndarray, dig: np.ndarray,
+            staging_cap: Optional[int] = None, manifest_cap: Optional[int] = None,
+            fill: int = 0xA5) -> Tuple[np.ndarray, np.ndarray, dict]:
+    """Gather the marked chunks.  Returns (staging[staging_cap], manifest[manifest_cap],
+    counts).  Bytes / entries the call does not write keep the ``fill`` pattern."""
+    n = nchunks(bufs, chunk)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    dig = np.ascontiguousarray(dig, dtype=np.uint64)
+    if mask.size != n or dig.size != n:
+        raise ValueError("mask/digest count does not match the buffer list")
+    lens = chunk_lens(bufs, chunk).astype(np.uint64)
+    need = int((((lens + 15) // 16) * 16)[mask != 0].sum())
+    if staging_cap is None:
+        staging_cap = need
+    if manifest_cap is None:
+        manifest_cap = int((mask != 0).sum())
+    staging = np.full(staging_cap, fill, dtype=np.uint8)
+    manifest = np.frombuffer(bytes([fill]) * (32 * manifest_cap), dtype=ENTRY_DTYPE).copy()
+    c = _Counts()
+    _load().ora_compact(_desc(bufs), len(bufs), chunk, _p(mask), _p(dig), _p(staging),
+                        staging_cap, _p(manifest), manifest_cap, ctypes.byref(c))
+    return staging, manifest, {"ndirty": c.ndirty, "staged_bytes": c.staged_bytes,
+                               "overflow": c.overflow}
+
+
+def restore(dst: List[np.ndarray], staging: np.ndarray, manifest: np.ndarray,
+            staging_bytes: Optional[int] = None) -> int:
+    """Scatter staging back into ``dst`` (modified in place).  Returns 0 or
+    -(1 + index of the first entry that does not fit)."""
+    staging = np.ascontiguousarray(staging, dtype=np.uint8)
+    manifest = np.ascontiguousarray(manifest, dtype=ENTRY_DTYPE)
+    if staging_bytes is None:
+        staging_bytes = staging.size
+    for b in dst:
+        if not b.flags["WRITEABLE"]:
+            raise TypeError("destination buffers must be writable")
+    return int(_load().ora_restore(_desc(dst), len(dst), _p(staging), staging_bytes,
+                                   _p(manifest), manifest.size))

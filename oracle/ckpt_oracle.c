@@ -1,0 +1,343 @@
+/*
+ * ckpt_oracle.c -- plain CPU oracle for the device-state snapshot path.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke
+ * check and the benchmark's cpu_baseline leg may call it.  It shares no code
+ * with the HIP library: its own types, its own hash, its own loops.
+ *
+ * What it computes (Singularity paper, sections 4.5, 4.6, 5.2.1 and 6):
+ *   - a content checksum of every live device buffer (sec. 5.2.1, sec. 6),
+ *     here at the granularity of fixed-size chunks inside each buffer, with
+ *     XXH64 (seed 0) as the checksum function -- the paper names none;
+ *   - a comparison of those checksums with another rank's / an earlier
+ *     snapshot's checksums (sec. 5.2.1 "same content checksum", sec. 4.6
+ *     de-dup across workers and across time, sec. 5.2.3 mutation = difference
+ *     of checksum state);
+ *   - the swap-out of only the non-deduplicated data (sec. 5.2.1), here a
+ *     gather into one contiguous staging area plus a manifest;
+ *   - the swap-in / restore that puts the data back at the addresses it came
+ *     from (sec. 4.5), here a scatter driven by the manifest.
+ *
+ * Every function is the definition written out: one loop over buffers, one
+ * over chunks, memcpy for copies.  No blocking, no fusion.  The only
+ * concession to run time is ora_fingerprint's optional static split of the
+ * chunk range over pthreads (chunks are independent by definition).
+ *
+ * Pins (tests/test_oracle_*.py): XXH64 vectors under tests/golden/, agreement
+ * with the installed xxHash library and with a separate big-integer
+ * implementation, brute-force byte comparison, prefix-sum and round-trip
+ * invariants, NumPy closed forms for staging and manifest.
+ */
+#include <pthread.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+  void *ptr;       /* host pointer to the buffer's bytes */
+  uint64_t nbytes; /* may be 0: such a buffer has no chunks */
+} ora_buf_t;
+
+/* One staged chunk.  32 bytes, little-endian fields, no padding. */
+typedef struct {
+  uint32_t buf;       /* index into the buffer list */
+  uint32_t len;       /* true chunk length in bytes (<= chunk size) */
+  uint64_t buf_off;   /* byte offset of the chunk inside its buffer */
+  uint64_t stage_off; /* byte offset of the chunk inside staging */
+  uint64_t digest;    /* the chunk's XXH64 */
+} ora_entry_t;
+
+typedef struct {
+  uint64_t ndirty;       /* chunks whose mask is 1 */
+  uint64_t staged_bytes; /* sum of pad16(len) over those chunks */
+  uint64_t overflow;     /* entries that did not fit the given capacities */
+} ora_counts_t;
+
+/* ------------------------------------------------------------------ XXH64 */
+/* The public XXH64 definition, seed passed in.  All arithmetic is unsigned
+ * 64-bit with wrap-around; input words are little-endian. */
+
+#define P1 0x9E3779B185EBCA87ULL
+#define P2 0xC2B2AE3D27D4EB4FULL
+#define P3 0x165667B19E3779F9ULL
+#define P4 0x85EBCA77C2B2AE63ULL
+#define P5 0x27D4EB2F165667C5ULL
+
+static uint64_t rotl64(uint64_t x, int r) { return (x << r) | (x >> (64 - r)); }
+
+static uint64_t le64(const uint8_t *p) {
+  uint64_t v = 0;
+  for (int i = 7; i >= 0; --i) v = (v << 8) | p[i];
+  return v;
+}
+
+static uint64_t le32(const uint8_t *p) {
+  uint64_t v = 0;
+  for (int i = 3; i >= 0; --i) v = (v << 8) | p[i];
+  return v;
+}
+
+/* One accumulator step: fold one 8-byte word into an accumulator. */
+static uint64_t xxh_round(uint64_t acc, uint64_t word) {
+  acc += word * P2;
+  acc = rotl64(acc, 31);
+  return acc * P1;
+}
+
+/* Fold a finished accumulator into the converged hash. */
+static uint64_t xxh_merge(uint64_t h, uint64_t acc) {
+  h ^= xxh_round(0, acc);
+  return h * P1 + P4;
+}
+
+uint64_t ora_xxh64(const void *data, uint64_t len, uint64_t seed) {
+  const uint8_t *p = (const uint8_t *)data;
+  uint64_t left = len;
+  uint64_t h;
+
+  if (len >= 32) {
+    /* four accumulators, each eats one 8-byte word of every 32-byte stripe */
+    uint64_t v1 = seed + P1 + P2;
+    uint64_t v2 = seed + P2;
+    uint64_t v3 = seed;
+    uint64_t v4 = seed - P1;
+    while (left >= 32) {
+      v1 = xxh_round(v1, le64(p + 0));
+      v2 = xxh_round(v2, le64(p + 8));
+      v3 = xxh_round(v3, le64(p + 16));
+      v4 = xxh_round(v4, le64(p + 24));
+      p += 32;
+      left -= 32;
+    }
+    h = rotl64(v1, 1) + rotl64(v2, 7) + rotl64(v3, 12) + rotl64(v4, 18);
+    h = xxh_merge(h, v1);
+    h = xxh_merge(h, v2);
+    h = xxh_merge(h, v3);
+    h = xxh_merge(h, v4);
+  } else {
+    h = seed + P5;
+  }
+
+  h += len;
+
+  /* the last len mod 32 bytes: 8-byte words, then one 4-byte word, then bytes */
+  while (left >= 8) {
+    h ^= xxh_round(0, le64(p));
+    h = rotl64(h, 27) * P1 + P4;
+    p += 8;
+    left -= 8;
+  }
+  if (left >= 4) {
+    h ^= le32(p) * P1;
+    h = rotl64(h, 23) * P2 + P3;
+    p += 4;
+    left -= 4;
+  }
+  while (left > 0) {
+    h ^= (uint64_t)(*p) * P5;
+    h = rotl64(h, 11) * P1;
+    p += 1;
+    left -= 1;
+  }
+
+  /* avalanche */
+  h ^= h >> 33;
+  h *= P2;
+  h ^= h >> 29;
+  h *= P3;
+  h ^= h >> 32;
+  return h;
+}
+
+/* --------------------------------------------------------------- chunking */
+/* Buffer i is cut into n_i = ceil(nbytes_i / chunk) chunks; chunk j of buffer
+ * i covers bytes [j*chunk, min((j+1)*chunk, nbytes_i)).  A chunk never spans
+ * two buffers.  Global chunk ids run over the buffers in list order. */
+
+static uint64_t chunks_of(uint64_t nbytes, uint64_t chunk) {
+  return nbytes / chunk + (nbytes % chunk != 0);
+}
+
+static uint64_t pad16(uint64_t x) { return (x + 15) & ~(uint64_t)15; }
+
+uint64_t ora_nchunks(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk) {
+  uint64_t n = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) n += chunks_of(bufs[i].nbytes, chunk);
+  return n;
+}
+
+/* Length of every chunk in global order (lens has ora_nchunks entries). */
+void ora_chunk_lens(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, uint32_t *lens) {
+  uint64_t k = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = chunks_of(bufs[i].nbytes, chunk);
+    for (uint64_t j = 0; j < n; ++j) {
+      uint64_t off = j * chunk;
+      uint64_t len = bufs[i].nbytes - off;
+      if (len > chunk) len = chunk;
+      lens[k++] = (uint32_t)len;
+    }
+  }
+}
+
+/* ------------------------------------------------------------ fingerprint */
+/* dig[k] = XXH64(bytes of chunk k, seed 0)  (sec. 5.2.1: a content checksum
+ * of each live buffer; here one per chunk). */
+
+typedef struct {
+  const ora_buf_t *bufs;
+  uint64_t nbufs, chunk;
+  uint64_t k_lo, k_hi; /* this worker hashes global chunk ids [k_lo, k_hi) */
+  uint64_t *dig;
+} fp_job_t;
+
+static void *fp_worker(void *arg) {
+  fp_job_t *job = (fp_job_t *)arg;
+  uint64_t k = 0;
+  for (uint64_t i = 0; i < job->nbufs; ++i) {
+    uint64_t n = chunks_of(job->bufs[i].nbytes, job->chunk);
+    if (k + n <= job->k_lo) { /* whole buffer before this worker's range */
+      k += n;
+      continue;
+    }
+    if (k >= job->k_hi) break;
+    const uint8_t *base = (const uint8_t *)job->bufs[i].ptr;
+    for (uint64_t j = 0; j < n; ++j, ++k) {
+      if (k < job->k_lo || k >= job->k_hi) continue;
+      uint64_t off = j * job->chunk;
+      uint64_t len = job->bufs[i].nbytes - off;
+      if (len > job->chunk) len = job->chunk;
+      job->dig[k] = ora_xxh64(base + off, len, 0);
+    }
+  }
+  return NULL;
+}
+
+/* nthreads <= 1: one plain loop.  Otherwise the chunk id range is split into
+ * nthreads equal contiguous parts, one pthread each.  Returns 0, or -1 if a
+ * thread could not be started. */
+int ora_fingerprint(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, uint64_t *dig,
+                    int nthreads) {
+  uint64_t N = ora_nchunks(bufs, nbufs, chunk);
+  if (nthreads <= 1 || N < 2) {
+    fp_job_t job = {bufs, nbufs, chunk, 0, N, dig};
+    fp_worker(&job);
+    return 0;
+  }
+  if ((uint64_t)nthreads > N) nthreads = (int)N;
+  pthread_t *tid = (pthread_t *)malloc(sizeof(pthread_t) * (size_t)nthreads);
+  fp_job_t *jobs = (fp_job_t *)malloc(sizeof(fp_job_t) * (size_t)nthreads);
+  if (!tid || !jobs) {
+    free(tid);
+    free(jobs);
+    return -1;
+  }
+  int started = 0, rc = 0;
+  for (int t = 0; t < nthreads; ++t) {
+    fp_job_t job = {bufs, nbufs, chunk, N * (uint64_t)t / (uint64_t)nthreads,
+                    N * (uint64_t)(t + 1) / (uint64_t)nthreads, dig};
+    jobs[t] = job;
+    if (pthread_create(&tid[t], NULL, fp_worker, &jobs[t]) != 0) {
+      rc = -1;
+      break;
+    }
+    ++started;
+  }
+  for (int t = 0; t < started; ++t) pthread_join(tid[t], NULL);
+  free(tid);
+  free(jobs);
+  return rc;
+}
+
+/* ------------------------------------------------------------------- diff */
+/* mask[k] = 1 when chunk k must be moved: no reference at all (the first
+ * rank really swaps out, sec. 5.2.1) or its checksum differs from the
+ * reference's checksum at the same position; else 0.  counts gets the number
+ * of such chunks and the staging bytes they need.  overflow is set to 0. */
+void ora_diff(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, const uint64_t *dig,
+              const uint64_t *ref, uint8_t *mask, ora_counts_t *counts) {
+  uint64_t k = 0, ndirty = 0, bytes = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = chunks_of(bufs[i].nbytes, chunk);
+    for (uint64_t j = 0; j < n; ++j, ++k) {
+      uint64_t len = bufs[i].nbytes - j * chunk;
+      if (len > chunk) len = chunk;
+      uint8_t m = (ref == NULL || dig[k] != ref[k]) ? 1 : 0;
+      mask[k] = m;
+      if (m) {
+        ndirty += 1;
+        bytes += pad16(len);
+      }
+    }
+  }
+  counts->ndirty = ndirty;
+  counts->staged_bytes = bytes;
+  counts->overflow = 0;
+}
+
+/* ---------------------------------------------------------------- compact */
+/* Walk the chunks in ascending global id.  Every chunk with mask 1 gets the
+ * next manifest entry and the next pad16(len) bytes of staging: its bytes,
+ * then zeros up to the 16-byte boundary.  Offsets are therefore the exclusive
+ * prefix sum of pad16(len) over the dirty chunks.
+ *
+ * Capacities: entry e is written to the manifest only if e < manifest_cap;
+ * its bytes are written to staging only if, in addition, they end at or
+ * before staging_cap.  Each dirty chunk that misses either test adds one to
+ * counts->overflow.  ndirty and staged_bytes always report the full need. */
+void ora_compact(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, const uint8_t *mask,
+                 const uint64_t *dig, void *staging, uint64_t staging_cap,
+                 ora_entry_t *manifest, uint64_t manifest_cap, ora_counts_t *counts) {
+  uint8_t *out = (uint8_t *)staging;
+  uint64_t k = 0, e = 0, soff = 0, overflow = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = chunks_of(bufs[i].nbytes, chunk);
+    const uint8_t *base = (const uint8_t *)bufs[i].ptr;
+    for (uint64_t j = 0; j < n; ++j, ++k) {
+      if (!mask[k]) continue;
+      uint64_t off = j * chunk;
+      uint64_t len = bufs[i].nbytes - off;
+      if (len > chunk) len = chunk;
+      uint64_t padded = pad16(len);
+      int fits_manifest = e < manifest_cap;
+      int fits_staging = fits_manifest && soff + padded <= staging_cap;
+      if (fits_manifest) {
+        manifest[e].buf = (uint32_t)i;
+        manifest[e].len = (uint32_t)len;
+        manifest[e].buf_off = off;
+        manifest[e].stage_off = soff;
+        manifest[e].digest = dig[k];
+      }
+      if (fits_staging) {
+        memcpy(out + soff, base + off, len);
+        memset(out + soff + len, 0, padded - len);
+      }
+      if (!fits_staging) overflow += 1;
+      e += 1;
+      soff += padded;
+    }
+  }
+  counts->ndirty = e;
+  counts->staged_bytes = soff;
+  counts->overflow = overflow;
+}
+
+/* ---------------------------------------------------------------- restore */
+/* For each manifest entry, in order, copy len bytes from staging back to the
+ * place in the destination buffer list the entry names (sec. 4.5: tensors go
+ * back to the addresses they had).  Nothing else is written.  Returns 0, or
+ * -(1 + index of the first entry that does not fit the destination geometry
+ * or the staging size); entries before it have been applied. */
+int64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, const void *staging,
+                    uint64_t staging_bytes, const ora_entry_t *manifest, uint64_t nentries) {
+  const uint8_t *in = (const uint8_t *)staging;
+  for (uint64_t e = 0; e < nentries; ++e) {
+    const ora_entry_t *m = &manifest[e];
+    if (m->buf >= nbufs) return -(int64_t)(1 + e);
+    if (m->buf_off + m->len > dst[m->buf].nbytes) return -(int64_t)(1 + e);
+    if (m->stage_off + m->len > staging_bytes) return -(int64_t)(1 + e);
+    memcpy((uint8_t *)dst[m->buf].ptr + m->buf_off, in + m->stage_off, m->len);
+  }
+  return 0;
+}

@@ -1,0 +1,262 @@
+"""Pins of the oracle's chunk / diff / compact / restore steps: NumPy closed
+forms, brute-force byte comparison on tiny inputs, and the invariants the
+paper states (sec. 5.2.1: P and O identical across replicas, only the first
+rank swaps them out; sec. 4.5: restore puts bytes back where they were;
+sec. 5.2.3: mutations = difference of checksum state)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2202_07848_amd import workloads as wl
+
+xxhash = pytest.importorskip("xxhash")
+
+
+def rand_bufs(rng, sizes):
+    return [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+
+
+ODD_SIZES = [0, 1, 15, 16, 17, 255, 256, 257, 1000, 4096, 4097, 8191, 8192, 12289, 0, 31, 100000]
+
+
+def np_chunks(bufs, chunk):
+    """Brute-force chunk list: (buffer index, offset, bytes)."""
+    out = []
+    for i, b in enumerate(bufs):
+        for off in range(0, b.size, chunk):
+            out.append((i, off, b[off:off + chunk]))
+    return out
+
+
+@pytest.mark.parametrize("chunk", [256, 1024, 4096])
+def test_chunking_closed_form(chunk):
+    rng = np.random.default_rng(1)
+    bufs = rand_bufs(rng, ODD_SIZES)
+    ref = np_chunks(bufs, chunk)
+    assert oracle.nchunks(bufs, chunk) == len(ref) == sum(-(-n // chunk) for n in ODD_SIZES)
+    lens = oracle.chunk_lens(bufs, chunk)
+    assert lens.tolist() == [c[2].size for c in ref]
+    assert int(lens.sum()) == sum(ODD_SIZES)
+
+
+@pytest.mark.parametrize("chunk", [256, 4096])
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_fingerprint_is_library_hash_of_each_slice(chunk, threads):
+    rng = np.random.default_rng(2)
+    bufs = rand_bufs(rng, ODD_SIZES)
+    dig = oracle.fingerprint(bufs, chunk, threads)
+    want = [xxhash.xxh64_intdigest(c[2].tobytes(), 0) for c in np_chunks(bufs, chunk)]
+    assert dig.tolist() == want
+
+
+def test_empty_inputs():
+    assert oracle.nchunks([], 4096) == 0
+    z = [np.zeros(0, dtype=np.uint8)] * 3
+    assert oracle.nchunks(z, 4096) == 0
+    dig = oracle.fingerprint(z, 4096)
+    mask, cnt = oracle.diff(z, 4096, dig, None)
+    assert dig.size == 0 and mask.size == 0 and cnt == {"ndirty": 0, "staged_bytes": 0,
+                                                        "overflow": 0}
+    st, man, cnt = oracle.compact(z, 4096, mask, dig)
+    assert st.size == 0 and man.size == 0 and cnt["staged_bytes"] == 0
+
+
+@pytest.mark.parametrize("chunk", [256, 1024])
+def test_diff_equals_bytewise_comparison(chunk):
+    """Checksum equality must equal byte equality, chunk by chunk."""
+    rng = np.random.default_rng(3)
+    a = rand_bufs(rng, ODD_SIZES)
+    b = [x.copy() for x in a]
+    # flip single bytes in some chunks, first/last byte of others, leave most alone
+    touched = [(3, 0), (7, 256), (8, 999), (11, 8190), (13, 12288), (16, 99999), (16, 5000)]
+    for i, off in touched:
+        b[i][off] ^= 0x40
+    da, db = oracle.fingerprint(a, chunk), oracle.fingerprint(b, chunk)
+    mask, cnt = oracle.diff(b, chunk, db, da)
+    brute = np.array([not np.array_equal(x[2], y[2])
+                      for x, y in zip(np_chunks(a, chunk), np_chunks(b, chunk))], dtype=np.uint8)
+    assert mask.tolist() == brute.tolist()
+    assert cnt["ndirty"] == int(brute.sum()) == len({(i, off // chunk) for i, off in touched})
+    lens = oracle.chunk_lens(b, chunk).astype(np.int64)
+    assert cnt["staged_bytes"] == int((((lens + 15) // 16) * 16)[brute != 0].sum())
+
+
+def test_diff_identical_replica_and_no_reference():
+    rng = np.random.default_rng(4)
+    a = rand_bufs(rng, ODD_SIZES)
+    dig = oracle.fingerprint(a, 512)
+    mask, cnt = oracle.diff(a, 512, dig, dig.copy())
+    assert mask.sum() == 0 and cnt["ndirty"] == 0 and cnt["staged_bytes"] == 0
+    mask, cnt = oracle.diff(a, 512, dig, None)
+    assert mask.all() and cnt["ndirty"] == dig.size
+    lens = oracle.chunk_lens(a, 512).astype(np.int64)
+    assert cnt["staged_bytes"] == int((((lens + 15) // 16) * 16).sum())
+
+
+def test_diff_rejects_other_geometry():
+    rng = np.random.default_rng(5)
+    a = rand_bufs(rng, [1000, 2000])
+    dig = oracle.fingerprint(a, 256)
+    with pytest.raises(ValueError):
+        oracle.diff(a, 256, dig, dig[:-1])
+
+
+@pytest.mark.parametrize("chunk", [256, 4096])
+def test_compact_closed_form(chunk):
+    """staging == concatenation of zero-padded marked chunks, offsets are the
+    exclusive prefix sum of padded lengths, entries ascend in (buf, offset)."""
+    rng = np.random.default_rng(6)
+    bufs = rand_bufs(rng, ODD_SIZES)
+    dig = oracle.fingerprint(bufs, chunk)
+    mask = (rng.random(dig.size) < 0.4).astype(np.uint8)
+    mask[-1] = 1                       # the ragged last chunk of the last buffer
+    staging, man, cnt = oracle.compact(bufs, chunk, mask, dig)
+    chunks = np_chunks(bufs, chunk)
+    pieces, entries, soff = [], [], 0
+    for k, (i, off, data) in enumerate(chunks):
+        if mask[k]:
+            pad = (-data.size) % 16
+            pieces.append(np.concatenate([data, np.zeros(pad, dtype=np.uint8)]))
+            entries.append((i, data.size, off, soff, int(dig[k])))
+            soff += data.size + pad
+    assert cnt == {"ndirty": len(entries), "staged_bytes": soff, "overflow": 0}
+    assert np.array_equal(staging, np.concatenate(pieces))
+    got = [(int(e["buf"]), int(e["len"]), int(e["buf_off"]), int(e["stage_off"]),
+            int(e["digest"])) for e in man]
+    assert got == entries
+    so = man["stage_off"].astype(np.int64)
+    padded = (man["len"].astype(np.int64) + 15) // 16 * 16
+    assert so[0] == 0 and np.array_equal(so[1:], np.cumsum(padded)[:-1])
+    assert np.all(np.diff(so) > 0)
+    key = man["buf"].astype(np.int64) * (1 << 40) + man["buf_off"].astype(np.int64)
+    assert np.all(np.diff(key) > 0)
+
+
+def test_compact_capacity_limits():
+    rng = np.random.default_rng(7)
+    bufs = rand_bufs(rng, [1000, 1000, 1000])
+    dig = oracle.fingerprint(bufs, 256)
+    mask = np.ones(dig.size, dtype=np.uint8)
+    full_st, full_man, full_cnt = oracle.compact(bufs, 256, mask, dig)
+    assert full_cnt["overflow"] == 0
+    # manifest too small: entries beyond it dropped, their bytes too
+    st, man, cnt = oracle.compact(bufs, 256, mask, dig, staging_cap=full_st.size, manifest_cap=5)
+    assert cnt["ndirty"] == 12 and cnt["overflow"] == 7 and cnt["staged_bytes"] == full_st.size
+    assert np.array_equal(man, full_man[:5])
+    end = int(full_man[5]["stage_off"])
+    assert np.array_equal(st[:end], full_st[:end]) and np.all(st[end:] == 0xA5)
+    # staging too small: all entries listed, bytes only where they fit entirely
+    st, man, cnt = oracle.compact(bufs, 256, mask, dig, staging_cap=700, manifest_cap=12)
+    assert np.array_equal(man, full_man)
+    assert np.array_equal(st[:512], full_st[:512]) and np.all(st[512:] == 0xA5)
+    assert cnt["overflow"] == 10
+
+
+@pytest.mark.parametrize("with_ref", [False, True])
+def test_compact_restore_round_trip(with_ref):
+    rng = np.random.default_rng(8)
+    chunk = 512
+    snap = rand_bufs(rng, ODD_SIZES)
+    dig = oracle.fingerprint(snap, chunk)
+    if with_ref:
+        ref = [x.copy() for x in snap]
+        for i in (4, 9, 13, 16):
+            ref[i][::97] ^= 0x11
+        mask, _ = oracle.diff(snap, chunk, dig, oracle.fingerprint(ref, chunk))
+        assert 0 < mask.sum() < mask.size
+        dst_content = ref
+    else:
+        mask, _ = oracle.diff(snap, chunk, dig, None)
+        dst_content = [rng.integers(0, 256, size=x.size, dtype=np.uint8) for x in snap]
+    staging, man, cnt = oracle.compact(snap, chunk, mask, dig)
+    # canary bytes around every destination buffer
+    arenas = [np.full(x.size + 64, 0xEE, dtype=np.uint8) for x in dst_content]
+    dst = []
+    for ar, x in zip(arenas, dst_content):
+        ar[32:32 + x.size] = x
+        dst.append(ar[32:32 + x.size])
+    assert oracle.restore(dst, staging, man) == 0
+    for ar, d, s in zip(arenas, dst, snap):
+        assert np.array_equal(d, s)
+        assert np.all(ar[:32] == 0xEE) and np.all(ar[32 + s.size:] == 0xEE)
+
+
+def test_restore_writes_only_listed_chunks():
+    rng = np.random.default_rng(9)
+    snap = rand_bufs(rng, [4096, 4096])
+    dig = oracle.fingerprint(snap, 1024)
+    mask = np.array([0, 1, 0, 0, 0, 0, 1, 0], dtype=np.uint8)
+    staging, man, _ = oracle.compact(snap, 1024, mask, dig)
+    dst = [np.zeros(4096, dtype=np.uint8), np.zeros(4096, dtype=np.uint8)]
+    assert oracle.restore(dst, staging, man) == 0
+    assert np.array_equal(dst[0][1024:2048], snap[0][1024:2048])
+    assert np.array_equal(dst[1][2048:3072], snap[1][2048:3072])
+    assert dst[0][:1024].sum() == 0 and dst[0][2048:].sum() == 0
+    assert dst[1][:2048].sum() == 0 and dst[1][3072:].sum() == 0
+
+
+def test_restore_rejects_entries_outside_destination():
+    rng = np.random.default_rng(10)
+    snap = rand_bufs(rng, [2048, 1000])
+    dig = oracle.fingerprint(snap, 1024)
+    mask = np.ones(dig.size, dtype=np.uint8)
+    staging, man, _ = oracle.compact(snap, 1024, mask, dig)
+    small = [np.zeros(2048, dtype=np.uint8), np.zeros(999, dtype=np.uint8)]
+    assert oracle.restore(small, staging, man) == -3          # third entry does not fit
+    assert np.array_equal(small[0], snap[0])                 # earlier entries applied
+    assert oracle.restore([np.zeros(2048, dtype=np.uint8)], staging, man) == -3
+    assert oracle.restore([x.copy() for x in snap], staging[:-16], man) == -3
+
+
+# ---- the five configurations, reduced to CPU size -------------------------
+
+@pytest.mark.parametrize("cfg,shrink", [(1, 1), (2, 6), (4, 16), (5, 16)])
+def test_replica_configs_dedup_exactly_shared_state(cfg, shrink):
+    """P and O chunks are clean, G and A chunks dirty (sec. 5.2.1); the staged
+    size is that of the per-replica part alone, whatever the replica count."""
+    w = wl.config(cfg, shrink)
+    rep0 = wl.numpy_replica(w, 0)
+    ref = oracle.fingerprint(rep0, w.chunk, 8)
+    assert ref.size == w.nchunks
+    staged = []
+    for r in range(1, w.nreplicas):
+        rep = wl.numpy_replica(w, r)
+        dig = oracle.fingerprint(rep, w.chunk, 8)
+        mask, cnt = oracle.diff(rep, w.chunk, dig, ref)
+        buf, off, length = wl.chunk_table(w)
+        expect = np.array([not w.bufs[b].shared for b in buf], dtype=np.uint8)
+        assert np.array_equal(mask, expect)
+        assert cnt["ndirty"] == w.distinct_chunks
+        staging, man, cnt2 = oracle.compact(rep, w.chunk, mask, dig)
+        assert cnt2["staged_bytes"] == staging.size == int(((length + 15) // 16 * 16)[mask != 0].sum())
+        staged.append(staging.size)
+        # delta restore into replica 0's buffers reproduces replica r exactly
+        dst = [x.copy() for x in rep0]
+        assert oracle.restore(dst, staging, man) == 0
+        assert all(np.array_equal(d, s) for d, s in zip(dst, rep))
+    assert len(set(staged)) == 1
+
+
+@pytest.mark.parametrize("fraction", [0.01, 0.10, 0.50])
+def test_fragmented_config_marks_exactly_the_rewritten_chunks(fraction):
+    w = wl.config(3, 250)          # 400 buffers
+    t0 = wl.numpy_replica(w, 0)
+    ref = oracle.fingerprint(t0, w.chunk, 8)
+    step = int(fraction * 100)
+    ids = wl.dirty_chunk_ids(w, fraction, step)
+    assert ids.size == round(fraction * w.nchunks)
+    t1 = [x.copy() for x in t0]
+    wl.numpy_rewrite_chunks(w, t1, ids, step)
+    dig = oracle.fingerprint(t1, w.chunk, 8)
+    mask, cnt = oracle.diff(t1, w.chunk, dig, ref)
+    assert np.array_equal(np.flatnonzero(mask), ids)
+    staging, man, _ = oracle.compact(t1, w.chunk, mask, dig)
+    dst = [x.copy() for x in t0]
+    assert oracle.restore(dst, staging, man) == 0
+    assert all(np.array_equal(d, s) for d, s in zip(dst, t1))
+    # all-zero buffers hash to the same per-length digests
+    zero_chunks = [k for k, b in enumerate(wl.chunk_table(w)[0]) if w.bufs[b].kind == "zero"
+                   and wl.chunk_table(w)[2][k] == w.chunk]
+    if zero_chunks:
+        assert len(set(ref[zero_chunks].tolist())) == 1
+        assert int(ref[zero_chunks[0]]) == 0xAC869B6F32D8BBDB
