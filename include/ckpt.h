@@ -1,0 +1,183 @@
+/*
+ * ckpt.h -- C ABI of the MI355X device-state snapshot library (libckpt.so).
+ *
+ * The path it implements is the checksum-deduplicated swap-out / swap-in of a
+ * training job's live device buffers described in the Singularity paper:
+ *   sec. 5.2.1  content checksums of every live buffer at a context switch;
+ *               a buffer whose checksum is already known is not swapped out;
+ *               with 4 ranks on a GPU only the first swaps out P and O;
+ *   sec. 4.6    the same checksum de-dup across workers before a checkpoint
+ *               upload, and across time (incremental checkpoints);
+ *   sec. 5.2.3  mutations between two points = difference of checksum state;
+ *   sec. 4.5    restore copies the tensors back to the addresses they had;
+ *   sec. 6      the checksum kernels are ordinary stream work, the comparison
+ *               used to be host work -- here it runs on the device too.
+ * The paper names no checksum function and works per buffer; this library
+ * fingerprints fixed-size chunks inside each buffer with XXH64, seed 0.
+ *
+ * Model
+ *   A plan describes a list of B live buffers (device pointer, size) and a
+ *   chunk size C.  Buffer i is cut into n_i = ceil(nbytes_i / C) chunks; the
+ *   last one may be short; an empty buffer has none.  Chunks are numbered
+ *   globally in list order: k = (sum of n_i' for i' < i) + j.  N = sum n_i.
+ *
+ * Conventions for every call
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; everything
+ *     else is host memory.  The library allocates device memory only inside
+ *     ckpt_plan_create (descriptor tables and a small scan scratch) and frees
+ *     it in ckpt_plan_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     The four data calls only enqueue kernels on it and return; outputs are
+ *     valid once the caller has synchronised the stream.  Calls on one stream
+ *     are ordered.  A plan must not be used by two streams at once (its scan
+ *     scratch is shared).
+ *   - Return value: 0 (CKPT_OK) or a negative ckpt_status.  Argument errors
+ *     are reported synchronously and nothing is enqueued.  Nothing is ever
+ *     written outside the ranges described below, also on capacity overflow.
+ *   - The current HIP device must be the one that owns the buffers.
+ */
+#ifndef CKPT_H_
+#define CKPT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ckpt_status {
+  CKPT_OK = 0,
+  CKPT_ERR_INVALID_ARG = -1, /* NULL where a pointer is required, size overflow */
+  CKPT_ERR_ALIGNMENT = -2,   /* a buffer / staging / digest / manifest pointer is misaligned */
+  CKPT_ERR_CHUNK = -3,       /* chunk size not a power of two in [256 B, 1 GiB] */
+  CKPT_ERR_GEOMETRY = -4,    /* reference digest count differs from the plan's N */
+  CKPT_ERR_CAPACITY = -5,    /* reserved for callers that turn counts.overflow into a status */
+  CKPT_ERR_DEVICE = -6,      /* a HIP call failed (see ckpt_last_device_error) */
+  CKPT_ERR_NOMEM = -7        /* host or device allocation failed in ckpt_plan_create */
+} ckpt_status;
+
+/* One live buffer.  ptr: device address, 16-byte aligned (unless nbytes == 0,
+ * then it is ignored).  Buffers may not overlap if the plan is used as the
+ * destination of ckpt_restore. */
+typedef struct ckpt_buf {
+  void *ptr;
+  uint64_t nbytes;
+} ckpt_buf_t;
+
+/* One staged chunk; 32 bytes, device-resident array written by ckpt_compact in
+ * ascending global chunk order. */
+typedef struct ckpt_entry {
+  uint32_t buf;       /* index of the chunk's buffer in the plan's list */
+  uint32_t len;       /* chunk length in bytes (C, or less for a last chunk) */
+  uint64_t buf_off;   /* offset of the chunk in its buffer (multiple of C) */
+  uint64_t stage_off; /* offset of the chunk in staging (multiple of 16) */
+  uint64_t digest;    /* XXH64 of the chunk */
+} ckpt_entry_t;
+
+typedef struct ckpt_counts {
+  uint64_t ndirty;       /* chunks with mask 1 */
+  uint64_t staged_bytes; /* sum over those chunks of len rounded up to 16 */
+  uint64_t overflow;     /* dirty chunks ckpt_compact could not stage (0 = complete) */
+} ckpt_counts_t;
+
+typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
+
+/* ---- plan --------------------------------------------------------------- */
+
+/* Builds the chunk geometry of a buffer list (the paper's device proxy knows
+ * every live buffer because it owns the allocator, sec. 3.2.1 / 5.2.1) and
+ * uploads the descriptor tables to the current device.  Synchronous.
+ *   bufs        host array of nbufs descriptors (may be NULL when nbufs == 0)
+ *   chunk_bytes C: power of two, 256 <= C <= 2^30
+ *   out         receives the plan; destroy it with ckpt_plan_destroy
+ * Errors: INVALID_ARG, CHUNK, ALIGNMENT (ptr not 16-byte aligned),
+ * NOMEM, DEVICE. */
+int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,
+                     ckpt_plan_t **out);
+
+/* Frees the plan's host and device memory.  The caller must have synchronised
+ * every stream that used it.  NULL is accepted. */
+int ckpt_plan_destroy(ckpt_plan_t *plan);
+
+uint64_t ckpt_plan_nchunks(const ckpt_plan_t *plan);     /* N */
+uint64_t ckpt_plan_nbytes(const ckpt_plan_t *plan);      /* S = sum nbytes_i */
+uint64_t ckpt_plan_nbufs(const ckpt_plan_t *plan);       /* B */
+uint64_t ckpt_plan_chunk_bytes(const ckpt_plan_t *plan); /* C */
+
+/* ---- the four data calls ------------------------------------------------- */
+
+/* Content checksum of every chunk (sec. 5.2.1, sec. 6):
+ *   d_digests[k] = XXH64(bytes of chunk k, length len_k, seed 0), k in [0, N).
+ * A short last chunk is hashed at its true length.  Reads every buffer byte
+ * once and nothing else; writes N native-endian uint64.
+ *   d_digests   device array of N uint64, 8-byte aligned
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_fingerprint(const ckpt_plan_t *plan, uint64_t *d_digests, void *stream);
+
+/* Positional comparison with a reference replica's or an earlier snapshot's
+ * checksums (sec. 5.2.1 "same content checksum"; sec. 4.6; sec. 5.2.3):
+ *   d_mask[k] = 1 if d_ref == NULL or d_digests[k] != d_ref[k], else 0.
+ *   d_counts->ndirty = number of ones, ->staged_bytes = staging size
+ *   ckpt_compact will need for them, ->overflow = 0.
+ *   d_ref   device array of n_ref uint64, or NULL (no reference: the first
+ *           rank really swaps everything out); n_ref must equal N otherwise
+ *   d_mask  device array of N bytes
+ *   d_counts device ckpt_counts_t, 8-byte aligned
+ * Errors: INVALID_ARG, GEOMETRY (n_ref != N), ALIGNMENT, DEVICE. */
+int ckpt_diff(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t *d_ref,
+              uint64_t n_ref, uint8_t *d_mask, ckpt_counts_t *d_counts, void *stream);
+
+/* Swap-out of what is not de-duplicated (sec. 5.2.1), as a gather into one
+ * contiguous staging buffer: walking k upwards, each chunk with d_mask[k] != 0
+ * gets the next manifest entry e and the next pad16(len_k) bytes of staging
+ * (its bytes, then zeros up to a multiple of 16), so
+ *   stage_off[0] = 0, stage_off[e+1] = stage_off[e] + pad16(len[e]).
+ * d_counts receives ndirty, staged_bytes (both the full need, whatever the
+ * capacities) and overflow.
+ *   d_staging    device buffer of staging_cap bytes, 16-byte aligned, not
+ *                overlapping any plan buffer
+ *   d_manifest   device array of manifest_cap entries, 8-byte aligned
+ * Capacity: entry e is written only if e < manifest_cap; its bytes are written
+ * only if also stage_off + pad16(len) <= staging_cap.  Every dirty chunk that
+ * is not fully staged adds 1 to d_counts->overflow; nothing is written past
+ * either capacity.  (The prefix that fits is complete and usable.)
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
+                 void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                 uint64_t manifest_cap, ckpt_counts_t *d_counts, void *stream);
+
+/* Swap-in / restore (sec. 4.5, sec. 5.2.1): for each of the first nentries
+ * manifest entries, copy len bytes from d_staging + stage_off to buffer
+ * entry.buf of dst_plan at offset buf_off.  Chunks without an entry are not
+ * touched (the caller guarantees they already hold the reference's bytes).
+ * An entry that names a buffer outside dst_plan, a range outside that buffer,
+ * or a range outside [0, staging_bytes) is skipped, never partially applied.
+ *   d_rejected  optional device uint64 that receives the number of skipped
+ *               entries (0 = all applied); may be NULL
+ * dst_plan may be the snapshot's own plan or another one with compatible
+ * geometry (e.g. the buffers of a different replica).
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,
+                 const ckpt_entry_t *d_manifest, uint64_t nentries, uint64_t *d_rejected,
+                 void *stream);
+
+/* ---- helpers -------------------------------------------------------------- */
+
+/* Plain streaming kernels used to calibrate HBM counters and the achievable
+ * bandwidth next to the path's own kernels: copy nbytes (multiple of 16,
+ * 16-byte aligned pointers) from d_src to d_dst; or read nbytes and write one
+ * 8-byte XOR checksum per workgroup into d_sink (at least 16 KiB).
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream);
+int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *stream);
+
+const char *ckpt_strerror(int status);
+/* hipError_t of the last failed HIP call on this thread (0 if none). */
+int ckpt_last_device_error(void);
+/* 1000 * major + minor */
+int ckpt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKPT_H_ */

@@ -71,8 +71,8 @@ def _load():
         lib.ora_diff.argtypes = [vp, u64, u64, vp, vp, vp, vp]
         lib.ora_compact.restype = None
         lib.ora_compact.argtypes = [vp, u64, u64, vp, vp, vp, u64, vp, u64, vp]
-        lib.ora_restore.restype = ctypes.c_int64
-        lib.ora_restore.argtypes = [vp, u64, vp, u64, vp, u64]
+        lib.ora_restore.restype = ctypes.c_uint64
+        lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         _lib = lib
     return _lib
 
@@ -162,10 +162,10 @@ def compact(bufs: Sequence[np.ndarray], chunk: int, mask: np.ndarray, dig: np.nd
                                "overflow": c.overflow}
 
 
-def restore(dst: List[np.ndarray], staging: np.ndarray, manifest: np.ndarray,
+def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np.ndarray,
             staging_bytes: Optional[int] = None) -> int:
-    """Scatter staging back into ``dst`` (modified in place).  Returns 0 or
-    -(1 + index of the first entry that does not fit)."""
+    """Scatter staging back into ``dst`` (modified in place).  Returns the
+    number of entries skipped because they do not fit ``dst`` or staging."""
     staging = np.ascontiguousarray(staging, dtype=np.uint8)
     manifest = np.ascontiguousarray(manifest, dtype=ENTRY_DTYPE)
     if staging_bytes is None:
@@ -173,5 +173,5 @@ def restore(dst: List[np.ndarray], staging: np.ndarray, manifest: np.ndarray,
     for b in dst:
         if not b.flags["WRITEABLE"]:
             raise TypeError("destination buffers must be writable")
-    return int(_load().ora_restore(_desc(dst), len(dst), _p(staging), staging_bytes,
+    return int(_load().ora_restore(_desc(dst), len(dst), chunk, _p(staging), staging_bytes,
                                    _p(manifest), manifest.size))

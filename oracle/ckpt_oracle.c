@@ -326,18 +326,26 @@ void ora_compact(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, const ui
 /* ---------------------------------------------------------------- restore */
 /* For each manifest entry, in order, copy len bytes from staging back to the
  * place in the destination buffer list the entry names (sec. 4.5: tensors go
- * back to the addresses they had).  Nothing else is written.  Returns 0, or
- * -(1 + index of the first entry that does not fit the destination geometry
- * or the staging size); entries before it have been applied. */
-int64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, const void *staging,
-                    uint64_t staging_bytes, const ora_entry_t *manifest, uint64_t nentries) {
+ * back to the addresses they had).  Nothing else is written.  An entry that
+ * compact could not have produced for this destination -- a buffer outside the
+ * list, a range outside its buffer or outside staging, an offset that is not a
+ * multiple of 16, a length above the chunk size -- is skipped; the return value is the number of entries
+ * skipped (0 = everything applied). */
+uint64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const void *staging,
+                     uint64_t staging_bytes, const ora_entry_t *manifest,
+                     uint64_t nentries) {
   const uint8_t *in = (const uint8_t *)staging;
+  uint64_t rejected = 0;
   for (uint64_t e = 0; e < nentries; ++e) {
     const ora_entry_t *m = &manifest[e];
-    if (m->buf >= nbufs) return -(int64_t)(1 + e);
-    if (m->buf_off + m->len > dst[m->buf].nbytes) return -(int64_t)(1 + e);
-    if (m->stage_off + m->len > staging_bytes) return -(int64_t)(1 + e);
+    int ok = m->buf < nbufs && m->buf_off % 16 == 0 && m->stage_off % 16 == 0 && m->len <= chunk;
+    if (ok) ok = m->buf_off <= dst[m->buf].nbytes && m->len <= dst[m->buf].nbytes - m->buf_off;
+    if (ok) ok = m->stage_off <= staging_bytes && m->len <= staging_bytes - m->stage_off;
+    if (!ok) {
+      rejected += 1;
+      continue;
+    }
     memcpy((uint8_t *)dst[m->buf].ptr + m->buf_off, in + m->stage_off, m->len);
   }
-  return 0;
+  return rejected;
 }

@@ -1,0 +1,205 @@
+"""ctypes binding of libckpt.so -- argument marshalling only.
+
+Same names as the C ABI (include/ckpt.h): ``fingerprint``, ``diff``,
+``compact``, ``restore`` over a ``Plan`` built from a buffer-descriptor list.
+PyTorch supplies device memory and the HIP stream; every step of the path runs
+in the library's kernels.  There is no CPU fallback: if the library is missing
+the import of this module's functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckpt.so")
+
+ENTRY_DTYPE = np.dtype(
+    [("buf", "<u4"), ("len", "<u4"), ("buf_off", "<u8"), ("stage_off", "<u8"), ("digest", "<u8")]
+)
+ENTRY_BYTES = 32
+COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
+
+EXPORTS = (
+    "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
+    "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
+    "ckpt_restore", "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
+    "ckpt_version",
+)
+
+
+class CkptError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().ckpt_strerror(status).decode()
+        if status == -6:
+            msg += " (hipError %d)" % _lib().ckpt_last_device_error()
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+class _Buf(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
+
+
+_handle = None
+
+
+def _lib():
+    global _handle
+    if _handle is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is not built; run `python -m paper_2202_07848_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        u64, vp, ci = ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int
+        lib.ckpt_plan_create.restype = ci
+        lib.ckpt_plan_create.argtypes = [vp, u64, u64, ctypes.POINTER(vp)]
+        lib.ckpt_plan_destroy.restype = ci
+        lib.ckpt_plan_destroy.argtypes = [vp]
+        for name in ("ckpt_plan_nchunks", "ckpt_plan_nbytes", "ckpt_plan_nbufs",
+                     "ckpt_plan_chunk_bytes"):
+            getattr(lib, name).restype = u64
+            getattr(lib, name).argtypes = [vp]
+        lib.ckpt_fingerprint.restype = ci
+        lib.ckpt_fingerprint.argtypes = [vp, vp, vp]
+        lib.ckpt_diff.restype = ci
+        lib.ckpt_diff.argtypes = [vp, vp, vp, u64, vp, vp, vp]
+        lib.ckpt_compact.restype = ci
+        lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_restore.restype = ci
+        lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_bw_copy.restype = ci
+        lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
+        lib.ckpt_bw_read.restype = ci
+        lib.ckpt_bw_read.argtypes = [vp, u64, vp, vp]
+        lib.ckpt_strerror.restype = ctypes.c_char_p
+        lib.ckpt_strerror.argtypes = [ci]
+        lib.ckpt_last_device_error.restype = ci
+        lib.ckpt_version.restype = ci
+        _handle = lib
+    return _handle
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise CkptError(status, where)
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch stream (None = torch's current stream)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+class Plan:
+    """Chunk geometry of a list of live device buffers (``ckpt_plan_create``).
+
+    ``buffers``: sequence of (device pointer, nbytes) pairs or of torch tensors
+    (their storage bytes are the buffer).  Tensors are kept alive by the plan.
+    """
+
+    def __init__(self, buffers: Sequence, chunk_bytes: int):
+        self._keep = []
+        descs = (_Buf * max(1, len(buffers)))()
+        for i, b in enumerate(buffers):
+            if isinstance(b, tuple):
+                ptr, nbytes = b
+            else:
+                if not b.is_contiguous():
+                    raise ValueError("buffer tensors must be contiguous")
+                ptr, nbytes = b.data_ptr(), b.numel() * b.element_size()
+                self._keep.append(b)
+            descs[i].ptr = ptr if nbytes else None
+            descs[i].nbytes = nbytes
+        handle = ctypes.c_void_p()
+        _check(_lib().ckpt_plan_create(descs, len(buffers), chunk_bytes, ctypes.byref(handle)),
+               "ckpt_plan_create")
+        self._h = handle
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            _check(_lib().ckpt_plan_destroy(self._h), "ckpt_plan_destroy")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def nchunks(self) -> int:
+        return int(_lib().ckpt_plan_nchunks(self._h))
+
+    @property
+    def nbytes(self) -> int:
+        return int(_lib().ckpt_plan_nbytes(self._h))
+
+    @property
+    def nbufs(self) -> int:
+        return int(_lib().ckpt_plan_nbufs(self._h))
+
+    @property
+    def chunk_bytes(self) -> int:
+        return int(_lib().ckpt_plan_chunk_bytes(self._h))
+
+
+def fingerprint(plan: Plan, digests, stream=None) -> None:
+    """``ckpt_fingerprint``: digests (int64/uint64 CUDA tensor, N elements) <- XXH64 per chunk."""
+    _check(_lib().ckpt_fingerprint(plan._h, _ptr(digests), _stream(stream)), "ckpt_fingerprint")
+
+
+def diff(plan: Plan, digests, ref, mask, counts, stream=None, n_ref: Optional[int] = None) -> None:
+    """``ckpt_diff``: mask (uint8, N) and counts (3 x int64) from digests vs ref (or None)."""
+    if n_ref is None:
+        n_ref = 0 if ref is None else ref.numel()
+    _check(_lib().ckpt_diff(plan._h, _ptr(digests), _ptr(ref), n_ref, _ptr(mask), _ptr(counts),
+                            _stream(stream)), "ckpt_diff")
+
+
+def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,
+            staging_cap: Optional[int] = None, manifest_cap: Optional[int] = None) -> None:
+    """``ckpt_compact``: staging (uint8) and manifest (uint8 view of 32-byte entries)."""
+    if staging_cap is None:
+        staging_cap = 0 if staging is None else staging.numel() * staging.element_size()
+    if manifest_cap is None:
+        manifest_cap = 0 if manifest is None else \
+            manifest.numel() * manifest.element_size() // ENTRY_BYTES
+    _check(_lib().ckpt_compact(plan._h, _ptr(mask), _ptr(digests), _ptr(staging), staging_cap,
+                               _ptr(manifest), manifest_cap, _ptr(counts), _stream(stream)),
+           "ckpt_compact")
+
+
+def restore(dst_plan: Plan, staging, staging_bytes: int, manifest, nentries: int,
+            rejected=None, stream=None) -> None:
+    """``ckpt_restore``: scatter the first nentries manifest entries into dst_plan's buffers."""
+    _check(_lib().ckpt_restore(dst_plan._h, _ptr(staging), staging_bytes, _ptr(manifest), nentries,
+                               _ptr(rejected), _stream(stream)), "ckpt_restore")
+
+
+def bw_copy(dst, src, nbytes: int, stream=None) -> None:
+    _check(_lib().ckpt_bw_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "ckpt_bw_copy")
+
+
+def bw_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(_lib().ckpt_bw_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "ckpt_bw_read")
+
+
+def version() -> int:
+    return int(_lib().ckpt_version())
+
+
+def manifest_to_numpy(manifest, nentries: int) -> np.ndarray:
+    """Host copy of the first nentries manifest entries as a structured array."""
+    raw = manifest.view(-1)[: nentries * ENTRY_BYTES].cpu().numpy()
+    return raw.view(ENTRY_DTYPE)

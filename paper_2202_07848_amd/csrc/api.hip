@@ -1,0 +1,262 @@
+// C ABI of libckpt.so: argument checks, the plan object, kernel launches.
+// Semantics and citations are in include/ckpt.h.
+#include <new>
+#include <vector>
+
+#include "ckpt_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int device_error(hipError_t e) {
+  g_last_hip_error = (int)e;
+  (void)hipGetLastError();   // clear the sticky launch error, it has been recorded
+  return CKPT_ERR_DEVICE;
+}
+
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+}  // namespace
+
+struct ckpt_plan {
+  ckpt::PlanDev dev{};
+  uint64_t nbytes = 0;
+  uint64_t chunk = 0;
+  void *d_tables = nullptr;        // one allocation holding every table
+  uint64_t *d_blocksums = nullptr; // scan scratch: 2 x uint64 per SCAN_BLOCK chunks (+2)
+  int device = -1;
+};
+
+extern "C" {
+
+int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,
+                     ckpt_plan_t **out) {
+  if (out == nullptr) return CKPT_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (bufs == nullptr && nbufs != 0) return CKPT_ERR_INVALID_ARG;
+  if (nbufs >= 0xFFFFFFFFull) return CKPT_ERR_INVALID_ARG;
+  if (chunk_bytes < 256 || chunk_bytes > (1ull << 30) || (chunk_bytes & (chunk_bytes - 1)) != 0)
+    return CKPT_ERR_CHUNK;
+  uint32_t chunk_log2 = 0;
+  while ((1ull << chunk_log2) < chunk_bytes) ++chunk_log2;
+
+  std::vector<uint64_t> dense_ptr, dense_nbytes, dense_base, list_ptr, list_nbytes;
+  std::vector<uint32_t> dense_orig, group_first;
+  uint64_t nchunks = 0, total = 0;
+  try {
+    list_ptr.reserve(nbufs);
+    list_nbytes.reserve(nbufs);
+    for (uint64_t i = 0; i < nbufs; ++i) {
+      const uint64_t n = bufs[i].nbytes;
+      if (n != 0) {
+        if (bufs[i].ptr == nullptr) return CKPT_ERR_INVALID_ARG;
+        if (!aligned(bufs[i].ptr, 16)) return CKPT_ERR_ALIGNMENT;
+        if (total + n < total) return CKPT_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(bufs[i].ptr) + n < n) return CKPT_ERR_INVALID_ARG;
+      }
+      list_ptr.push_back(reinterpret_cast<uint64_t>(n ? bufs[i].ptr : nullptr));
+      list_nbytes.push_back(n);
+      if (n == 0) continue;
+      dense_ptr.push_back(reinterpret_cast<uint64_t>(bufs[i].ptr));
+      dense_nbytes.push_back(n);
+      dense_base.push_back(nchunks);
+      dense_orig.push_back((uint32_t)i);
+      nchunks += (n + chunk_bytes - 1) >> chunk_log2;
+      total += n;
+    }
+    dense_base.push_back(nchunks);
+    const uint64_t ngroups = (nchunks + ckpt::GROUP - 1) / ckpt::GROUP;
+    if (ngroups > 0x7FFFFFFFull) return CKPT_ERR_INVALID_ARG;
+    group_first.resize(ngroups);
+    uint32_t row = 0;
+    for (uint64_t g = 0; g < ngroups; ++g) {
+      const uint64_t k = g * ckpt::GROUP;
+      while (k >= dense_base[row + 1]) ++row;
+      group_first[g] = row;
+    }
+  } catch (const std::bad_alloc &) {
+    return CKPT_ERR_NOMEM;
+  }
+
+  ckpt_plan *plan = new (std::nothrow) ckpt_plan();
+  if (plan == nullptr) return CKPT_ERR_NOMEM;
+  plan->nbytes = total;
+  plan->chunk = chunk_bytes;
+  if (hipGetDevice(&plan->device) != hipSuccess) {
+    delete plan;
+    return device_error(hipGetLastError());
+  }
+
+  // one device allocation, every table 16-byte aligned inside it
+  const size_t nb = dense_ptr.size();
+  auto up16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+  const size_t o_dptr = 0;
+  const size_t o_dnb = o_dptr + up16(8 * nb);
+  const size_t o_dbase = o_dnb + up16(8 * nb);
+  const size_t o_dorig = o_dbase + up16(8 * (nb + 1));
+  const size_t o_gfirst = o_dorig + up16(4 * nb);
+  const size_t o_lptr = o_gfirst + up16(4 * group_first.size());
+  const size_t o_lnb = o_lptr + up16(8 * (size_t)nbufs);
+  const size_t o_spare = (o_lnb + up16(8 * (size_t)nbufs) + 255) & ~(size_t)255;
+  const size_t bytes = o_spare + 256;
+
+  hipError_t e = hipMalloc(&plan->d_tables, bytes);
+  if (e != hipSuccess) {
+    delete plan;
+    (void)hipGetLastError();
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? CKPT_ERR_NOMEM : CKPT_ERR_DEVICE;
+  }
+  const uint64_t nscan = (nchunks + ckpt::SCAN_BLOCK - 1) / ckpt::SCAN_BLOCK;
+  e = hipMalloc(reinterpret_cast<void **>(&plan->d_blocksums), 16 * (nscan + 1));
+  if (e != hipSuccess) {
+    (void)hipFree(plan->d_tables);
+    delete plan;
+    (void)hipGetLastError();
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? CKPT_ERR_NOMEM : CKPT_ERR_DEVICE;
+  }
+
+  char *base = static_cast<char *>(plan->d_tables);
+  auto upload = [&](size_t off, const void *src, size_t n) -> hipError_t {
+    if (n == 0) return hipSuccess;
+    return hipMemcpy(base + off, src, n, hipMemcpyHostToDevice);
+  };
+  e = upload(o_dptr, dense_ptr.data(), 8 * nb);
+  if (e == hipSuccess) e = upload(o_dnb, dense_nbytes.data(), 8 * nb);
+  if (e == hipSuccess) e = upload(o_dbase, dense_base.data(), 8 * (nb + 1));
+  if (e == hipSuccess) e = upload(o_dorig, dense_orig.data(), 4 * nb);
+  if (e == hipSuccess) e = upload(o_gfirst, group_first.data(), 4 * group_first.size());
+  if (e == hipSuccess) e = upload(o_lptr, list_ptr.data(), 8 * (size_t)nbufs);
+  if (e == hipSuccess) e = upload(o_lnb, list_nbytes.data(), 8 * (size_t)nbufs);
+  if (e == hipSuccess) e = hipMemset(base + o_spare, 0, 256);
+  if (e != hipSuccess) {
+    (void)hipFree(plan->d_tables);
+    (void)hipFree(plan->d_blocksums);
+    delete plan;
+    return device_error(e);
+  }
+
+  ckpt::PlanDev &d = plan->dev;
+  d.dense_ptr = reinterpret_cast<const uint64_t *>(base + o_dptr);
+  d.dense_nbytes = reinterpret_cast<const uint64_t *>(base + o_dnb);
+  d.dense_base = reinterpret_cast<const uint64_t *>(base + o_dbase);
+  d.dense_orig = reinterpret_cast<const uint32_t *>(base + o_dorig);
+  d.group_first = reinterpret_cast<const uint32_t *>(base + o_gfirst);
+  d.list_ptr = reinterpret_cast<const uint64_t *>(base + o_lptr);
+  d.list_nbytes = reinterpret_cast<const uint64_t *>(base + o_lnb);
+  d.spare = reinterpret_cast<const uint8_t *>(base + o_spare);
+  d.nchunks = nchunks;
+  d.nbufs = nbufs;
+  d.nb = (uint32_t)nb;
+  d.chunk_log2 = chunk_log2;
+  *out = plan;
+  return CKPT_OK;
+}
+
+int ckpt_plan_destroy(ckpt_plan_t *plan) {
+  if (plan == nullptr) return CKPT_OK;
+  hipError_t e1 = hipFree(plan->d_tables);
+  hipError_t e2 = hipFree(plan->d_blocksums);
+  delete plan;
+  if (e1 != hipSuccess) return device_error(e1);
+  if (e2 != hipSuccess) return device_error(e2);
+  return CKPT_OK;
+}
+
+uint64_t ckpt_plan_nchunks(const ckpt_plan_t *plan) { return plan ? plan->dev.nchunks : 0; }
+uint64_t ckpt_plan_nbytes(const ckpt_plan_t *plan) { return plan ? plan->nbytes : 0; }
+uint64_t ckpt_plan_nbufs(const ckpt_plan_t *plan) { return plan ? plan->dev.nbufs : 0; }
+uint64_t ckpt_plan_chunk_bytes(const ckpt_plan_t *plan) { return plan ? plan->chunk : 0; }
+
+int ckpt_fingerprint(const ckpt_plan_t *plan, uint64_t *d_digests, void *stream) {
+  if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nchunks == 0) return CKPT_OK;
+  if (d_digests == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_digests, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_fingerprint(plan->dev, d_digests, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_diff(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t *d_ref,
+              uint64_t n_ref, uint8_t *d_mask, ckpt_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (d_ref != nullptr && n_ref != n) return CKPT_ERR_GEOMETRY;
+  if (n != 0 && (d_digests == nullptr || d_mask == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_digests, 8) || !aligned(d_ref, 8) || !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_diff(plan->dev, d_digests, d_ref, d_mask, plan->d_blocksums, d_counts,
+                                   static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
+                 void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                 uint64_t manifest_cap, ckpt_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && (d_mask == nullptr || d_digests == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (staging_cap != 0 && d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_staging, 16) || !aligned(d_manifest, 8) || !aligned(d_digests, 8) ||
+      !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = ckpt::launch_compact_scan(plan->dev, d_mask, d_digests, staging_cap, d_manifest,
+                                           manifest_cap, plan->d_blocksums, d_counts, s);
+  if (e == hipSuccess)
+    e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, s);
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,
+                 const ckpt_entry_t *d_manifest, uint64_t nentries, uint64_t *d_rejected,
+                 void *stream) {
+  if (dst_plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (nentries != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (staging_bytes != 0 && d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (nentries > (1ull << 40)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_staging, 16) || !aligned(d_manifest, 8) || !aligned(d_rejected, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_scatter(dst_plan->dev, d_manifest, nentries, d_staging, staging_bytes,
+                                      d_rejected, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream) {
+  if (nbytes == 0) return CKPT_OK;
+  if (d_dst == nullptr || d_src == nullptr || (nbytes & 15) != 0) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_dst, 16) || !aligned(d_src, 16)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_bw_copy(d_dst, d_src, nbytes, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *stream) {
+  if (d_sink == nullptr || (nbytes != 0 && d_src == nullptr) || (nbytes & 15) != 0)
+    return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_src, 16) || !aligned(d_sink, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_bw_read(d_src, nbytes, d_sink, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+const char *ckpt_strerror(int status) {
+  switch (status) {
+    case CKPT_OK: return "ok";
+    case CKPT_ERR_INVALID_ARG: return "invalid argument";
+    case CKPT_ERR_ALIGNMENT: return "pointer not aligned as required";
+    case CKPT_ERR_CHUNK: return "chunk size must be a power of two in [256, 2^30]";
+    case CKPT_ERR_GEOMETRY: return "reference digests have a different chunk geometry";
+    case CKPT_ERR_CAPACITY: return "staging or manifest capacity exceeded";
+    case CKPT_ERR_DEVICE: return "HIP call failed";
+    case CKPT_ERR_NOMEM: return "out of memory";
+    default: return "unknown status";
+  }
+}
+
+int ckpt_last_device_error(void) { return g_last_hip_error; }
+
+int ckpt_version(void) { return 1000 * 0 + 1; }
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the HIP translation units of libckpt.so.
+// Nothing here is part of the ABI (that is include/ckpt.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ckpt.h"
+
+namespace ckpt {
+
+// Chunks handled by one wavefront of the fingerprint kernel: 16 chunks x 4
+// lanes, one XXH64 accumulator per lane.  The plan's group table has one entry
+// per GROUP consecutive chunk ids.
+constexpr int GROUP = 16;
+constexpr int GROUP_LOG2 = 4;
+
+// Chunk geometry on the device.  The "dense" arrays skip empty buffers so that
+// every table row owns at least one chunk; `orig` maps a row back to the
+// caller's buffer index.  The "list" arrays are indexed by the caller's buffer
+// index (manifest entries carry that index).
+struct PlanDev {
+  const uint64_t *dense_ptr;     // [nb]   device address of the buffer
+  const uint64_t *dense_nbytes;  // [nb]
+  const uint64_t *dense_base;    // [nb+1] global id of the buffer's first chunk; [nb] = N
+  const uint32_t *dense_orig;    // [nb]   index in the caller's list
+  const uint32_t *group_first;   // [ceil(N/GROUP)] dense row that holds chunk GROUP*g
+  const uint64_t *list_ptr;      // [nbufs]
+  const uint64_t *list_nbytes;   // [nbufs]
+  const uint8_t *spare;          // 256 readable bytes (zero), 256-byte aligned
+  uint64_t nchunks;              // N
+  uint64_t nbufs;                // B (caller's list length)
+  uint32_t nb;                   // dense rows
+  uint32_t chunk_log2;           // log2(C)
+};
+
+struct ChunkRef {
+  uint32_t row;   // dense row
+  uint32_t len;   // chunk length in bytes
+  uint64_t off;   // offset inside the buffer
+};
+
+// Buffer row, offset and length of global chunk k (k < N).  The group table
+// gives the row of the group's first chunk; at most GROUP-1 rows follow before
+// the one that owns k, because every dense row owns at least one chunk.
+__device__ __forceinline__ ChunkRef locate_chunk(const PlanDev &p, uint64_t k) {
+  uint32_t row = p.group_first[k >> GROUP_LOG2];
+  while (k >= p.dense_base[row + 1]) ++row;   // ends: dense_base[nb] = N > k
+  ChunkRef r;
+  r.row = row;
+  r.off = (k - p.dense_base[row]) << p.chunk_log2;
+  uint64_t rem = p.dense_nbytes[row] - r.off;
+  uint64_t c = 1ull << p.chunk_log2;
+  r.len = (uint32_t)(rem < c ? rem : c);
+  return r;
+}
+
+__device__ __forceinline__ uint64_t pad16(uint64_t x) { return (x + 15) & ~15ull; }
+
+// Scan geometry: one workgroup of SCAN_THREADS threads covers SCAN_BLOCK
+// consecutive chunk ids, SCAN_PER_THREAD each.
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_PER_THREAD = 4;
+constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
+
+// Copy geometry: one wavefront moves one piece of one staged chunk per
+// iteration; a piece is min(C, COPY_PIECE) bytes.
+constexpr int COPY_PIECE_LOG2 = 14;
+constexpr int COPY_THREADS = 256;
+constexpr int COPY_MAX_GROUPS = 4096;
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s);
+hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
+                       uint8_t *d_mask, uint64_t *d_blocksums, ckpt_counts_t *d_counts,
+                       hipStream_t s);
+hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
+                               uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                               uint64_t manifest_cap, uint64_t *d_blocksums,
+                               ckpt_counts_t *d_counts, hipStream_t s);
+hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                         const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
+                         hipStream_t s);
+hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
+                          const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
+                          hipStream_t s);
+hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
+hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
+
+}  // namespace ckpt

@@ -1,0 +1,220 @@
+// Data movement of the snapshot path: gather of the marked chunks into the
+// contiguous staging buffer (the swap-out of what was not de-duplicated,
+// Singularity paper sec. 5.2.1) and the inverse scatter (swap-in / restore to
+// the original addresses, sec. 4.5).  Also two plain streaming kernels used to
+// calibrate bandwidth and HBM counters.
+//
+// Work item = one piece (min(C, 16 KiB)) of one manifest entry, handled by one
+// wavefront: 64 lanes x 16 B = 1 KiB per instruction, four loads in flight per
+// lane.  Items are dealt to wavefronts round-robin (item = wave id + i * number
+// of waves), so neighbouring waves stream neighbouring 16 KiB pieces of source
+// and staging.  The gather does not know the entry count on the host (it sits
+// in device memory right after the scan), so the grid is fixed and every wave
+// loops until its item index passes the device-side count: every wave reaches
+// the exit, nothing waits on another wave.
+#include "ckpt_internal.h"
+
+namespace ckpt {
+
+namespace {
+
+constexpr int UNROLL = 4;
+
+__device__ __forceinline__ uint4 load_partial16(const uint8_t *src, uint32_t valid) {
+  // bytes [0, valid) from src, zeros above; valid in 1..15
+  uint32_t w[4] = {0, 0, 0, 0};
+  for (uint32_t b = 0; b < valid; ++b) w[b >> 2] |= (uint32_t)src[b] << (8 * (b & 3));
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ void store_partial16(uint8_t *dst, uint4 v, uint32_t valid) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  for (uint32_t b = 0; b < valid; ++b) dst[b] = (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+}
+
+// GATHER: buffers -> staging (zero padded to 16).  !GATHER: staging -> buffers
+// (exactly len bytes).  `count_dev`, when not null, supplies the entry count
+// (its ndirty, clipped to entry_cap); otherwise entry_cap is the count.
+template <bool GATHER>
+__global__ __launch_bounds__(COPY_THREADS) void k_move(PlanDev p,
+                                                       const ckpt_entry_t *__restrict__ manifest,
+                                                       uint64_t entry_cap,
+                                                       const ckpt_counts_t *__restrict__ count_dev,
+                                                       uint8_t *__restrict__ staging,
+                                                       uint64_t staging_limit,
+                                                       unsigned long long *__restrict__ rejected) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;     // pieces per chunk
+
+  uint64_t nentries = entry_cap;
+  if (count_dev != nullptr) {
+    const uint64_t n = count_dev->ndirty;
+    nentries = n < entry_cap ? n : entry_cap;
+  }
+  const uint64_t nitems = nentries << ppc_log2;
+
+  for (uint64_t item = (uint64_t)blockIdx.x * (COPY_THREADS / 64) + wave_in_group; item < nitems;
+       item += nwaves) {
+    const uint64_t e = item >> ppc_log2;
+    const uint32_t piece = (uint32_t)(item & ((1ull << ppc_log2) - 1));
+    const ckpt_entry_t ent = manifest[e];
+    const uint64_t padded = pad16(ent.len);
+
+    // validity (always true for a manifest this library wrote with enough capacity);
+    // written so that no sum can wrap
+    bool ok = ent.buf < p.nbufs && ((ent.buf_off | ent.stage_off) & 15) == 0 &&
+              ent.len <= (1ull << p.chunk_log2);
+    if (ok) {
+      const uint64_t nb = p.list_nbytes[ent.buf];
+      ok = ent.buf_off <= nb && ent.len <= nb - ent.buf_off;
+    }
+    const uint64_t need = GATHER ? padded : (uint64_t)ent.len;
+    ok = ok && ent.stage_off <= staging_limit && need <= staging_limit - ent.stage_off;
+    if (!ok) {
+      if (!GATHER && rejected != nullptr && piece == 0 && lane == 0) atomicAdd(rejected, 1ull);
+      continue;
+    }
+
+    uint8_t *buf = reinterpret_cast<uint8_t *>(p.list_ptr[ent.buf]) + ent.buf_off;
+    uint8_t *stg = staging + ent.stage_off;
+    const uint8_t *src = GATHER ? buf : stg;
+    uint8_t *dst = GATHER ? stg : buf;
+
+    const uint32_t lo = piece << piece_log2;
+    uint32_t hi = lo + (1u << piece_log2);
+    if (hi > padded) hi = (uint32_t)padded;
+    const uint32_t len = ent.len;
+
+    for (uint32_t base = lo + lane * 16; base < hi; base += 64 * 16 * UNROLL) {
+      uint4 v[UNROLL];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t o = base + u * 64 * 16;
+        if (o + 16 <= len)
+          v[u] = *reinterpret_cast<const uint4 *>(src + o);
+        else if (o < len)
+          v[u] = load_partial16(src + o, len - o);
+      }
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t o = base + u * 64 * 16;
+        if (o + 16 <= len) {
+          *reinterpret_cast<uint4 *>(dst + o) = v[u];
+        } else if (o < len) {
+          if (GATHER)
+            *reinterpret_cast<uint4 *>(dst + o) = v[u];      // zero padded by load_partial16
+          else
+            store_partial16(dst + o, v[u], len - o);
+        }
+      }
+    }
+  }
+}
+
+__global__ void k_zero_u64(unsigned long long *p) { *p = 0; }
+
+__global__ __launch_bounds__(256) void k_bw_copy(uint4 *__restrict__ dst,
+                                                 const uint4 *__restrict__ src, uint64_t n16) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256 * UNROLL;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 * UNROLL + threadIdx.x; i < n16; i += stride) {
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (i + u * 256 < n16) v[u] = src[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (i + u * 256 < n16) dst[i + u * 256] = v[u];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_bw_read(const uint4 *__restrict__ src, uint64_t n16,
+                                                 uint64_t *__restrict__ sink) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256 * UNROLL;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 * UNROLL + threadIdx.x; i < n16; i += stride) {
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (i + u * 256 < n16) v[u] = src[i + u * 256];
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      acc.x ^= v[u].x;
+      acc.y ^= v[u].y;
+      acc.z ^= v[u].z;
+      acc.w ^= v[u].w;
+    }
+  }
+  __shared__ uint64_t s_x[256];
+  s_x[threadIdx.x] = ((uint64_t)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) s_x[threadIdx.x] ^= s_x[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) sink[blockIdx.x] = s_x[0];
+}
+
+inline uint32_t move_groups(const PlanDev &p, uint64_t max_entries) {
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
+  const uint64_t items = max_entries << ppc_log2;
+  uint64_t groups = (items + COPY_THREADS / 64 - 1) / (COPY_THREADS / 64);
+  if (groups > COPY_MAX_GROUPS) groups = COPY_MAX_GROUPS;
+  return (uint32_t)groups;
+}
+
+}  // namespace
+
+hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                         const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
+                         hipStream_t s) {
+  const uint64_t most = p.nchunks < manifest_cap ? p.nchunks : manifest_cap;
+  const uint32_t groups = move_groups(p, most);
+  if (groups == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_move<true>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, most,
+                     d_counts, reinterpret_cast<uint8_t *>(d_staging), staging_cap,
+                     (unsigned long long *)nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
+                          const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
+                          hipStream_t s) {
+  if (d_rejected)
+    hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(1), 0, s,
+                       reinterpret_cast<unsigned long long *>(d_rejected));
+  const uint32_t groups = move_groups(p, nentries);
+  if (groups == 0) return hipGetLastError();
+  hipLaunchKernelGGL(k_move<false>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, nentries,
+                     (const ckpt_counts_t *)nullptr,
+                     const_cast<uint8_t *>(reinterpret_cast<const uint8_t *>(d_staging)),
+                     staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected));
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s) {
+  const uint64_t n16 = nbytes / 16;
+  if (n16 == 0) return hipSuccess;
+  uint64_t groups = (n16 + 256 * UNROLL - 1) / (256 * UNROLL);
+  if (groups > 2048) groups = 2048;
+  hipLaunchKernelGGL(k_bw_copy, dim3((uint32_t)groups), dim3(256), 0, s,
+                     reinterpret_cast<uint4 *>(d_dst), reinterpret_cast<const uint4 *>(d_src), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s) {
+  const uint64_t n16 = nbytes / 16;
+  uint64_t groups = (n16 + 256 * UNROLL - 1) / (256 * UNROLL);
+  if (groups > 2048) groups = 2048;
+  if (groups == 0) groups = 1;
+  hipLaunchKernelGGL(k_bw_read, dim3((uint32_t)groups), dim3(256), 0, s,
+                     reinterpret_cast<const uint4 *>(d_src), n16, d_sink);
+  return hipGetLastError();
+}
+
+}  // namespace ckpt

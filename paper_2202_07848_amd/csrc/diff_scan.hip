@@ -1,0 +1,237 @@
+// Checksum comparison and the prefix scan that orders the swap-out.
+//
+// diff: the comparison of a rank's checksums "with the other rank's copy" that
+// the Singularity paper does on the host (sec. 6; sec. 5.2.1, 5.2.3) -- here a
+// device kernel, one thread per four chunks.
+//
+// compact, metadata half: stable compaction.  Staging order must be ascending
+// chunk id, so offsets come from an exclusive prefix sum over
+// (mask, mask * pad16(len)) pairs, done in three deterministic steps with no
+// inter-workgroup waiting: per-workgroup sums, a single-workgroup scan of
+// those sums, then a per-workgroup rescan that writes the manifest.
+#include "ckpt_internal.h"
+
+namespace ckpt {
+
+namespace {
+
+struct Pair {
+  uint64_t cnt;
+  uint64_t bytes;
+};
+
+__device__ __forceinline__ Pair operator+(Pair a, Pair b) { return {a.cnt + b.cnt, a.bytes + b.bytes}; }
+
+__device__ __forceinline__ Pair shfl_up(Pair v, int delta) {
+  Pair r;
+  r.cnt = __shfl_up(v.cnt, delta, 64);
+  r.bytes = __shfl_up(v.bytes, delta, 64);
+  return r;
+}
+
+// Exclusive scan of one Pair per thread across a workgroup of SCAN_THREADS
+// threads; `total` receives the workgroup sum in every thread.
+__device__ Pair block_exclusive_scan(Pair v, Pair *total) {
+  __shared__ Pair s_wave[SCAN_THREADS / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Pair incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    Pair o = shfl_up(incl, d);
+    if (lane >= d) incl = incl + o;
+  }
+  __syncthreads();                 // s_wave may still be read from a previous call
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  Pair before = {0, 0}, all = {0, 0};
+#pragma unroll
+  for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+    if (w < wave) before = before + s_wave[w];
+    all = all + s_wave[w];
+  }
+  *total = all;
+  Pair excl = before + incl;
+  excl.cnt -= v.cnt;
+  excl.bytes -= v.bytes;
+  return excl;
+}
+
+// Per-thread view of SCAN_PER_THREAD consecutive chunks.
+struct Quad {
+  uint64_t k0;
+  int n;                          // valid chunks (0..SCAN_PER_THREAD)
+  uint8_t m[SCAN_PER_THREAD];
+  ChunkRef ref[SCAN_PER_THREAD];
+};
+
+__device__ __forceinline__ uint64_t thread_first_chunk() {
+  return (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
+}
+
+__device__ __forceinline__ Pair sum_marked(const PlanDev &p, uint64_t k0, const uint8_t *m, int n,
+                                           ChunkRef *refs) {
+  Pair s = {0, 0};
+  for (int i = 0; i < n; ++i) {
+    if (m[i]) {
+      ChunkRef r = locate_chunk(p, k0 + i);
+      if (refs) refs[i] = r;
+      s.cnt += 1;
+      s.bytes += pad16(r.len);
+    }
+  }
+  return s;
+}
+
+// mask[k] = (ref == nullptr || dig[k] != ref[k]); per-workgroup sums of the
+// marked chunks go to blocksums[2*b], [2*b+1].
+__global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t *__restrict__ dig,
+                                                       const uint64_t *__restrict__ ref,
+                                                       uint8_t *__restrict__ mask,
+                                                       uint64_t *__restrict__ blocksums) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  int n = 0;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    if (k < p.nchunks) {
+      m[i] = (ref == nullptr || dig[k] != ref[k]) ? 1 : 0;
+      mask[k] = m[i];
+      n = i + 1;
+    }
+  }
+  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  block_exclusive_scan(mine, &total);
+  if (threadIdx.x == 0) {
+    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
+    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  }
+}
+
+// Same sums for a caller-supplied mask (any non-zero byte marks a chunk).
+__global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(PlanDev p,
+                                                             const uint8_t *__restrict__ mask,
+                                                             uint64_t *__restrict__ blocksums) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  int n = 0;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    if (k < p.nchunks) {
+      m[i] = mask[k] != 0;
+      n = i + 1;
+    }
+  }
+  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  block_exclusive_scan(mine, &total);
+  if (threadIdx.x == 0) {
+    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
+    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  }
+}
+
+// One workgroup: turns blocksums[0..nblocks) into their exclusive prefix sums
+// (when `rewrite`) and writes the grand totals to counts, overflow = 0.
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(uint64_t *__restrict__ blocksums,
+                                                              uint64_t nblocks, int rewrite,
+                                                              ckpt_counts_t *__restrict__ counts) {
+  Pair carry = {0, 0};
+  for (uint64_t base = 0; base < nblocks; base += SCAN_THREADS) {
+    const uint64_t b = base + threadIdx.x;
+    Pair v = {0, 0};
+    if (b < nblocks) v = {blocksums[2 * b], blocksums[2 * b + 1]};
+    Pair total;
+    Pair excl = block_exclusive_scan(v, &total);
+    if (rewrite && b < nblocks) {
+      blocksums[2 * b] = carry.cnt + excl.cnt;
+      blocksums[2 * b + 1] = carry.bytes + excl.bytes;
+    }
+    carry = carry + total;
+  }
+  if (threadIdx.x == 0) {
+    counts->ndirty = carry.cnt;
+    counts->staged_bytes = carry.bytes;
+    counts->overflow = 0;
+  }
+}
+
+// Final pass: every marked chunk learns its entry index and staging offset and
+// writes its manifest entry.  blockoff holds the exclusive sums from
+// k_scan_blocks.  Entries that miss a capacity are counted in counts->overflow.
+__global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
+    PlanDev p, const uint8_t *__restrict__ mask, const uint64_t *__restrict__ dig,
+    const uint64_t *__restrict__ blockoff, ckpt_entry_t *__restrict__ manifest,
+    uint64_t manifest_cap, uint64_t staging_cap, ckpt_counts_t *__restrict__ counts) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  ChunkRef refs[SCAN_PER_THREAD];
+  int n = 0;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    if (k < p.nchunks) {
+      m[i] = mask[k] != 0;
+      n = i + 1;
+    }
+  }
+  Pair mine = sum_marked(p, k0, m, n, refs), total;
+  Pair pos = block_exclusive_scan(mine, &total);
+  pos.cnt += blockoff[2 * (uint64_t)blockIdx.x];
+  pos.bytes += blockoff[2 * (uint64_t)blockIdx.x + 1];
+  uint32_t missed = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!m[i]) continue;
+    const ChunkRef r = refs[i];
+    const uint64_t padded = pad16(r.len);
+    const bool fits_manifest = pos.cnt < manifest_cap;
+    const bool fits_staging = fits_manifest && pos.bytes + padded <= staging_cap;
+    if (fits_manifest) {
+      ckpt_entry_t e;
+      e.buf = p.dense_orig[r.row];
+      e.len = r.len;
+      e.buf_off = r.off;
+      e.stage_off = pos.bytes;
+      e.digest = dig[k0 + i];
+      manifest[pos.cnt] = e;
+    }
+    if (!fits_staging) ++missed;
+    pos.cnt += 1;
+    pos.bytes += padded;
+  }
+  if (missed) atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow),
+                        (unsigned long long)missed);
+}
+
+inline uint32_t scan_blocks(uint64_t nchunks) {
+  return (uint32_t)((nchunks + SCAN_BLOCK - 1) / SCAN_BLOCK);
+}
+
+}  // namespace
+
+hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
+                       uint8_t *d_mask, uint64_t *d_blocksums, ckpt_counts_t *d_counts,
+                       hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  if (nblocks)
+    hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
+                       d_blocksums);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
+                     (uint64_t)nblocks, 0, d_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
+                               uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                               uint64_t manifest_cap, uint64_t *d_blocksums,
+                               ckpt_counts_t *d_counts, hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  if (nblocks)
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
+                       d_blocksums);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
+                     (uint64_t)nblocks, 1, d_counts);
+  if (nblocks)
+    hipLaunchKernelGGL(k_emit_manifest, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dig,
+                       d_blocksums, d_manifest, manifest_cap, staging_cap, d_counts);
+  return hipGetLastError();
+}
+
+}  // namespace ckpt

@@ -1,0 +1,232 @@
+// Fingerprint kernel: one XXH64 (seed 0) per chunk of every live buffer -- the
+// "content checksum of each live buffer" of the Singularity paper (sec. 5.2.1,
+// sec. 6), at chunk granularity.
+//
+// Mapping.  XXH64 offers four independent chains per chunk and nothing more, so
+// a wavefront takes GROUP = 16 consecutive chunks and gives each chunk a quad of
+// lanes: lane 4c+t owns accumulator t of chunk c.  That lane needs the t-th
+// 8-byte word of every 32-byte stripe -- 8 bytes at stride 32 -- which is the
+// opposite of what coalesces.  So the wave loads in a different role: each
+// global_load_dwordx4 instruction fetches 256 contiguous bytes (one TILE) from
+// each of four chunks, 16 lanes x 16 B per chunk, the tile goes through LDS,
+// and the hashing lanes read their words back with ds_read_b64.  Tiles are
+// prefetched DEPTH deep in registers, so LDS only ever holds the tile being
+// hashed (4.5 KiB per wave).  Loads are never inside a branch: a loader lane
+// with nothing left to fetch reads a 256-byte spare block owned by the plan.
+// The workgroup is a single wavefront: LDS traffic of one wave is executed in order, so only compiler-level (wavefront-scope)
+// fences are needed between the write and read phases, never s_barrier and
+// never a wait on outstanding global loads.
+//
+// A chunk of length len is split as  full tiles | up to 7 stripes | < 32 bytes.
+// The tile loop is wave-uniform up to the longest chunk in the group; lanes of
+// shorter chunks are masked.  Residual stripes and the tail are read straight
+// from global memory (they are < 256 bytes per chunk).
+#include "ckpt_internal.h"
+#include "xxh64_device.h"
+
+namespace ckpt {
+
+namespace {
+
+constexpr int TILE = 256;              // bytes of one chunk staged per step
+constexpr int TILE_LOG2 = 8;
+constexpr int LDS_PITCH = TILE + 32;   // per-chunk pitch; the 32-byte skew spreads chunks over banks
+constexpr int LOADS = GROUP * TILE / (64 * 16);   // dwordx4 loads per lane per step (= 4)
+constexpr int DEPTH = 4;               // tiles in flight per lane (registers)
+
+__device__ __forceinline__ void lds_phase_fence() {
+  // Orders this wave's LDS writes and reads in the compiler; the hardware
+  // executes one wave's LDS instructions in issue order.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// 16-byte load through a pointer known to be global memory (global_load, which
+// only counts on vmcnt, instead of flat_load, which also holds up LDS waits).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
+__device__ __forceinline__ u32x4 gload16(const uint8_t *p) { return *(global_u32x4_ptr)(p); }
+
+// One step of the tile pipeline: the prefetched tile in q goes to LDS, the
+// slot is refilled with tile `next` (REFILL), the hashing lanes consume it.
+// In the non-uniform case a loader lane whose chunk has no tile `next` reads
+// the plan's spare block instead, and a hashing lane whose chunk is already
+// finished sits the step out; nothing in the step is a branch around a load,
+// so the compiler can count outstanding loads exactly.
+template <bool UNIFORM, bool REFILL>
+__device__ __forceinline__ uint64_t tile_step(u32x4 (&q)[LOADS], uint8_t *wr, const uint8_t *rd,
+                                              const uint8_t *const (&lptr)[LOADS],
+                                              const uint32_t (&ltiles)[LOADS],
+                                              const uint8_t *spare, uint32_t my_tiles, uint32_t tt,
+                                              uint32_t next, uint64_t acc) {
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) *reinterpret_cast<u32x4 *>(wr + i * 4 * LDS_PITCH) = q[i];
+  lds_phase_fence();
+  if (REFILL) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const uint8_t *a = lptr[i] + (uint64_t)next * TILE;
+      if (!UNIFORM) a = next < ltiles[i] ? a : spare;
+      q[i] = gload16(a);
+    }
+  }
+  if (UNIFORM || tt < my_tiles) {
+#pragma unroll
+    for (int s = 0; s < TILE / 32; ++s)
+      acc = xxh::round(acc, *reinterpret_cast<const uint64_t *>(rd + 32 * s));
+  }
+  lds_phase_fence();
+  return acc;
+}
+
+template <bool UNIFORM>
+__device__ __forceinline__ uint64_t hash_tiles(uint8_t *s_tile, const uint8_t *const (&lptr)[LOADS],
+                                               const uint32_t (&ltiles)[LOADS],
+                                               const uint8_t *spare, uint32_t my_tiles,
+                                               uint32_t max_tiles, int lane, uint64_t acc) {
+  const int c = lane >> 2, t = lane & 3;
+  uint8_t *wr = s_tile + (lane >> 4) * LDS_PITCH + 16 * (lane & 15);
+  const uint8_t *rd = s_tile + c * LDS_PITCH + 8 * t;
+  spare += 16 * (lane & 15);
+
+  // prologue: tiles 0..DEPTH-1 (those that exist)
+  u32x4 q[DEPTH][LOADS];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const uint32_t have = UNIFORM ? max_tiles : ltiles[i];
+      q[d][i] = gload16((uint32_t)d < have ? lptr[i] + (uint64_t)d * TILE : spare);
+    }
+  }
+
+  // steady state: every step refills its slot, DEPTH steps per trip
+  const uint32_t steady = max_tiles > DEPTH ? (max_tiles - DEPTH) / DEPTH * DEPTH : 0;
+  uint32_t tile = 0;
+  for (; tile < steady; tile += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+      acc = tile_step<UNIFORM, true>(q[d], wr, rd, lptr, ltiles, spare, my_tiles, tile + d,
+                                     tile + d + DEPTH, acc);
+  }
+  // drain: the last DEPTH..2*DEPTH-1 tiles (or all of them if there are fewer)
+#pragma unroll
+  for (int d = 0; d < 2 * DEPTH; ++d) {
+    const uint32_t tt = steady + d;              // wave-uniform
+    if (tt < max_tiles) {
+      if (tt + DEPTH < max_tiles)
+        acc = tile_step<UNIFORM, true>(q[d % DEPTH], wr, rd, lptr, ltiles, spare, my_tiles, tt,
+                                       tt + DEPTH, acc);
+      else
+        acc = tile_step<UNIFORM, false>(q[d % DEPTH], wr, rd, lptr, ltiles, spare, my_tiles, tt, 0,
+                                        acc);
+    }
+  }
+  return acc;
+}
+
+__global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restrict__ dig) {
+  __shared__ __align__(16) uint8_t s_tile[GROUP * LDS_PITCH];
+  __shared__ uint64_t s_ptr[GROUP];
+  __shared__ uint32_t s_len[GROUP];
+
+  const int lane = threadIdx.x;
+  const uint64_t k0 = (uint64_t)blockIdx.x * GROUP;
+
+  if (lane < GROUP) {
+    const uint64_t k = k0 + lane;
+    uint64_t ptr = 0;
+    uint32_t len = 0;
+    if (k < p.nchunks) {
+      ChunkRef r = locate_chunk(p, k);
+      ptr = p.dense_ptr[r.row] + r.off;
+      len = r.len;
+    }
+    s_ptr[lane] = ptr;
+    s_len[lane] = len;
+  }
+  __syncthreads();
+
+  const int c = lane >> 2, t = lane & 3;
+  const uint32_t my_len = s_len[c];
+  const uint8_t *my_ptr = reinterpret_cast<const uint8_t *>(s_ptr[c]);
+  const uint32_t my_tiles = my_len >> TILE_LOG2;
+
+  // loader role: load i of this lane serves chunk 4*i + lane/16, bytes 16*(lane%16)..+15 of a tile
+  const uint8_t *lptr[LOADS];
+  uint32_t ltiles[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int lc = 4 * i + (lane >> 4);
+    lptr[i] = reinterpret_cast<const uint8_t *>(s_ptr[lc]) + 16 * (lane & 15);
+    ltiles[i] = s_len[lc] >> TILE_LOG2;
+  }
+  uint32_t max_tiles = 0, min_tiles = 0xFFFFFFFFu;
+#pragma unroll
+  for (int i = 0; i < GROUP; ++i) {
+    const uint32_t n = s_len[i] >> TILE_LOG2;
+    max_tiles = n > max_tiles ? n : max_tiles;
+    min_tiles = n < min_tiles ? n : min_tiles;
+  }
+  max_tiles = __builtin_amdgcn_readfirstlane(max_tiles);
+  min_tiles = __builtin_amdgcn_readfirstlane(min_tiles);
+
+  uint64_t acc = xxh::acc_init(t);
+  if (max_tiles == min_tiles)
+    acc = hash_tiles<true>(s_tile, lptr, ltiles, p.spare, my_tiles, max_tiles, lane, acc);
+  else
+    acc = hash_tiles<false>(s_tile, lptr, ltiles, p.spare, my_tiles, max_tiles, lane, acc);
+
+  // up to 7 stripes between the last full tile and the tail
+  const uint32_t rem = my_len & (TILE - 1);
+  const uint32_t rstripes = rem >> 5;
+  const uint8_t *rp = my_ptr + ((uint64_t)my_tiles << TILE_LOG2);
+#pragma unroll
+  for (int s = 0; s < TILE / 32 - 1; ++s) {
+    if ((uint32_t)s < rstripes)
+      acc = xxh::round(acc, *reinterpret_cast<const uint64_t *>(rp + 32 * s + 8 * t));
+  }
+
+  // gather the quad's four accumulators (every lane of the quad gets all four)
+  const int qbase = lane & ~3;
+  const uint64_t v1 = __shfl(acc, qbase + 0, 64);
+  const uint64_t v2 = __shfl(acc, qbase + 1, 64);
+  const uint64_t v3 = __shfl(acc, qbase + 2, 64);
+  const uint64_t v4 = __shfl(acc, qbase + 3, 64);
+
+  if (t == 0 && my_len != 0) {
+    uint64_t h = my_len >= 32 ? xxh::converge(v1, v2, v3, v4) : xxh::PRIME5;
+    h += my_len;
+    const uint8_t *tp = rp + 32 * rstripes;
+    uint32_t left = my_len & 31;
+    while (left >= 8) {
+      h = xxh::tail8(h, *reinterpret_cast<const uint64_t *>(tp));
+      tp += 8;
+      left -= 8;
+    }
+    if (left >= 4) {
+      h = xxh::tail4(h, *reinterpret_cast<const uint32_t *>(tp));
+      tp += 4;
+      left -= 4;
+    }
+    while (left > 0) {
+      h = xxh::tail1(h, *tp);
+      tp += 1;
+      left -= 1;
+    }
+    dig[k0 + c] = xxh::avalanche(h);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s) {
+  if (p.nchunks == 0) return hipSuccess;
+  const uint64_t groups = (p.nchunks + GROUP - 1) / GROUP;
+  if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_fingerprint, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests);
+  return hipGetLastError();
+}
+
+}  // namespace ckpt

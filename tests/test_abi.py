@@ -1,0 +1,65 @@
+"""The C-ABI library loads without a GPU and exports every function that
+include/ckpt.h declares; argument errors that need no device are reported."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2202_07848_amd import binding as ck
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ckpt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ckpt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    lib = ctypes.CDLL(ck.LIB_PATH)
+    names = declared_functions()
+    assert {"ckpt_fingerprint", "ckpt_diff", "ckpt_compact", "ckpt_restore",
+            "ckpt_plan_create", "ckpt_plan_destroy"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(ck.EXPORTS) == set(names)
+
+
+def test_version_and_strerror():
+    assert ck.version() >= 1
+    lib = ck._lib()
+    for status in range(0, -8, -1):
+        assert lib.ckpt_strerror(status).decode() not in ("", "unknown status")
+    assert lib.ckpt_strerror(-99).decode() == "unknown status"
+
+
+def test_host_side_argument_checks_need_no_device():
+    lib = ck._lib()
+    out = ctypes.c_void_p()
+    one = (ck._Buf * 1)()
+    one[0].ptr, one[0].nbytes = 0x1000, 4096
+    assert lib.ckpt_plan_create(one, 1, 1000, ctypes.byref(out)) == -3        # not a power of two
+    assert lib.ckpt_plan_create(one, 1, 128, ctypes.byref(out)) == -3         # too small
+    assert lib.ckpt_plan_create(one, 1, 1 << 31, ctypes.byref(out)) == -3     # too large
+    assert lib.ckpt_plan_create(None, 1, 4096, ctypes.byref(out)) == -1
+    assert lib.ckpt_plan_create(one, 1, 4096, None) == -1
+    one[0].ptr = 0x1008
+    assert lib.ckpt_plan_create(one, 1, 4096, ctypes.byref(out)) == -2        # misaligned buffer
+    one[0].ptr = None
+    assert lib.ckpt_plan_create(one, 1, 4096, ctypes.byref(out)) == -1        # NULL with bytes
+    assert out.value is None
+    assert lib.ckpt_fingerprint(None, None, None) == -1
+    assert lib.ckpt_diff(None, None, None, 0, None, None, None) == -1
+    assert lib.ckpt_compact(None, None, None, None, 0, None, 0, None, None) == -1
+    assert lib.ckpt_restore(None, None, 0, None, 0, None, None) == -1
+    assert lib.ckpt_plan_destroy(None) == 0
+    assert lib.ckpt_plan_nchunks(None) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    monkeypatch.setattr(ck, "_handle", None)
+    monkeypatch.setattr(ck, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libckpt.so"))
+    with pytest.raises(ImportError):
+        ck.version()

@@ -175,7 +175,7 @@ def test_compact_restore_round_trip(with_ref):
     for ar, x in zip(arenas, dst_content):
         ar[32:32 + x.size] = x
         dst.append(ar[32:32 + x.size])
-    assert oracle.restore(dst, staging, man) == 0
+    assert oracle.restore(dst, chunk, staging, man) == 0
     for ar, d, s in zip(arenas, dst, snap):
         assert np.array_equal(d, s)
         assert np.all(ar[:32] == 0xEE) and np.all(ar[32 + s.size:] == 0xEE)
@@ -188,7 +188,7 @@ def test_restore_writes_only_listed_chunks():
     mask = np.array([0, 1, 0, 0, 0, 0, 1, 0], dtype=np.uint8)
     staging, man, _ = oracle.compact(snap, 1024, mask, dig)
     dst = [np.zeros(4096, dtype=np.uint8), np.zeros(4096, dtype=np.uint8)]
-    assert oracle.restore(dst, staging, man) == 0
+    assert oracle.restore(dst, 1024, staging, man) == 0
     assert np.array_equal(dst[0][1024:2048], snap[0][1024:2048])
     assert np.array_equal(dst[1][2048:3072], snap[1][2048:3072])
     assert dst[0][:1024].sum() == 0 and dst[0][2048:].sum() == 0
@@ -202,10 +202,22 @@ def test_restore_rejects_entries_outside_destination():
     mask = np.ones(dig.size, dtype=np.uint8)
     staging, man, _ = oracle.compact(snap, 1024, mask, dig)
     small = [np.zeros(2048, dtype=np.uint8), np.zeros(999, dtype=np.uint8)]
-    assert oracle.restore(small, staging, man) == -3          # third entry does not fit
-    assert np.array_equal(small[0], snap[0])                 # earlier entries applied
-    assert oracle.restore([np.zeros(2048, dtype=np.uint8)], staging, man) == -3
-    assert oracle.restore([x.copy() for x in snap], staging[:-16], man) == -3
+    assert oracle.restore(small, 1024, staging, man) == 1           # third entry does not fit
+    assert np.array_equal(small[0], snap[0])                 # the others are applied
+    assert small[1].sum() == 0
+    assert oracle.restore([np.zeros(2048, dtype=np.uint8)], 1024, staging, man) == 1
+    part = [x.copy() for x in snap]
+    part[1][:] = 0
+    assert oracle.restore(part, 1024, staging[:-16], man) == 1     # last entry's bytes cut off
+    assert part[1].sum() == 0 and np.array_equal(part[0], snap[0])
+    # entries compact could not have written: odd offsets, length above the chunk size
+    bad = man.copy()
+    bad["stage_off"][0] += 8
+    bad["buf_off"][1] += 4
+    bad["len"][2] = 1025
+    fresh = [np.zeros(2048, dtype=np.uint8), np.zeros(1000, dtype=np.uint8)]
+    assert oracle.restore(fresh, 1024, staging, bad) == 3
+    assert fresh[0].sum() == 0 and fresh[1].sum() == 0
 
 
 # ---- the five configurations, reduced to CPU size -------------------------
@@ -232,7 +244,7 @@ def test_replica_configs_dedup_exactly_shared_state(cfg, shrink):
         staged.append(staging.size)
         # delta restore into replica 0's buffers reproduces replica r exactly
         dst = [x.copy() for x in rep0]
-        assert oracle.restore(dst, staging, man) == 0
+        assert oracle.restore(dst, w.chunk, staging, man) == 0
         assert all(np.array_equal(d, s) for d, s in zip(dst, rep))
     assert len(set(staged)) == 1
 
@@ -252,7 +264,7 @@ def test_fragmented_config_marks_exactly_the_rewritten_chunks(fraction):
     assert np.array_equal(np.flatnonzero(mask), ids)
     staging, man, _ = oracle.compact(t1, w.chunk, mask, dig)
     dst = [x.copy() for x in t0]
-    assert oracle.restore(dst, staging, man) == 0
+    assert oracle.restore(dst, w.chunk, staging, man) == 0
     assert all(np.array_equal(d, s) for d, s in zip(dst, t1))
     # all-zero buffers hash to the same per-length digests
     zero_chunks = [k for k, b in enumerate(wl.chunk_table(w)[0]) if w.bufs[b].kind == "zero"
