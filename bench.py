@@ -1,0 +1,286 @@
+#!/usr/bin/env python3
+"""Benchmark of the device-state snapshot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--dirty F]
+
+One step = one pass of the whole path over the configuration's synthetic
+training state, everything already resident in HBM:
+
+    replica configs (1, 2, 4, 5):  fingerprint(replica 0) -> reference digests,
+        then for every other replica r: fingerprint(r), diff against the
+        reference, compact, restore (back into r's own buffers, so the state is
+        the same for the next step);
+    config 3 (one fragmented replica, previous-snapshot diff):  fingerprint(t1),
+        diff against the digests of t0, compact, restore.
+
+Prints ONE JSON line.  `value` is device-state GB/s over fingerprint + diff +
+compact (all bytes fingerprinted in the step / the time of those three phases,
+from HIP events on the launch stream); restore is timed inside the same step
+and reported beside it; `ms_per_step` is the wall time of the whole step.
+The default workload is config 5 (3B-parameter replicas x2, 1 MiB chunks), the
+configuration the throughput target is quoted on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--shrink", type=int, default=1, help="reduced workload (debugging only)")
+    ap.add_argument("--dirty", type=float, default=0.10, help="config 3: rewritten chunk fraction")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-gib", type=float, default=8.0)
+    return ap.parse_args()
+
+
+class Replica:
+    def __init__(self, w, arena, offs, ck):
+        self.arena = arena
+        base = arena.data_ptr()
+        self.desc = [(base + int(o), b.nbytes) for o, b in zip(offs, w.bufs)]
+        self.offs = offs
+        self.plan = ck.Plan(self.desc, w.chunk)
+
+
+def read_traffic_note(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE runs), kept as text under profiles/.  None when no such record exists."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{kernel}_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, rep_ref, rep_new, sample_bytes, torch):
+    """The oracle, as it stands, on a bounded sample of the same workload: every
+    s-th buffer of the list (so shared and per-replica buffers keep their mix)."""
+    import numpy as np
+    import oracle
+
+    total = w.nbytes
+    stride = max(1, int(round(total / max(1, sample_bytes))))
+    idx = list(range(0, len(w.bufs), stride))
+    if w.distinct_bytes and not any(not w.bufs[i].shared for i in idx):
+        idx.append(next(i for i, b in enumerate(w.bufs) if not b.shared))
+        idx.sort()
+
+    def fetch(rep):
+        out = []
+        for i in idx:
+            o, n = int(rep.offs[i]), w.bufs[i].nbytes
+            out.append(rep.arena[o:o + n].cpu().numpy())
+        return out
+
+    h_ref, h_new = fetch(rep_ref), fetch(rep_new)
+    nbytes = sum(b.size for b in h_new)
+    threads = len(os.sched_getaffinity(0))
+    t0 = time.perf_counter()
+    ref = oracle.fingerprint(h_ref, w.chunk, threads)
+    dig = oracle.fingerprint(h_new, w.chunk, threads)
+    mask, cnt = oracle.diff(h_new, w.chunk, dig, ref)
+    staging, man, cnt2 = oracle.compact(h_new, w.chunk, mask, dig)
+    dt = time.perf_counter() - t0
+    hashed = sum(b.size for b in h_ref) + nbytes
+    return {
+        "value": hashed / dt / 1e9, "unit": "GB/s of device state (fingerprint+diff+compact)",
+        "cores": threads, "kind": "oracle",
+        "sample": f"every {stride}th buffer of both replicas: {len(idx)} buffers, "
+                  f"{hashed / 2**30:.2f} GiB fingerprinted, {cnt2['staged_bytes'] / 2**30:.2f} GiB "
+                  f"staged, {dt:.2f} s wall (fingerprint on {threads} threads, rest on one)",
+    }, (idx, dig, mask)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path shards per device with no "
+              "exchange); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2202_07848_amd import binding as ck
+    from paper_2202_07848_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.config(args.config, args.shrink)
+    t_gen = time.perf_counter()
+
+    replicas = []
+    if w.nreplicas >= 2:
+        for r in range(w.nreplicas):
+            arena, offs = wl.torch_replica(w, r, dev, shared_from=replicas[0].arena if r else None)
+            replicas.append(Replica(w, arena, offs, ck))
+        pairs = [(replicas[0], replicas[r]) for r in range(1, w.nreplicas)]
+        fingerprinted = w.nreplicas
+        expect_dirty = w.distinct_chunks
+    else:
+        arena0, offs = wl.torch_replica(w, 0, dev)
+        t0 = Replica(w, arena0, offs, ck)
+        arena1 = arena0.clone()
+        t1 = Replica(w, arena1, offs, ck)
+        ids = wl.dirty_chunk_ids(w, args.dirty, int(args.dirty * 100))
+        wl.torch_rewrite_chunks(w, arena1, offs, ids, int(args.dirty * 100))
+        replicas = [t0, t1]
+        pairs = [(t0, t1)]
+        fingerprinted = 1
+        expect_dirty = int(ids.size)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    n = w.nchunks
+    S = w.nbytes
+    ref = torch.zeros(n, dtype=torch.int64, device=dev)
+    digs = [torch.zeros(n, dtype=torch.int64, device=dev) for _ in pairs]
+    masks = [torch.zeros(n, dtype=torch.uint8, device=dev) for _ in pairs]
+    counts = [torch.zeros(3, dtype=torch.int64, device=dev) for _ in pairs]
+
+    # size staging from a first diff (part of set-up, like plan creation)
+    ck.fingerprint(pairs[0][0].plan, ref)
+    staged, ndirty = [], []
+    for (a, b), dig, mask, cnt in zip(pairs, digs, masks, counts):
+        ck.fingerprint(b.plan, dig)
+        ck.diff(b.plan, dig, ref, mask, cnt)
+    torch.cuda.synchronize()
+    for cnt in counts:
+        ndirty.append(int(cnt[0]))
+        staged.append(int(cnt[1]))
+    assert all(x == expect_dirty for x in ndirty), (ndirty, expect_dirty)
+    stagings = [torch.empty(max(16, s), dtype=torch.uint8, device=dev) for s in staged]
+    manifests = [torch.empty(max(1, k) * 32, dtype=torch.uint8, device=dev) for k in ndirty]
+
+    ev = torch.cuda.Event
+
+    def step(timed):
+        marks = [ev(enable_timing=True)]
+        marks[0].record()
+        if w.nreplicas >= 2:
+            ck.fingerprint(pairs[0][0].plan, ref)
+        marks.append(ev(enable_timing=True)); marks[-1].record()
+        for i, (a, b) in enumerate(pairs):
+            ck.fingerprint(b.plan, digs[i])
+            marks.append(ev(enable_timing=True)); marks[-1].record()
+            ck.diff(b.plan, digs[i], ref, masks[i], counts[i])
+            marks.append(ev(enable_timing=True)); marks[-1].record()
+            ck.compact(b.plan, masks[i], digs[i], stagings[i], manifests[i], counts[i],
+                       staging_cap=staged[i], manifest_cap=ndirty[i])
+            marks.append(ev(enable_timing=True)); marks[-1].record()
+            ck.restore(b.plan, stagings[i], staged[i], manifests[i], ndirty[i])
+            marks.append(ev(enable_timing=True)); marks[-1].record()
+        return marks
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    all_marks = []
+    wall0 = time.perf_counter()
+    for _ in range(args.steps):
+        all_marks.append(step(True))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+
+    ph = {"fingerprint_ref": [], "fingerprint": [], "diff": [], "compact": [], "restore": []}
+    for marks in all_marks:
+        ph["fingerprint_ref"].append(marks[0].elapsed_time(marks[1]))
+        fp = df = cp = rs = 0.0
+        for i in range(len(pairs)):
+            m = marks[1 + 4 * i: 6 + 4 * i]
+            fp += m[0].elapsed_time(m[1]); df += m[1].elapsed_time(m[2])
+            cp += m[2].elapsed_time(m[3]); rs += m[3].elapsed_time(m[4])
+        ph["fingerprint"].append(fp); ph["diff"].append(df)
+        ph["compact"].append(cp); ph["restore"].append(rs)
+    mean = {k: float(np.mean(v)) for k, v in ph.items()}
+    med = {k: float(np.median(v)) for k, v in ph.items()}
+
+    for cnt, k, s in zip(counts, ndirty, staged):
+        c = cnt.cpu().numpy().view(np.uint64)
+        assert (int(c[0]), int(c[1]), int(c[2])) == (k, s, 0), c
+
+    bytes_fp = S * fingerprinted if w.nreplicas >= 2 else S
+    dirty_bytes = sum(staged)
+    t_fdc = (mean["fingerprint_ref"] + mean["fingerprint"] + mean["diff"] + mean["compact"]) / 1e3
+    value = bytes_fp / t_fdc / 1e9
+    moved = bytes_fp + 2 * dirty_bytes
+    n_fp_launch = fingerprinted if w.nreplicas >= 2 else 1
+    fp_launch_ms = (mean["fingerprint_ref"] + mean["fingerprint"]) / n_fp_launch
+    achieved = S / (fp_launch_ms / 1e3) / 1e9
+    workload = f"config{w.config}_{w.name}"
+    traffic = read_traffic_note("k_fingerprint", workload)
+
+    out = {
+        "metric": "device-state GB/s (fingerprint+diff+compact) and % of MI355X HBM peak",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {
+            "workload": workload, "chunk_bytes": w.chunk, "replicas": w.nreplicas,
+            "buffers": len(w.bufs), "bytes_per_replica": S, "chunks_per_replica": n,
+            "dirty_chunks": ndirty, "staged_bytes": staged,
+            "dirty_fraction": round(dirty_bytes / (S * len(pairs)), 4),
+            "shrink": args.shrink,
+        },
+        "hbm_frac_fp_diff_compact": round(moved / t_fdc / 1e9 / HBM_PEAK_GBPS, 4),
+        "bytes_moved_algorithmic": moved,
+        "phases_ms_mean": {k: round(v, 3) for k, v in mean.items()},
+        "phases_ms_median": {k: round(v, 3) for k, v in med.items()},
+        "restore_GBps_read_plus_write": round(2 * dirty_bytes / (mean["restore"] / 1e3) / 1e9, 1)
+        if dirty_bytes else None,
+        "compact_GBps_read_plus_write": round(2 * dirty_bytes / (mean["compact"] / 1e3) / 1e9, 1)
+        if dirty_bytes else None,
+        "setup_s": round(t_gen, 1),
+        "roofline": {
+            "kernel": "k_fingerprint", "bound": "hbm", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": S, "launch_ms": round(fp_launch_ms, 3),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        base, (idx, o_dig, o_mask) = cpu_baseline(w, pairs[0][0], pairs[0][1],
+                                                  args.cpu_sample_gib * 2**30, torch)
+        out["cpu_baseline"] = base
+        # the sampled buffers' digests and masks must equal what the GPU produced
+        buf, off, length = wl.chunk_table(w)
+        sel = np.flatnonzero(np.isin(buf, np.array(idx)))
+        g_dig = digs[0].cpu().numpy().view(np.uint64)[sel]
+        g_mask = masks[0].cpu().numpy()[sel]
+        out["cpu_baseline"]["sample_matches_gpu"] = bool(
+            np.array_equal(g_dig, o_dig) and np.array_equal(g_mask, o_mask))
+        assert out["cpu_baseline"]["sample_matches_gpu"], "GPU and oracle disagree on the sample"
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -54,6 +54,10 @@ def _lib():
             raise ImportError(
                 f"{LIB_PATH} is not built; run `python -m paper_2202_07848_amd.build` "
                 "(there is no CPU fallback)")
+        # PyTorch must load its HIP runtime first: the library then binds to that
+        # same runtime (same SONAME) instead of bringing a second copy into the
+        # process, which would not share torch's device context.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         u64, vp, ci = ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int
         lib.ckpt_plan_create.restype = ci
