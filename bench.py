@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--dirty", type=float, default=0.10, help="config 3: rewritten chunk fraction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=8.0)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
+                         "the known-size dispatches that scale the rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -265,6 +268,25 @@ def main():
             "algorithmic_bytes_per_launch": S, "launch_ms": round(fp_launch_ms, 3),
         },
     }
+
+    if args.calibrate:
+        nb = min(8 * 2**30, pairs[0][1].arena.numel() // 16 * 16, stagings[0].numel() // 16 * 16)
+        src, dst = pairs[0][1].arena, stagings[0]
+        sink = torch.zeros(4096, dtype=torch.int64, device=dev)
+        cal = {}
+        for name, fn in (("copy", lambda: ck.bw_copy(dst, src, nb)),
+                         ("read", lambda: ck.bw_read(src, nb, sink))):
+            fn()
+            e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            cal[name] = {"bytes": nb, "ms": round(ms, 3),
+                         "GBps": round((2 if name == "copy" else 1) * nb / ms / 1e6, 1)}
+        out["calibration"] = cal
 
     if not args.no_cpu_baseline:
         base, (idx, o_dig, o_mask) = cpu_baseline(w, pairs[0][0], pairs[0][1],
