@@ -44,9 +44,14 @@ __device__ __forceinline__ void lds_phase_fence() {
 
 // 16-byte load through a pointer known to be global memory (global_load, which
 // only counts on vmcnt, instead of flat_load, which also holds up LDS waits).
+// Every byte is read exactly once, so the load is non-temporal: measured on
+// MI355X a plain streaming read reaches 7.2 TB/s with the nt hint and 6.4 TB/s
+// without it.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
-__device__ __forceinline__ u32x4 gload16(const uint8_t *p) { return *(global_u32x4_ptr)(p); }
+__device__ __forceinline__ u32x4 gload16(const uint8_t *p) {
+  return __builtin_nontemporal_load((global_u32x4_ptr)(p));
+}
 
 // One step of the tile pipeline: the prefetched tile in q goes to LDS, the
 // slot is refilled with tile `next` (REFILL), the hashing lanes consume it.
