@@ -1,6 +1,8 @@
 // C ABI of libckpt.so: argument checks, the plan object, kernel launches.
 // Semantics and citations are in include/ckpt.h.
+#include <algorithm>
 #include <new>
+#include <numeric>
 #include <vector>
 
 #include "ckpt_internal.h"
@@ -43,7 +45,9 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
 
   std::vector<uint64_t> dense_ptr, dense_nbytes, dense_base, list_ptr, list_nbytes;
   std::vector<uint32_t> dense_orig, group_first;
-  uint64_t nchunks = 0, total = 0;
+  std::vector<uint64_t> full_ptr, full_chunk0, full_base, short_ptr, short_chunk;
+  std::vector<uint32_t> full_group_first, short_len;
+  uint64_t nchunks = 0, total = 0, nfull = 0;
   try {
     list_ptr.reserve(nbufs);
     list_nbytes.reserve(nbufs);
@@ -62,10 +66,50 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
       dense_nbytes.push_back(n);
       dense_base.push_back(nchunks);
       dense_orig.push_back((uint32_t)i);
-      nchunks += (n + chunk_bytes - 1) >> chunk_log2;
+      const uint64_t whole = n >> chunk_log2, rest = n & (chunk_bytes - 1);
+      if (whole != 0) {
+        full_ptr.push_back(reinterpret_cast<uint64_t>(bufs[i].ptr));
+        full_chunk0.push_back(nchunks);
+        full_base.push_back(nfull);
+        nfull += whole;
+      }
+      if (rest != 0) {
+        short_ptr.push_back(reinterpret_cast<uint64_t>(bufs[i].ptr) + (whole << chunk_log2));
+        short_chunk.push_back(nchunks + whole);
+        short_len.push_back((uint32_t)rest);
+      }
+      nchunks += whole + (rest != 0);
       total += n;
     }
     dense_base.push_back(nchunks);
+    full_base.push_back(nfull);
+    {
+      // short chunks, longest first (stable, so equal lengths keep list order)
+      std::vector<uint32_t> order(short_len.size());
+      std::iota(order.begin(), order.end(), 0u);
+      std::stable_sort(order.begin(), order.end(),
+                       [&](uint32_t a, uint32_t b) { return short_len[a] > short_len[b]; });
+      std::vector<uint64_t> sp(order.size()), sc(order.size());
+      std::vector<uint32_t> sl(order.size());
+      for (size_t j = 0; j < order.size(); ++j) {
+        sp[j] = short_ptr[order[j]];
+        sc[j] = short_chunk[order[j]];
+        sl[j] = short_len[order[j]];
+      }
+      short_ptr.swap(sp);
+      short_chunk.swap(sc);
+      short_len.swap(sl);
+    }
+    {
+      const uint64_t nfg = (nfull + ckpt::GROUP - 1) / ckpt::GROUP;
+      full_group_first.resize(nfg);
+      uint32_t frow = 0;
+      for (uint64_t g = 0; g < nfg; ++g) {
+        const uint64_t f = g * ckpt::GROUP;
+        while (f >= full_base[frow + 1]) ++frow;
+        full_group_first[g] = frow;
+      }
+    }
     const uint64_t ngroups = (nchunks + ckpt::GROUP - 1) / ckpt::GROUP;
     if (ngroups > 0x7FFFFFFFull) return CKPT_ERR_INVALID_ARG;
     group_first.resize(ngroups);
@@ -98,7 +142,15 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   const size_t o_gfirst = o_dorig + up16(4 * nb);
   const size_t o_lptr = o_gfirst + up16(4 * group_first.size());
   const size_t o_lnb = o_lptr + up16(8 * (size_t)nbufs);
-  const size_t o_spare = (o_lnb + up16(8 * (size_t)nbufs) + 255) & ~(size_t)255;
+  const size_t nf = full_ptr.size(), ns = short_ptr.size();
+  const size_t o_fptr = o_lnb + up16(8 * (size_t)nbufs);
+  const size_t o_fc0 = o_fptr + up16(8 * nf);
+  const size_t o_fbase = o_fc0 + up16(8 * nf);
+  const size_t o_fgf = o_fbase + up16(8 * (nf + 1));
+  const size_t o_sptr = o_fgf + up16(4 * full_group_first.size());
+  const size_t o_sck = o_sptr + up16(8 * ns);
+  const size_t o_slen = o_sck + up16(8 * ns);
+  const size_t o_spare = (o_slen + up16(4 * ns) + 255) & ~(size_t)255;
   const size_t bytes = o_spare + 256;
 
   hipError_t e = hipMalloc(&plan->d_tables, bytes);
@@ -130,6 +182,13 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   if (e == hipSuccess) e = upload(o_gfirst, group_first.data(), 4 * group_first.size());
   if (e == hipSuccess) e = upload(o_lptr, list_ptr.data(), 8 * (size_t)nbufs);
   if (e == hipSuccess) e = upload(o_lnb, list_nbytes.data(), 8 * (size_t)nbufs);
+  if (e == hipSuccess) e = upload(o_fptr, full_ptr.data(), 8 * nf);
+  if (e == hipSuccess) e = upload(o_fc0, full_chunk0.data(), 8 * nf);
+  if (e == hipSuccess) e = upload(o_fbase, full_base.data(), 8 * (nf + 1));
+  if (e == hipSuccess) e = upload(o_fgf, full_group_first.data(), 4 * full_group_first.size());
+  if (e == hipSuccess) e = upload(o_sptr, short_ptr.data(), 8 * ns);
+  if (e == hipSuccess) e = upload(o_sck, short_chunk.data(), 8 * ns);
+  if (e == hipSuccess) e = upload(o_slen, short_len.data(), 4 * ns);
   if (e == hipSuccess) e = hipMemset(base + o_spare, 0, 256);
   if (e != hipSuccess) {
     (void)hipFree(plan->d_tables);
@@ -147,6 +206,15 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   d.list_ptr = reinterpret_cast<const uint64_t *>(base + o_lptr);
   d.list_nbytes = reinterpret_cast<const uint64_t *>(base + o_lnb);
   d.spare = reinterpret_cast<const uint8_t *>(base + o_spare);
+  d.full_ptr = reinterpret_cast<const uint64_t *>(base + o_fptr);
+  d.full_chunk0 = reinterpret_cast<const uint64_t *>(base + o_fc0);
+  d.full_base = reinterpret_cast<const uint64_t *>(base + o_fbase);
+  d.full_group_first = reinterpret_cast<const uint32_t *>(base + o_fgf);
+  d.short_ptr = reinterpret_cast<const uint64_t *>(base + o_sptr);
+  d.short_chunk = reinterpret_cast<const uint64_t *>(base + o_sck);
+  d.short_len = reinterpret_cast<const uint32_t *>(base + o_slen);
+  d.nfull = nfull;
+  d.nshort = ns;
   d.nchunks = nchunks;
   d.nbufs = nbufs;
   d.nb = (uint32_t)nb;

@@ -28,6 +28,19 @@ struct PlanDev {
   const uint64_t *list_ptr;      // [nbufs]
   const uint64_t *list_nbytes;   // [nbufs]
   const uint8_t *spare;          // 256 readable bytes (zero), 256-byte aligned
+  // Work lists of the fingerprint kernel.  Full chunks (length C) and last
+  // chunks shorter than C are grouped separately so that the 16 chunks a
+  // wavefront hashes together have the same length (full) or nearly the same
+  // (short ones are sorted by length, longest first).
+  const uint64_t *full_ptr;      // [nf]   address of a buffer that has >= 1 full chunk
+  const uint64_t *full_chunk0;   // [nf]   global id of that buffer's first chunk
+  const uint64_t *full_base;     // [nf+1] full chunks in earlier rows; [nf] = nfull
+  const uint32_t *full_group_first;  // [ceil(nfull/GROUP)] row holding full chunk GROUP*g
+  const uint64_t *short_ptr;     // [nshort] address of the short chunk
+  const uint64_t *short_chunk;   // [nshort] its global id
+  const uint32_t *short_len;     // [nshort] its length, descending
+  uint64_t nfull;                // chunks of length C
+  uint64_t nshort;               // chunks shorter than C (at most one per buffer)
   uint64_t nchunks;              // N
   uint64_t nbufs;                // B (caller's list length)
   uint32_t nb;                   // dense rows

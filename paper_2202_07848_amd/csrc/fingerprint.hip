@@ -3,8 +3,8 @@
 // sec. 6), at chunk granularity.
 //
 // Mapping.  XXH64 offers four independent chains per chunk and nothing more, so
-// a wavefront takes GROUP = 16 consecutive chunks and gives each chunk a quad of
-// lanes: lane 4c+t owns accumulator t of chunk c.  That lane needs the t-th
+// a wavefront takes GROUP = 16 chunks of equal (or, for short last chunks,
+// similar) length and gives each chunk a quad of lanes: lane 4c+t owns accumulator t of chunk c.  That lane needs the t-th
 // 8-byte word of every 32-byte stripe -- 8 bytes at stride 32 -- which is the
 // opposite of what coalesces.  So the wave loads in a different role: each
 // global_load_dwordx4 instruction fetches 256 contiguous bytes (one TILE) from
@@ -134,21 +134,37 @@ __device__ __forceinline__ uint64_t hash_tiles(uint8_t *s_tile, const uint8_t *c
 __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restrict__ dig) {
   __shared__ __align__(16) uint8_t s_tile[GROUP * LDS_PITCH];
   __shared__ uint64_t s_ptr[GROUP];
+  __shared__ uint64_t s_chunk[GROUP];
   __shared__ uint32_t s_len[GROUP];
 
   const int lane = threadIdx.x;
-  const uint64_t k0 = (uint64_t)blockIdx.x * GROUP;
+  const uint64_t full_groups = (p.nfull + GROUP - 1) / GROUP;
 
+  // The grid is the full-chunk groups (longest work first) followed by the
+  // groups of short chunks, which are sorted by length.
   if (lane < GROUP) {
-    const uint64_t k = k0 + lane;
-    uint64_t ptr = 0;
+    uint64_t ptr = 0, k = 0;
     uint32_t len = 0;
-    if (k < p.nchunks) {
-      ChunkRef r = locate_chunk(p, k);
-      ptr = p.dense_ptr[r.row] + r.off;
-      len = r.len;
+    if (blockIdx.x < full_groups) {
+      const uint64_t f = (uint64_t)blockIdx.x * GROUP + lane;     // ordinal among full chunks
+      if (f < p.nfull) {
+        uint32_t row = p.full_group_first[blockIdx.x];
+        while (f >= p.full_base[row + 1]) ++row;                  // ends: full_base[nf] = nfull > f
+        const uint64_t j = f - p.full_base[row];
+        ptr = p.full_ptr[row] + (j << p.chunk_log2);
+        k = p.full_chunk0[row] + j;
+        len = 1u << p.chunk_log2;
+      }
+    } else {
+      const uint64_t s = ((uint64_t)blockIdx.x - full_groups) * GROUP + lane;
+      if (s < p.nshort) {
+        ptr = p.short_ptr[s];
+        k = p.short_chunk[s];
+        len = p.short_len[s];
+      }
     }
     s_ptr[lane] = ptr;
+    s_chunk[lane] = k;
     s_len[lane] = len;
   }
   __syncthreads();
@@ -220,7 +236,7 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
       tp += 1;
       left -= 1;
     }
-    dig[k0 + c] = xxh::avalanche(h);
+    dig[s_chunk[c]] = xxh::avalanche(h);
   }
 }
 
@@ -228,7 +244,7 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
 
 hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s) {
   if (p.nchunks == 0) return hipSuccess;
-  const uint64_t groups = (p.nchunks + GROUP - 1) / GROUP;
+  const uint64_t groups = (p.nfull + GROUP - 1) / GROUP + (p.nshort + GROUP - 1) / GROUP;
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_fingerprint, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests);
   return hipGetLastError();
