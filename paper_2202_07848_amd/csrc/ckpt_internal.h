@@ -80,7 +80,7 @@ constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
 // iteration; a piece is min(C, COPY_PIECE) bytes.
 constexpr int COPY_PIECE_LOG2 = 14;
 constexpr int COPY_THREADS = 256;
-constexpr int COPY_MAX_GROUPS = 4096;
+constexpr int COPY_MAX_GROUPS = 65536;
 
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s);
