@@ -1,0 +1,86 @@
+"""The oracle's independent pins as one function, runnable against any build of
+ckpt_oracle.c:  python tests/oracle_pins.py [path/to/lib.so]  exits 0 when every
+pin holds, 1 when one fails.  (A planted mistake may also corrupt memory and
+crash the process; the mutation test runs this file as a child for that reason.)"""
+import ctypes
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import oracle  # noqa: E402
+import xxhash  # noqa: E402
+from test_oracle_xxh64 import VECTORS  # noqa: E402
+
+
+def pattern_bufs(sizes, seed):
+    rng = np.random.default_rng(seed)
+    return [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+
+
+def pins_hold() -> bool:
+    """All independent pins, evaluated against whatever library `oracle` currently wraps."""
+    try:
+        for _, data, want in VECTORS:
+            assert oracle.xxh64(data) == want
+        sizes = [0, 1, 17, 255, 256, 257, 1000, 4097, 31]
+        chunk = 256
+        bufs = pattern_bufs(sizes, 1)
+        pieces = [(i, o, b[o:o + chunk]) for i, b in enumerate(bufs) for o in range(0, b.size, chunk)]
+        assert oracle.nchunks(bufs, chunk) == len(pieces)
+        for threads in (1, 3):
+            dig = oracle.fingerprint(bufs, chunk, threads)
+            assert dig.tolist() == [xxhash.xxh64_intdigest(p[2].tobytes(), 0) for p in pieces]
+        other = [b.copy() for b in bufs]
+        other[4][0] ^= 1
+        other[6][999] ^= 1
+        other[7][4096] ^= 1
+        odig = oracle.fingerprint(other, chunk)
+        mask, cnt = oracle.diff(other, chunk, odig, dig)
+        brute = [int(not np.array_equal(d, other[i][o:o + chunk])) for i, o, d in pieces]
+        assert mask.tolist() == brute and cnt["ndirty"] == 3
+        allm, _ = oracle.diff(bufs, chunk, dig, None)
+        assert allm.all()
+        sel = allm.copy()
+        sel[[1, 2, 5, 11]] = 0           # a partial mask: entry index != chunk index
+        staging, man, cnt = oracle.compact(bufs, chunk, sel, dig)
+        want, entries, soff = [], [], 0
+        for k, (i, o, d) in enumerate(pieces):
+            if not sel[k]:
+                continue
+            pad = (-d.size) % 16
+            want.append(np.concatenate([d, np.zeros(pad, np.uint8)]))
+            entries.append((i, d.size, o, soff, int(dig[k])))
+            soff += d.size + pad
+        assert cnt["staged_bytes"] == soff and np.array_equal(staging, np.concatenate(want))
+        assert [(int(e["buf"]), int(e["len"]), int(e["buf_off"]), int(e["stage_off"]),
+                 int(e["digest"])) for e in man] == entries
+        staging, man, cnt = oracle.compact(bufs, chunk, allm, dig)
+        arenas = [np.full(b.size + 64, 0xEE, np.uint8) for b in bufs]
+        dst = [a[32:32 + b.size] for a, b in zip(arenas, bufs)]
+        assert oracle.restore(dst, chunk, staging, man) == 0
+        for a, d, b in zip(arenas, dst, bufs):
+            assert np.array_equal(d, b) and np.all(a[:32] == 0xEE) and np.all(a[32 + b.size:] == 0xEE)
+        return True
+    except AssertionError:
+        return False
+
+
+
+
+def use_library(path):
+    good = oracle._load()
+    other = ctypes.CDLL(path)
+    for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
+               "ora_compact", "ora_restore"):
+        getattr(other, fn).restype = getattr(good, fn).restype
+        getattr(other, fn).argtypes = getattr(good, fn).argtypes
+    oracle._lib = other
+
+
+if __name__ == "__main__":
+    if len(sys.argv) > 1:
+        use_library(sys.argv[1])
+    sys.exit(0 if pins_hold() else 1)
