@@ -71,6 +71,10 @@ def _load():
         lib.ora_diff.argtypes = [vp, u64, u64, vp, vp, vp, vp]
         lib.ora_compact.restype = None
         lib.ora_compact.argtypes = [vp, u64, u64, vp, vp, vp, u64, vp, u64, vp]
+        lib.ora_match.restype = ctypes.c_int
+        lib.ora_match.argtypes = [vp, u64, u64, vp, vp, u64, vp, vp, vp]
+        lib.ora_apply_matches.restype = u64
+        lib.ora_apply_matches.argtypes = [vp, u64, vp, u64, u64, vp]
         lib.ora_restore.restype = ctypes.c_uint64
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         _lib = lib
@@ -160,6 +164,41 @@ def compact(bufs: Sequence[np.ndarray], chunk: int, mask: np.ndarray, dig: np.nd
                         staging_cap, _p(manifest), manifest_cap, ctypes.byref(c))
     return staging, manifest, {"ndirty": c.ndirty, "staged_bytes": c.staged_bytes,
                                "overflow": c.overflow}
+
+
+class _MatchCounts(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in
+                ("nsame", "nmoved", "ndup", "nnew", "staged_bytes", "table_full")]
+
+
+def match(bufs: Sequence[np.ndarray], chunk: int, dig: np.ndarray,
+          ref: np.ndarray) -> Tuple[np.ndarray, np.ndarray, dict]:
+    """Content-addressed lookup of every snapshot checksum in the reference's
+    checksums (any geometry).  Returns (src int64[N], mask uint8[N], counts)."""
+    n = nchunks(bufs, chunk)
+    dig = np.ascontiguousarray(dig, dtype=np.uint64)
+    ref = np.ascontiguousarray(ref, dtype=np.uint64)
+    if dig.size != n:
+        raise ValueError("digest count does not match the buffer list")
+    src = np.zeros(n, dtype=np.int64)
+    mask = np.zeros(n, dtype=np.uint8)
+    c = _MatchCounts()
+    rc = _load().ora_match(_desc(bufs), len(bufs), chunk, _p(dig), _p(ref), ref.size, _p(src),
+                           _p(mask), ctypes.byref(c))
+    if rc != 0:
+        raise MemoryError("oracle: match scratch allocation failed")
+    return src, mask, {f: int(getattr(c, f)) for f, _ in _MatchCounts._fields_}
+
+
+def apply_matches(dst: List[np.ndarray], ref: Sequence[np.ndarray], chunk: int,
+                  src: np.ndarray) -> int:
+    """Copies matched chunks from ``ref`` and duplicates from ``dst`` itself
+    into ``dst`` (in place).  Returns the number of chunks skipped."""
+    src = np.ascontiguousarray(src, dtype=np.int64)
+    if src.size != nchunks(dst, chunk):
+        raise ValueError("src length does not match the destination geometry")
+    return int(_load().ora_apply_matches(_desc(dst), len(dst), _desc(ref), len(ref), chunk,
+                                         _p(src)))
 
 
 def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np.ndarray,

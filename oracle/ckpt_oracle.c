@@ -16,7 +16,10 @@
  *   - the swap-out of only the non-deduplicated data (sec. 5.2.1), here a
  *     gather into one contiguous staging area plus a manifest;
  *   - the swap-in / restore that puts the data back at the addresses it came
- *     from (sec. 4.5), here a scatter driven by the manifest.
+ *     from (sec. 4.5), here a scatter driven by the manifest;
+ *   - the paper's own content-addressed form of the comparison (sec. 5.2.1):
+ *     a checksum found at another position means a device-to-device move, not
+ *     a swap (ora_match, ora_apply_matches).
  *
  * Every function is the definition written out: one loop over buffers, one
  * over chunks, memcpy for copies.  No blocking, no fusion.  The only
@@ -26,7 +29,8 @@
  * Pins (tests/test_oracle_*.py): XXH64 vectors under tests/golden/, agreement
  * with the installed xxHash library and with a separate big-integer
  * implementation, brute-force byte comparison, prefix-sum and round-trip
- * invariants, NumPy closed forms for staging and manifest.
+ * invariants, NumPy closed forms for staging and manifest, pair-by-pair
+ * brute force for the content-addressed match.
  */
 #include <pthread.h>
 #include <stddef.h>
@@ -346,6 +350,138 @@ uint64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const
       continue;
     }
     memcpy((uint8_t *)dst[m->buf].ptr + m->buf_off, in + m->stage_off, m->len);
+  }
+  return rejected;
+}
+
+/* ------------------------------------------------- content-addressed match */
+/* The paper's own rule (sec. 5.2.1) looks a checksum up by content, wherever
+ * the buffer with that content lives; a hit at another address becomes a
+ * device-to-device move instead of a swap.  For every snapshot chunk k:
+ *   src[k] =  k            if the reference chunk at the same position has the
+ *                          same checksum (nothing to do),
+ *             j            else the lowest reference position j whose checksum
+ *                          equals dig[k] (content present elsewhere: move),
+ *             -2 - k0      else, if an earlier snapshot chunk has the same
+ *                          checksum, k0 being the first such chunk (a duplicate
+ *                          of a chunk that is itself new),
+ *             -1           else (new content: must be staged).
+ * mask[k] = 1 exactly for src[k] == -1.  The reference may have any number of
+ * chunks.  The lookup is done the plain way: sort (checksum, position) pairs,
+ * then binary-search the first pair with the wanted checksum. */
+
+typedef struct {
+  uint64_t nsame, nmoved, ndup, nnew, staged_bytes, table_full;
+} ora_match_counts_t;
+
+typedef struct {
+  uint64_t dig, pos;
+} ora_pair_t;
+
+static int pair_cmp(const void *a, const void *b) {
+  const ora_pair_t *x = (const ora_pair_t *)a, *y = (const ora_pair_t *)b;
+  if (x->dig != y->dig) return x->dig < y->dig ? -1 : 1;
+  if (x->pos != y->pos) return x->pos < y->pos ? -1 : 1;
+  return 0;
+}
+
+/* lowest position with checksum d in a sorted pair array, or -1 */
+static int64_t first_pos(const ora_pair_t *pairs, uint64_t n, uint64_t d) {
+  uint64_t lo = 0, hi = n;
+  while (lo < hi) {
+    uint64_t mid = lo + (hi - lo) / 2;
+    if (pairs[mid].dig < d) lo = mid + 1; else hi = mid;
+  }
+  return (lo < n && pairs[lo].dig == d) ? (int64_t)pairs[lo].pos : -1;
+}
+
+int ora_match(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, const uint64_t *dig,
+              const uint64_t *ref, uint64_t n_ref, int64_t *src, uint8_t *mask,
+              ora_match_counts_t *counts) {
+  uint64_t N = ora_nchunks(bufs, nbufs, chunk);
+  ora_pair_t *rp = (ora_pair_t *)malloc(sizeof(ora_pair_t) * (size_t)(n_ref ? n_ref : 1));
+  ora_pair_t *sp = (ora_pair_t *)malloc(sizeof(ora_pair_t) * (size_t)(N ? N : 1));
+  uint32_t *lens = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(N ? N : 1));
+  if (!rp || !sp || !lens) {
+    free(rp); free(sp); free(lens);
+    return -1;
+  }
+  for (uint64_t j = 0; j < n_ref; ++j) { rp[j].dig = ref[j]; rp[j].pos = j; }
+  for (uint64_t k = 0; k < N; ++k) { sp[k].dig = dig[k]; sp[k].pos = k; }
+  qsort(rp, (size_t)n_ref, sizeof(ora_pair_t), pair_cmp);
+  qsort(sp, (size_t)N, sizeof(ora_pair_t), pair_cmp);
+  ora_chunk_lens(bufs, nbufs, chunk, lens);
+  memset(counts, 0, sizeof(*counts));
+  for (uint64_t k = 0; k < N; ++k) {
+    int64_t s;
+    if (k < n_ref && ref[k] == dig[k]) {
+      s = (int64_t)k;
+      counts->nsame += 1;
+    } else {
+      int64_t j = first_pos(rp, n_ref, dig[k]);
+      if (j >= 0) {
+        s = j;
+        counts->nmoved += 1;
+      } else {
+        int64_t k0 = first_pos(sp, N, dig[k]); /* always found: at worst k itself */
+        if ((uint64_t)k0 < k) {
+          s = -2 - k0;
+          counts->ndup += 1;
+        } else {
+          s = -1;
+          counts->nnew += 1;
+          counts->staged_bytes += pad16(lens[k]);
+        }
+      }
+    }
+    src[k] = s;
+    mask[k] = (s == -1) ? 1 : 0;
+  }
+  free(rp); free(sp); free(lens);
+  return 0;
+}
+
+/* Rebuilds the snapshot's content in dst from what the match found, after the
+ * new chunks have been restored from staging: a matched chunk (src >= 0) is
+ * copied from chunk src[k] of the reference buffer list, a duplicate
+ * (src <= -2) from chunk -2 - src[k] of dst itself.  New chunks (src == -1)
+ * are left alone.  A chunk whose source does not exist or has another length
+ * is skipped and counted in the return value.  ref and dst must not overlap
+ * in memory unless every match is in place. */
+static int chunk_addr(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk, uint64_t k,
+                      uint8_t **ptr, uint64_t *len) {
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = chunks_of(bufs[i].nbytes, chunk);
+    if (k < n) {
+      uint64_t off = k * chunk, l = bufs[i].nbytes - off;
+      *ptr = (uint8_t *)bufs[i].ptr + off;
+      *len = l > chunk ? chunk : l;
+      return 1;
+    }
+    k -= n;
+  }
+  return 0;
+}
+
+uint64_t ora_apply_matches(const ora_buf_t *dst, uint64_t ndst, const ora_buf_t *ref,
+                           uint64_t nref, uint64_t chunk, const int64_t *src) {
+  uint64_t N = ora_nchunks(dst, ndst, chunk), rejected = 0;
+  for (int pass = 0; pass < 2; ++pass) { /* pass 0: from the reference, pass 1: duplicates */
+    for (uint64_t k = 0; k < N; ++k) {
+      int64_t s = src[k];
+      if (s == -1 || (pass == 0) != (s >= 0)) continue;
+      uint8_t *to, *from;
+      uint64_t tlen, flen;
+      chunk_addr(dst, ndst, chunk, k, &to, &tlen);
+      int ok = pass == 0 ? chunk_addr(ref, nref, chunk, (uint64_t)s, &from, &flen)
+                         : ((uint64_t)(-2 - s) < k &&
+                            chunk_addr(dst, ndst, chunk, (uint64_t)(-2 - s), &from, &flen));
+      if (!ok || flen != tlen) {
+        rejected += 1;
+        continue;
+      }
+      if (from != to) memmove(to, from, tlen);
+    }
   }
   return rejected;
 }
