@@ -49,9 +49,10 @@ typedef enum ckpt_status {
   CKPT_OK = 0,
   CKPT_ERR_INVALID_ARG = -1, /* NULL where a pointer is required, size overflow */
   CKPT_ERR_ALIGNMENT = -2,   /* a buffer / staging / digest / manifest pointer is misaligned */
-  CKPT_ERR_CHUNK = -3,       /* chunk size not a power of two in [256 B, 1 GiB] */
+  CKPT_ERR_CHUNK = -3,       /* chunk size not a power of two in [256 B, 1 GiB], or two plans differ */
   CKPT_ERR_GEOMETRY = -4,    /* reference digest count differs from the plan's N */
-  CKPT_ERR_CAPACITY = -5,    /* reserved for callers that turn counts.overflow into a status */
+  CKPT_ERR_CAPACITY = -5,    /* workspace too small (ckpt_match); also free for callers that turn
+                                counts.overflow into a status */
   CKPT_ERR_DEVICE = -6,      /* a HIP call failed (see ckpt_last_device_error) */
   CKPT_ERR_NOMEM = -7        /* host or device allocation failed in ckpt_plan_create */
 } ckpt_status;
@@ -160,6 +161,54 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
 int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,
                  const ckpt_entry_t *d_manifest, uint64_t nentries, uint64_t *d_rejected,
                  void *stream);
+
+/* ---- content-addressed comparison (the paper's own rule) ------------------- */
+
+/* Sec. 5.2.1 looks a checksum up by content wherever it lives: a hit at the same
+ * address needs nothing, a hit at another address becomes a device-to-device
+ * move, only a miss is swapped.  ckpt_match does that lookup for every chunk of
+ * the snapshot against the reference's digests (any geometry, n_ref chunks) and
+ * against the snapshot itself:
+ *   d_src[k] =  k         if k < n_ref and d_ref[k] == d_digests[k]   (same place)
+ *               j >= 0    else the lowest j with d_ref[j] == d_digests[k] (moved)
+ *               -2 - k0   else, if an earlier snapshot chunk has the same digest,
+ *                         k0 being the first such chunk        (duplicate of new data)
+ *               -1        else                                  (new: must be staged)
+ *   d_mask[k] = 1 exactly when d_src[k] == -1, so ckpt_compact(d_mask) stages the
+ *   new chunks only;  d_counts receives how many chunks fell in each class and
+ *   the staging bytes the new ones need.
+ *   d_workspace  device scratch of at least ckpt_match_workspace_bytes(n_ref, N)
+ *                bytes, 16-byte aligned; contents are overwritten
+ *   d_src        device array of N int64;  d_mask  device array of N bytes
+ * table_full in the counts stays 0 (the tables are sized so that every insert
+ * finds a slot); a non-zero value means the result must not be used.
+ * Errors: INVALID_ARG, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
+typedef struct ckpt_match_counts {
+  uint64_t nsame, nmoved, ndup, nnew; /* chunks per class; they sum to N */
+  uint64_t staged_bytes;              /* sum of pad16(len) over the new chunks */
+  uint64_t table_full;                /* inserts that found no slot (always 0) */
+} ckpt_match_counts_t;
+
+uint64_t ckpt_match_workspace_bytes(uint64_t n_ref, uint64_t nchunks);
+
+int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t *d_ref,
+               uint64_t n_ref, void *d_workspace, uint64_t workspace_bytes, int64_t *d_src,
+               uint8_t *d_mask, ckpt_match_counts_t *d_counts, void *stream);
+
+/* Puts the matched content into dst_plan's buffers (the device-to-device move of
+ * sec. 5.2.1): a chunk with d_src[k] >= 0 is copied from chunk d_src[k] of
+ * ref_plan's buffers, then a chunk with d_src[k] <= -2 from chunk -2 - d_src[k]
+ * of dst_plan itself (so the new chunks must already have been restored from
+ * staging on the same stream).  Chunks with -1 are not touched; a copy whose
+ * source and destination address coincide is skipped.  A chunk whose source
+ * does not exist, is not earlier (duplicates), or has another length is skipped
+ * and counted in *d_rejected (optional, device uint64).
+ * ref_plan's buffers must not overlap dst_plan's unless every match is in place
+ * (moves inside one memory image would need the phased copy the paper
+ * describes; not provided).  d_src must come from ckpt_match.
+ * Errors: INVALID_ARG, CHUNK (the plans' chunk sizes differ), ALIGNMENT, DEVICE. */
+int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
+                       const int64_t *d_src, uint64_t *d_rejected, void *stream);
 
 /* ---- helpers -------------------------------------------------------------- */
 

@@ -26,7 +26,7 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
+    "ckpt_restore", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
 )
 
@@ -76,6 +76,12 @@ def _lib():
         lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore.restype = ci
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_match_workspace_bytes.restype = u64
+        lib.ckpt_match_workspace_bytes.argtypes = [u64, u64]
+        lib.ckpt_match.restype = ci
+        lib.ckpt_match.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp, vp]
+        lib.ckpt_apply_matches.restype = ci
+        lib.ckpt_apply_matches.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_bw_copy.restype = ci
         lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
         lib.ckpt_bw_read.restype = ci
@@ -189,6 +195,30 @@ def restore(dst_plan: Plan, staging, staging_bytes: int, manifest, nentries: int
     """``ckpt_restore``: scatter the first nentries manifest entries into dst_plan's buffers."""
     _check(_lib().ckpt_restore(dst_plan._h, _ptr(staging), staging_bytes, _ptr(manifest), nentries,
                                _ptr(rejected), _stream(stream)), "ckpt_restore")
+
+
+MATCH_COUNT_FIELDS = ("nsame", "nmoved", "ndup", "nnew", "staged_bytes", "table_full")
+
+
+def match_workspace_bytes(n_ref: int, nchunks: int) -> int:
+    return int(_lib().ckpt_match_workspace_bytes(n_ref, nchunks))
+
+
+def match(plan: Plan, digests, ref, workspace, src, mask, counts, stream=None,
+          n_ref: Optional[int] = None) -> None:
+    """``ckpt_match``: src (int64, N), mask (uint8, N), counts (6 x int64) from a
+    content-addressed lookup of digests in ref (any length); workspace is a uint8 tensor."""
+    if n_ref is None:
+        n_ref = 0 if ref is None else ref.numel()
+    _check(_lib().ckpt_match(plan._h, _ptr(digests), _ptr(ref), n_ref, _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _ptr(src), _ptr(mask),
+                             _ptr(counts), _stream(stream)), "ckpt_match")
+
+
+def apply_matches(dst_plan: Plan, ref_plan: Plan, src, rejected=None, stream=None) -> None:
+    """``ckpt_apply_matches``: device-to-device moves of the matched chunks into dst_plan."""
+    _check(_lib().ckpt_apply_matches(dst_plan._h, ref_plan._h, _ptr(src), _ptr(rejected),
+                                     _stream(stream)), "ckpt_apply_matches")
 
 
 def bw_copy(dst, src, nbytes: int, stream=None) -> None:

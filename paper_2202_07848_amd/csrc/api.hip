@@ -293,6 +293,39 @@ int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t st
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+uint64_t ckpt_match_workspace_bytes(uint64_t n_ref, uint64_t nchunks) {
+  return ckpt::match_workspace_bytes(n_ref, nchunks);
+}
+
+int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t *d_ref,
+               uint64_t n_ref, void *d_workspace, uint64_t workspace_bytes, int64_t *d_src,
+               uint8_t *d_mask, ckpt_match_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && (d_digests == nullptr || d_src == nullptr || d_mask == nullptr))
+    return CKPT_ERR_INVALID_ARG;
+  if (n_ref != 0 && d_ref == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (n_ref > (1ull << 40)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_digests, 8) || !aligned(d_ref, 8) || !aligned(d_workspace, 16) ||
+      !aligned(d_src, 8) || !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  if (workspace_bytes < ckpt::match_workspace_bytes(n_ref, n)) return CKPT_ERR_CAPACITY;
+  hipError_t e = ckpt::launch_match(plan->dev, d_digests, d_ref, n_ref, d_workspace, d_src, d_mask,
+                                    d_counts, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
+                       const int64_t *d_src, uint64_t *d_rejected, void *stream) {
+  if (dst_plan == nullptr || ref_plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (dst_plan->dev.nchunks != 0 && d_src == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (dst_plan->chunk != ref_plan->chunk) return CKPT_ERR_CHUNK;
+  if (!aligned(d_src, 8) || !aligned(d_rejected, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_apply_matches(dst_plan->dev, ref_plan->dev, d_src, d_rejected,
+                                            static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream) {
   if (nbytes == 0) return CKPT_OK;
   if (d_dst == nullptr || d_src == nullptr || (nbytes & 15) != 0) return CKPT_ERR_INVALID_ARG;
@@ -314,7 +347,7 @@ const char *ckpt_strerror(int status) {
     case CKPT_OK: return "ok";
     case CKPT_ERR_INVALID_ARG: return "invalid argument";
     case CKPT_ERR_ALIGNMENT: return "pointer not aligned as required";
-    case CKPT_ERR_CHUNK: return "chunk size must be a power of two in [256, 2^30]";
+    case CKPT_ERR_CHUNK: return "chunk size must be a power of two in [256, 2^30] (and equal between plans)";
     case CKPT_ERR_GEOMETRY: return "reference digests have a different chunk geometry";
     case CKPT_ERR_CAPACITY: return "staging or manifest capacity exceeded";
     case CKPT_ERR_DEVICE: return "HIP call failed";
@@ -325,6 +358,6 @@ const char *ckpt_strerror(int status) {
 
 int ckpt_last_device_error(void) { return g_last_hip_error; }
 
-int ckpt_version(void) { return 1000 * 0 + 1; }
+int ckpt_version(void) { return 1000 * 0 + 2; }
 
 }  // extern "C"

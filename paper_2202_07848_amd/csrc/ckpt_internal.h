@@ -97,6 +97,12 @@ hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint6
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
                           hipStream_t s);
+uint64_t match_workspace_bytes(uint64_t n_ref, uint64_t n);
+hipError_t launch_match(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
+                        uint64_t n_ref, void *d_workspace, int64_t *d_src, uint8_t *d_mask,
+                        ckpt_match_counts_t *d_counts, hipStream_t s);
+hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev &refp, const int64_t *d_src,
+                                uint64_t *d_rejected, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
 

@@ -1,0 +1,130 @@
+"""GPU parity of the content-addressed match and of the moves it implies
+(paper sec. 5.2.1) against the oracle: src, mask and counts bit-exact, and the
+snapshot rebuilt from staging + reference + duplicates byte for byte."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_07848_amd import binding as ck
+from gpu_util import DeviceBuffers, run_compact, run_fingerprint, u64
+from test_oracle_match import make_case
+
+pytestmark = pytest.mark.gpu
+
+
+def run_match(plan, dig, ref, n_ref):
+    n = plan.nchunks
+    ws = torch.empty(ck.match_workspace_bytes(n_ref, n), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x3C)                                     # the call must initialise its tables itself
+    src = torch.full((max(1, n),), 12345, dtype=torch.int64, device="cuda")
+    mask = torch.full((max(1, n),), 0x77, dtype=torch.uint8, device="cuda")
+    counts = torch.full((6,), -1, dtype=torch.int64, device="cuda")
+    ck.match(plan, dig, ref, ws, src, mask, counts, n_ref=n_ref)
+    torch.cuda.synchronize()
+    c = counts.cpu().numpy().view(np.uint64)
+    return src, mask, {f: int(v) for f, v in zip(ck.MATCH_COUNT_FIELDS, c)}
+
+
+@pytest.mark.parametrize("chunk", [256, 4096])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_match_and_rebuild(chunk, seed):
+    rng = np.random.default_rng(seed)
+    ref, snap = make_case(rng, chunk)
+    d_ref, d_snap = DeviceBuffers(ref, chunk), DeviceBuffers(snap, chunk)
+    rdig, sdig = run_fingerprint(d_ref.plan), run_fingerprint(d_snap.plan)
+    n, n_ref = d_snap.plan.nchunks, d_ref.plan.nchunks
+    o_rdig, o_sdig = oracle.fingerprint(ref, chunk), oracle.fingerprint(snap, chunk)
+    assert np.array_equal(u64(sdig, n), o_sdig) and np.array_equal(u64(rdig, n_ref), o_rdig)
+
+    want_src, want_mask, want_cnt = oracle.match(snap, chunk, o_sdig, o_rdig)
+    src, mask, cnt = run_match(d_snap.plan, sdig, rdig, n_ref)
+    assert np.array_equal(src[:n].cpu().numpy(), want_src)
+    assert np.array_equal(mask[:n].cpu().numpy(), want_mask)
+    assert cnt == want_cnt and cnt["nmoved"] >= 3 and cnt["ndup"] >= 2
+
+    # stage the new chunks only, then rebuild the snapshot in a garbage-filled destination
+    want_st, want_man, _ = oracle.compact(snap, chunk, want_mask, o_sdig)
+    staging, manifest, _ = run_compact(d_snap.plan, mask, sdig, want_st.size, want_man.size)
+    assert np.array_equal(staging.cpu().numpy()[:want_st.size], want_st)
+    garbage = [np.full(b.size, 0x5C, dtype=np.uint8) for b in snap]
+    dst = DeviceBuffers(garbage, chunk)
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ck.restore(dst.plan, staging, want_st.size, manifest, want_man.size)
+    ck.apply_matches(dst.plan, d_ref.plan, src, rejected)
+    torch.cuda.synchronize()
+    assert int(rejected.item()) == 0
+    want_dst = [g.copy() for g in garbage]
+    assert oracle.restore(want_dst, chunk, want_st, want_man) == 0
+    assert oracle.apply_matches(want_dst, ref, chunk, want_src) == 0
+    got, img = dst.host()
+    for g, w, s in zip(got, want_dst, snap):
+        assert np.array_equal(g, w) and np.array_equal(g, s)
+    assert dst.canaries_intact(img) and d_ref.canaries_intact() and d_snap.canaries_intact()
+
+
+@pytest.mark.parametrize("n,n_ref,domain", [(5000, 5000, 40), (3000, 7000, 1 << 62), (4097, 0, 9),
+                                            (1, 1, 2), (20000, 20000, 3000)])
+def test_match_on_synthetic_digests(n, n_ref, domain):
+    """Digest arrays chosen freely (the lookup never reads chunk bytes): tiny key
+    domains force long probe chains and many duplicates; the all-ones digest,
+    which doubles as the empty-slot marker inside the tables, must still work."""
+    rng = np.random.default_rng(n + n_ref)
+    chunk = 256
+    host = [np.zeros(n * chunk - 100, dtype=np.uint8)]        # n chunks, the last one short
+    dev = DeviceBuffers(host, chunk)
+    assert dev.plan.nchunks == n
+    dig = rng.integers(0, domain, size=n, dtype=np.uint64)
+    ref = rng.integers(0, domain, size=n_ref, dtype=np.uint64)
+    ones = np.uint64(0xFFFFFFFFFFFFFFFF)
+    dig[rng.integers(0, n, size=max(1, n // 50))] = ones
+    if n_ref:
+        ref[rng.integers(0, n_ref, size=max(1, n_ref // 70))] = ones
+        same = rng.integers(0, min(n, n_ref), size=min(n, n_ref) // 3)
+        dig[same] = ref[same]                                 # plenty of same-place hits
+    want_src, want_mask, want_cnt = oracle.match(host, chunk, dig, ref)
+    d_dig = torch.from_numpy(dig.view(np.int64)).cuda()
+    d_ref = torch.from_numpy(ref.view(np.int64)).cuda() if n_ref else None
+    src, mask, cnt = run_match(dev.plan, d_dig, d_ref, n_ref)
+    assert np.array_equal(src[:n].cpu().numpy(), want_src)
+    assert np.array_equal(mask[:n].cpu().numpy(), want_mask)
+    assert cnt == want_cnt
+
+
+def test_match_without_reference_keeps_first_occurrences_only():
+    chunk = 256
+    a, b = np.full(chunk, 1, np.uint8), np.full(chunk, 2, np.uint8)
+    snap = [np.concatenate([a, b, a, a, b]), np.zeros(0, np.uint8), np.concatenate([b, a[:40]])]
+    dev = DeviceBuffers(snap, chunk)
+    dig = run_fingerprint(dev.plan)
+    src, mask, cnt = run_match(dev.plan, dig, None, 0)
+    assert src[:7].cpu().numpy().tolist() == [-1, -1, -2, -2, -3, -3, -1]
+    assert cnt["nnew"] == 3 and cnt["ndup"] == 4 and cnt["staged_bytes"] == 256 + 256 + 48
+
+
+def test_apply_matches_rejects_impossible_sources_and_checks_arguments():
+    chunk = 256
+    ref = [(np.arange(512) % 251).astype(np.uint8)]
+    d_ref = DeviceBuffers(ref, chunk)
+    dst_host = [np.zeros(600, dtype=np.uint8)]
+    dst = DeviceBuffers(dst_host, chunk)
+    src = np.array([5, 1, -2 - 2], dtype=np.int64)
+    want = [b.copy() for b in dst_host]
+    want_rej = oracle.apply_matches(want, ref, chunk, src)
+    rejected = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ck.apply_matches(dst.plan, d_ref.plan, torch.from_numpy(src).cuda(), rejected)
+    torch.cuda.synchronize()
+    assert int(rejected.item()) == want_rej == 2
+    got, img = dst.host()
+    assert np.array_equal(got[0], want[0]) and dst.canaries_intact(img)
+    other = DeviceBuffers(ref, 512)
+    with pytest.raises(ck.CkptError) as e:
+        ck.apply_matches(dst.plan, other.plan, torch.from_numpy(src).cuda())
+    assert e.value.status == -3
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    dig = run_fingerprint(dst.plan)
+    with pytest.raises(ck.CkptError) as e:
+        ck.match(dst.plan, dig, dig, small, torch.zeros(3, dtype=torch.int64, device="cuda"),
+                 torch.zeros(3, dtype=torch.uint8, device="cuda"),
+                 torch.zeros(6, dtype=torch.int64, device="cuda"))
+    assert e.value.status == -5
