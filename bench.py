@@ -45,6 +45,10 @@ def parse_args():
     ap.add_argument("--dirty", type=float, default=0.10, help="config 3: rewritten chunk fraction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=8.0)
+    ap.add_argument("--match", action="store_true",
+                    help="config 3 only: also run the content-addressed match on a snapshot whose "
+                         "buffer list is rotated by one (every unchanged chunk sits at another "
+                         "position), and the device-to-device moves that rebuild it")
     ap.add_argument("--calibrate", action="store_true",
                     help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
                          "the known-size dispatches that scale the rocprofv3 byte counters)")
@@ -110,6 +114,65 @@ def cpu_baseline(w, rep_ref, rep_new, sample_bytes, torch):
                   f"{hashed / 2**30:.2f} GiB fingerprinted, {cnt2['staged_bytes'] / 2**30:.2f} GiB "
                   f"staged, {dt:.2f} s wall (fingerprint on {threads} threads, rest on one)",
     }, (idx, dig, mask)
+
+
+def content_addressed_leg(w, t0, t1, ref, ck, torch, np, steps):
+    """Snapshot = t1's bytes described by a buffer list rotated by one buffer, so the
+    positional diff against t0 finds almost nothing while every unchanged chunk is
+    still present in t0 at another position.  Times ckpt_match, then rebuilds the
+    snapshot in a fresh arena from staging + moves and checks it byte for byte."""
+    dev = t1.arena.device
+    order = list(range(1, len(w.bufs))) + [0]
+    base1 = t1.arena.data_ptr()
+    rot = ck.Plan([(base1 + int(t1.offs[i]), w.bufs[i].nbytes) for i in order], w.chunk)
+    n = rot.nchunks
+    dig = torch.zeros(n, dtype=torch.int64, device=dev)
+    mask = torch.zeros(n, dtype=torch.uint8, device=dev)
+    pmask = torch.zeros(n, dtype=torch.uint8, device=dev)
+    src = torch.zeros(n, dtype=torch.int64, device=dev)
+    cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+    mcnt = torch.zeros(6, dtype=torch.int64, device=dev)
+    ws = torch.empty(ck.match_workspace_bytes(n, n), dtype=torch.uint8, device=dev)
+    ck.fingerprint(rot, dig)
+    ck.diff(rot, dig, ref, pmask, cnt)
+    ck.match(rot, dig, ref, ws, src, mask, mcnt)
+    torch.cuda.synchronize()
+    positional = cnt.cpu().numpy().view(np.uint64)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        ck.match(rot, dig, ref, ws, src, mask, mcnt)
+    e1.record()
+    torch.cuda.synchronize()
+    match_ms = e0.elapsed_time(e1) / steps
+    m = dict(zip(ck.MATCH_COUNT_FIELDS, (int(v) for v in mcnt.cpu().numpy().view(np.uint64))))
+    staging = torch.empty(max(16, m["staged_bytes"]), dtype=torch.uint8, device=dev)
+    manifest = torch.empty(max(1, m["nnew"]) * 32, dtype=torch.uint8, device=dev)
+    ck.compact(rot, mask, dig, staging, manifest, cnt, staging_cap=m["staged_bytes"],
+               manifest_cap=m["nnew"])
+    fresh = torch.full_like(t1.arena, 0x5C)
+    dst = ck.Plan([(fresh.data_ptr() + int(t1.offs[i]), w.bufs[i].nbytes) for i in order], w.chunk)
+    rej = torch.zeros(1, dtype=torch.int64, device=dev)
+    torch.cuda.synchronize()
+    e0.record()
+    ck.restore(dst, staging, m["staged_bytes"], manifest, m["nnew"])
+    ck.apply_matches(dst, t0.plan, src, rej)
+    e1.record()
+    torch.cuda.synchronize()
+    rebuild_ms = e0.elapsed_time(e1)
+    assert int(rej.item()) == 0 and m["table_full"] == 0
+    assert torch.equal(fresh, t1.arena), "content-addressed rebuild differs from the snapshot"
+    moved_bytes = w.nbytes - m["staged_bytes"]
+    return {
+        "chunks": n, "match_ms": round(match_ms, 3),
+        "match_Mchunks_per_s": round(n / match_ms / 1e3, 1),
+        "classes": {k: m[k] for k in ("nsame", "nmoved", "ndup", "nnew")},
+        "staged_bytes_content_addressed": m["staged_bytes"],
+        "staged_bytes_positional": int(positional[1]),
+        "rebuild_ms": round(rebuild_ms, 3),
+        "rebuild_GBps_read_plus_write": round(2 * w.nbytes / rebuild_ms / 1e6, 1),
+        "moved_or_duplicated_bytes": moved_bytes, "rebuild_matches_snapshot": True,
+    }
 
 
 def main():
@@ -287,6 +350,10 @@ def main():
             cal[name] = {"bytes": nb, "ms": round(ms, 3),
                          "GBps": round((2 if name == "copy" else 1) * nb / ms / 1e6, 1)}
         out["calibration"] = cal
+
+    if args.match and w.nreplicas == 1:
+        out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,
+                                                         np, args.steps)
 
     if not args.no_cpu_baseline:
         base, (idx, o_dig, o_mask) = cpu_baseline(w, pairs[0][0], pairs[0][1],

@@ -65,12 +65,18 @@ __global__ __launch_bounds__(256) void k_match_insert(Table t, const uint64_t *_
     atomicMin(t.lone, (unsigned long long)j);
     return;
   }
+  // Heavily repeated digests (all-zero chunks: one key for a fifth of a fragmented
+  // heap) would serialise on one slot, so look before touching it: values only
+  // ever decrease, hence a value already <= j, however stale, proves there is
+  // nothing left for this thread to do.  Loads go to L2 (agent scope).
   uint64_t s = slot_of(d, t.cap_mask);
   for (uint64_t tries = 0; tries <= t.cap_mask; ++tries) {
-    const unsigned long long old = atomicCAS(&t.keys[s], (unsigned long long)EMPTY,
-                                             (unsigned long long)d);
-    if (old == EMPTY || old == d) {
-      atomicMin(&t.vals[s], (unsigned long long)j);
+    unsigned long long key = __hip_atomic_load(&t.keys[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (key == EMPTY)
+      key = atomicCAS(&t.keys[s], (unsigned long long)EMPTY, (unsigned long long)d);
+    if (key == EMPTY || key == d) {
+      if (__hip_atomic_load(&t.vals[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > j)
+        atomicMin(&t.vals[s], (unsigned long long)j);
       return;
     }
     s = (s + 1) & t.cap_mask;
