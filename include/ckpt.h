@@ -210,6 +210,27 @@ int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_
 int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
                        const int64_t *d_src, uint64_t *d_rejected, void *stream);
 
+/* ---- squashing validation -------------------------------------------------- */
+
+/* Sec. 5.2.3 validates operation squashing by inferring mutations from
+ * checksums: what a rank changed between two points is the set of chunks whose
+ * digest changed, and two ranks sharing the GPU may be squashed only if their
+ * mutations are identical in address, checksum and size.  All four arrays are
+ * fingerprints over ONE plan geometry (same addresses by consistent allocation,
+ * hence same sizes), so the rule per chunk k is
+ *   changed_a(k) == changed_b(k)  and, where changed,  after_a[k] == after_b[k]
+ * with changed_x(k) = (before_x[k] != after_x[k]).
+ * d_result receives { chunks a changed, chunks b changed, chunks that break the
+ * rule (0 = squashing is safe), lowest such chunk id or UINT64_MAX }.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+typedef struct ckpt_validation {
+  uint64_t changed_a, changed_b, mismatches, first_mismatch;
+} ckpt_validation_t;
+
+int ckpt_validate_mutations(const ckpt_plan_t *plan, const uint64_t *d_before_a,
+                            const uint64_t *d_after_a, const uint64_t *d_before_b,
+                            const uint64_t *d_after_b, ckpt_validation_t *d_result, void *stream);
+
 /* ---- helpers -------------------------------------------------------------- */
 
 /* Plain streaming kernels used to calibrate HBM counters and the achievable

@@ -75,6 +75,8 @@ def _load():
         lib.ora_match.argtypes = [vp, u64, u64, vp, vp, u64, vp, vp, vp]
         lib.ora_apply_matches.restype = u64
         lib.ora_apply_matches.argtypes = [vp, u64, vp, u64, u64, vp]
+        lib.ora_validate_mutations.restype = None
+        lib.ora_validate_mutations.argtypes = [u64, vp, vp, vp, vp, vp]
         lib.ora_restore.restype = ctypes.c_uint64
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         _lib = lib
@@ -199,6 +201,17 @@ def apply_matches(dst: List[np.ndarray], ref: Sequence[np.ndarray], chunk: int,
         raise ValueError("src length does not match the destination geometry")
     return int(_load().ora_apply_matches(_desc(dst), len(dst), _desc(ref), len(ref), chunk,
                                          _p(src)))
+
+
+def validate_mutations(before_a, after_a, before_b, after_b) -> dict:
+    """Squashing validation over four checksum arrays of one geometry."""
+    arrs = [np.ascontiguousarray(x, dtype=np.uint64) for x in (before_a, after_a, before_b, after_b)]
+    if len({a.size for a in arrs}) != 1:
+        raise ValueError("the four checksum arrays must have one length")
+    res = np.zeros(4, dtype=np.uint64)
+    _load().ora_validate_mutations(arrs[0].size, *[_p(a) for a in arrs], _p(res))
+    return {"changed_a": int(res[0]), "changed_b": int(res[1]), "mismatches": int(res[2]),
+            "first_mismatch": int(res[3])}
 
 
 def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np.ndarray,

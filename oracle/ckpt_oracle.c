@@ -485,3 +485,32 @@ uint64_t ora_apply_matches(const ora_buf_t *dst, uint64_t ndst, const ora_buf_t 
   }
   return rejected;
 }
+
+/* ----------------------------------------------------- mutation validation */
+/* Squashing validation (sec. 5.2.3): the mutations a rank performed between
+ * two points are the chunks whose checksum changed; two ranks sharing a GPU
+ * may be squashed only if their mutations are identical in address, checksum
+ * and size.  With one chunk geometry for both ranks (same addresses by the
+ * consistent allocation of sec. 5.2.2, hence same sizes) that is, for every
+ * chunk k:  changed_a(k) == changed_b(k), and where changed, the new checksums
+ * are equal.  result = { chunks rank a changed, chunks rank b changed, chunks
+ * that break the rule, lowest such chunk or all-ones }. */
+void ora_validate_mutations(uint64_t nchunks, const uint64_t *before_a, const uint64_t *after_a,
+                            const uint64_t *before_b, const uint64_t *after_b,
+                            uint64_t result[4]) {
+  uint64_t na = 0, nb = 0, bad = 0, first = ~(uint64_t)0;
+  for (uint64_t k = 0; k < nchunks; ++k) {
+    int ca = before_a[k] != after_a[k];
+    int cb = before_b[k] != after_b[k];
+    na += (uint64_t)ca;
+    nb += (uint64_t)cb;
+    if (ca != cb || (ca && after_a[k] != after_b[k])) {
+      bad += 1;
+      if (first == ~(uint64_t)0) first = k;
+    }
+  }
+  result[0] = na;
+  result[1] = nb;
+  result[2] = bad;
+  result[3] = first;
+}

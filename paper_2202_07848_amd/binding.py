@@ -26,7 +26,8 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
+    "ckpt_restore", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_validate_mutations",
+    "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
 )
 
@@ -82,6 +83,8 @@ def _lib():
         lib.ckpt_match.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp, vp]
         lib.ckpt_apply_matches.restype = ci
         lib.ckpt_apply_matches.argtypes = [vp, vp, vp, vp, vp]
+        lib.ckpt_validate_mutations.restype = ci
+        lib.ckpt_validate_mutations.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.ckpt_bw_copy.restype = ci
         lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
         lib.ckpt_bw_read.restype = ci
@@ -219,6 +222,17 @@ def apply_matches(dst_plan: Plan, ref_plan: Plan, src, rejected=None, stream=Non
     """``ckpt_apply_matches``: device-to-device moves of the matched chunks into dst_plan."""
     _check(_lib().ckpt_apply_matches(dst_plan._h, ref_plan._h, _ptr(src), _ptr(rejected),
                                      _stream(stream)), "ckpt_apply_matches")
+
+
+VALIDATION_FIELDS = ("changed_a", "changed_b", "mismatches", "first_mismatch")
+
+
+def validate_mutations(plan: Plan, before_a, after_a, before_b, after_b, result,
+                       stream=None) -> None:
+    """``ckpt_validate_mutations``: result (4 x int64) from four digest arrays of plan's geometry."""
+    _check(_lib().ckpt_validate_mutations(plan._h, _ptr(before_a), _ptr(after_a), _ptr(before_b),
+                                          _ptr(after_b), _ptr(result), _stream(stream)),
+           "ckpt_validate_mutations")
 
 
 def bw_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -326,6 +326,22 @@ int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+int ckpt_validate_mutations(const ckpt_plan_t *plan, const uint64_t *d_before_a,
+                            const uint64_t *d_after_a, const uint64_t *d_before_b,
+                            const uint64_t *d_after_b, ckpt_validation_t *d_result, void *stream) {
+  if (plan == nullptr || d_result == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && (d_before_a == nullptr || d_after_a == nullptr || d_before_b == nullptr ||
+                 d_after_b == nullptr))
+    return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_before_a, 8) || !aligned(d_after_a, 8) || !aligned(d_before_b, 8) ||
+      !aligned(d_after_b, 8) || !aligned(d_result, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_validate(n, d_before_a, d_after_a, d_before_b, d_after_b, d_result,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream) {
   if (nbytes == 0) return CKPT_OK;
   if (d_dst == nullptr || d_src == nullptr || (nbytes & 15) != 0) return CKPT_ERR_INVALID_ARG;

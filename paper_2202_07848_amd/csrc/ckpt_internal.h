@@ -97,6 +97,8 @@ hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint6
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
                           hipStream_t s);
+hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a, const uint64_t *b_b,
+                           const uint64_t *a_b, ckpt_validation_t *d_result, hipStream_t s);
 uint64_t match_workspace_bytes(uint64_t n_ref, uint64_t n);
 hipError_t launch_match(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
                         uint64_t n_ref, void *d_workspace, int64_t *d_src, uint8_t *d_mask,

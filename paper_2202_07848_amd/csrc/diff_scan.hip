@@ -56,14 +56,6 @@ __device__ Pair block_exclusive_scan(Pair v, Pair *total) {
   return excl;
 }
 
-// Per-thread view of SCAN_PER_THREAD consecutive chunks.
-struct Quad {
-  uint64_t k0;
-  int n;                          // valid chunks (0..SCAN_PER_THREAD)
-  uint8_t m[SCAN_PER_THREAD];
-  ChunkRef ref[SCAN_PER_THREAD];
-};
-
 __device__ __forceinline__ uint64_t thread_first_chunk() {
   return (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
 }
@@ -200,6 +192,50 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
                         (unsigned long long)missed);
 }
 
+// Squashing validation (paper sec. 5.2.3): per chunk, did rank a and rank b
+// change it alike?  Counters are zeroed by k_validate_init on the same stream.
+__global__ void k_validate_init(ckpt_validation_t *r) {
+  r->changed_a = r->changed_b = r->mismatches = 0;
+  r->first_mismatch = ~0ull;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_validate(uint64_t n,
+                                                           const uint64_t *__restrict__ b_a,
+                                                           const uint64_t *__restrict__ a_a,
+                                                           const uint64_t *__restrict__ b_b,
+                                                           const uint64_t *__restrict__ a_b,
+                                                           ckpt_validation_t *__restrict__ r) {
+  uint32_t ca = 0, cb = 0, bad = 0;
+  uint64_t first = ~0ull;
+  const uint64_t stride = (uint64_t)gridDim.x * SCAN_THREADS;
+  for (uint64_t k = (uint64_t)blockIdx.x * SCAN_THREADS + threadIdx.x; k < n; k += stride) {
+    const uint64_t after_a = a_a[k], after_b = a_b[k];
+    const bool xa = b_a[k] != after_a, xb = b_b[k] != after_b;
+    ca += xa;
+    cb += xb;
+    if (xa != xb || (xa && after_a != after_b)) {
+      bad += 1;
+      if (k < first) first = k;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    ca += __shfl_down(ca, o, 64);
+    cb += __shfl_down(cb, o, 64);
+    bad += __shfl_down(bad, o, 64);
+    const uint64_t f = __shfl_down(first, o, 64);
+    first = f < first ? f : first;
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (ca) atomicAdd(reinterpret_cast<unsigned long long *>(&r->changed_a), (unsigned long long)ca);
+    if (cb) atomicAdd(reinterpret_cast<unsigned long long *>(&r->changed_b), (unsigned long long)cb);
+    if (bad) {
+      atomicAdd(reinterpret_cast<unsigned long long *>(&r->mismatches), (unsigned long long)bad);
+      atomicMin(reinterpret_cast<unsigned long long *>(&r->first_mismatch),
+                (unsigned long long)first);
+    }
+  }
+}
+
 inline uint32_t scan_blocks(uint64_t nchunks) {
   return (uint32_t)((nchunks + SCAN_BLOCK - 1) / SCAN_BLOCK);
 }
@@ -215,6 +251,18 @@ hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *
                        d_blocksums);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
                      (uint64_t)nblocks, 0, d_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a, const uint64_t *b_b,
+                           const uint64_t *a_b, ckpt_validation_t *d_result, hipStream_t s) {
+  hipLaunchKernelGGL(k_validate_init, dim3(1), dim3(1), 0, s, d_result);
+  if (n) {
+    uint64_t groups = (n + SCAN_THREADS - 1) / SCAN_THREADS;
+    if (groups > 4096) groups = 4096;
+    hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
+                       b_b, a_b, d_result);
+  }
   return hipGetLastError();
 }
 
