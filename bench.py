@@ -49,6 +49,10 @@ def parse_args():
                     help="config 3 only: also run the content-addressed match on a snapshot whose "
                          "buffer list is rotated by one (every unchanged chunk sits at another "
                          "position), and the device-to-device moves that rebuild it")
+    ap.add_argument("--swap", action="store_true",
+                    help="also swap the last replica's delta out to pinned host memory and back in "
+                         "(ckpt_swap_out / ckpt_swap_in through a small device ring)")
+    ap.add_argument("--swap-slice-mib", type=int, default=256)
     ap.add_argument("--calibrate", action="store_true",
                     help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
                          "the known-size dispatches that scale the rocprofv3 byte counters)")
@@ -114,6 +118,42 @@ def cpu_baseline(w, rep_ref, rep_new, sample_bytes, torch):
                   f"{hashed / 2**30:.2f} GiB fingerprinted, {cnt2['staged_bytes'] / 2**30:.2f} GiB "
                   f"staged, {dt:.2f} s wall (fingerprint on {threads} threads, rest on one)",
     }, (idx, dig, mask)
+
+
+def host_swap_leg(w, rep, dig, mask, manifest, d_staging, staged, ndirty, ck, torch, slice_bytes):
+    """Swap-out of the replica's delta to pinned host memory and swap-in back, each timed on
+    the host clock (the calls block until the data has landed).  The host image must equal
+    the device staging buffer that ckpt_compact produced for the same mask."""
+    host = torch.empty(max(16, staged), dtype=torch.uint8, pin_memory=True)
+    sw = ck.Swapper(slice_bytes)
+    t = {}
+    for name in ("warm", "timed"):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        cnt = sw.swap_out(rep.plan, mask, dig, host, manifest, staging_cap=staged,
+                          manifest_cap=ndirty)
+        t[name + "_out"] = time.perf_counter() - t0
+        assert cnt["status"] == 0 and cnt["staged_bytes"] == staged
+        t0 = time.perf_counter()
+        rejected = sw.swap_in(rep.plan, host, staged, manifest, ndirty)
+        t[name + "_in"] = time.perf_counter() - t0
+        assert rejected == 0
+    same = True
+    step = 1 << 30
+    for lo in range(0, staged, step):
+        hi = min(staged, lo + step)
+        same = same and bool(torch.equal(host[lo:hi], d_staging[lo:hi].cpu()))
+    assert same, "host image differs from the device staging buffer"
+    sw.close()
+    return {
+        "staged_bytes": staged, "state_bytes": w.nbytes, "slice_bytes": slice_bytes,
+        "device_ring_bytes": 2 * slice_bytes,
+        "swap_out_ms": round(t["timed_out"] * 1e3, 1), "swap_in_ms": round(t["timed_in"] * 1e3, 1),
+        "swap_out_GBps": round(staged / t["timed_out"] / 1e9, 1),
+        "swap_in_GBps": round(staged / t["timed_in"] / 1e9, 1),
+        "naive_full_state_ms_at_same_rate": round(w.nbytes / (staged / t["timed_out"]) * 1e3, 1),
+        "host_image_equals_device_staging": same,
+    }
 
 
 def content_addressed_leg(w, t0, t1, ref, ck, torch, np, steps):
@@ -350,6 +390,11 @@ def main():
             cal[name] = {"bytes": nb, "ms": round(ms, 3),
                          "GBps": round((2 if name == "copy" else 1) * nb / ms / 1e6, 1)}
         out["calibration"] = cal
+
+    if args.swap:
+        out["host_swap"] = host_swap_leg(w, pairs[-1][1], digs[-1], masks[-1], manifests[-1],
+                                         stagings[-1], staged[-1], ndirty[-1], ck, torch,
+                                         args.swap_slice_mib << 20)
 
     if args.match and w.nreplicas == 1:
         out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,

@@ -210,6 +210,44 @@ int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_
 int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
                        const int64_t *d_src, uint64_t *d_rejected, void *stream);
 
+/* ---- swap-out to / swap-in from host memory --------------------------------- */
+
+/* The paper's context switch copies what is not de-duplicated to host memory and
+ * back (sec. 5.1, 5.2.1).  These two calls do ckpt_compact / ckpt_restore through
+ * host memory without a full-size device staging buffer: staging is cut into
+ * slices; a slice is gathered into one half of a two-slot device ring and copied
+ * to the host on a second stream while the next slice is gathered (the reverse
+ * for swap-in).  The swapper owns the ring (2 x slice_bytes of device memory,
+ * allocated once in ckpt_swapper_create), the copy stream and the events.
+ *   slice_bytes  multiple of 64 KiB, 64 KiB .. 16 GiB
+ * A swapper serves one call at a time. */
+typedef struct ckpt_swapper ckpt_swapper_t;
+int ckpt_swapper_create(uint64_t slice_bytes, ckpt_swapper_t **out);
+int ckpt_swapper_destroy(ckpt_swapper_t *swapper);
+
+/* Swap-out: same result as ckpt_compact, except that the staged bytes land in
+ * h_staging (HOST memory; pinned memory is needed for the copies to overlap) and
+ * the counts in *h_counts (host).  The manifest stays on the device.  Blocks the
+ * calling thread until the last byte is in host memory; work is ordered after
+ * what `stream` already holds.  If the manifest or h_staging is too small the
+ * call returns CKPT_ERR_CAPACITY with the full need in *h_counts
+ * (overflow != 0) and h_staging untouched.
+ * Errors: INVALID_ARG, ALIGNMENT, CAPACITY, DEVICE. */
+int ckpt_swap_out(ckpt_swapper_t *swapper, const ckpt_plan_t *plan, const uint8_t *d_mask,
+                  const uint64_t *d_digests, void *h_staging, uint64_t h_staging_cap,
+                  ckpt_entry_t *d_manifest, uint64_t manifest_cap, ckpt_counts_t *h_counts,
+                  void *stream);
+
+/* Swap-in: same result as ckpt_restore from a staging image in host memory.
+ * d_manifest must be a manifest as ckpt_compact / ckpt_swap_out write it (entries
+ * cover [0, staged_bytes) without gaps, in order); an entry that breaks that, or
+ * does not fit dst_plan, ends the 64 KiB window it was met in and is counted in
+ * *h_rejected (host, optional).  Blocks until the buffers are written.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_swap_in(ckpt_swapper_t *swapper, const ckpt_plan_t *dst_plan, const void *h_staging,
+                 uint64_t staged_bytes, const ckpt_entry_t *d_manifest, uint64_t nentries,
+                 uint64_t *h_rejected, void *stream);
+
 /* ---- squashing validation -------------------------------------------------- */
 
 /* Sec. 5.2.3 validates operation squashing by inferring mutations from

@@ -27,6 +27,7 @@ EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
     "ckpt_restore", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_validate_mutations",
+    "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
 )
@@ -85,6 +86,14 @@ def _lib():
         lib.ckpt_apply_matches.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_validate_mutations.restype = ci
         lib.ckpt_validate_mutations.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        lib.ckpt_swapper_create.restype = ci
+        lib.ckpt_swapper_create.argtypes = [u64, ctypes.POINTER(vp)]
+        lib.ckpt_swapper_destroy.restype = ci
+        lib.ckpt_swapper_destroy.argtypes = [vp]
+        lib.ckpt_swap_out.restype = ci
+        lib.ckpt_swap_out.argtypes = [vp, vp, vp, vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_swap_in.restype = ci
+        lib.ckpt_swap_in.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_bw_copy.restype = ci
         lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
         lib.ckpt_bw_read.restype = ci
@@ -222,6 +231,54 @@ def apply_matches(dst_plan: Plan, ref_plan: Plan, src, rejected=None, stream=Non
     """``ckpt_apply_matches``: device-to-device moves of the matched chunks into dst_plan."""
     _check(_lib().ckpt_apply_matches(dst_plan._h, ref_plan._h, _ptr(src), _ptr(rejected),
                                      _stream(stream)), "ckpt_apply_matches")
+
+
+class Swapper:
+    """``ckpt_swapper_create``: device ring + copy stream for host swap-out / swap-in."""
+
+    def __init__(self, slice_bytes: int):
+        h = ctypes.c_void_p()
+        _check(_lib().ckpt_swapper_create(slice_bytes, ctypes.byref(h)), "ckpt_swapper_create")
+        self._h = h
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            _lib().ckpt_swapper_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def swap_out(self, plan: Plan, mask, digests, host_staging, manifest, stream=None,
+                 staging_cap: Optional[int] = None, manifest_cap: Optional[int] = None) -> dict:
+        """``ckpt_swap_out``: host_staging is a (pinned) CPU uint8 tensor.  Returns the counts."""
+        if staging_cap is None:
+            staging_cap = host_staging.numel()
+        if manifest_cap is None:
+            manifest_cap = manifest.numel() * manifest.element_size() // ENTRY_BYTES
+        counts = (ctypes.c_uint64 * 3)()
+        status = _lib().ckpt_swap_out(self._h, plan._h, _ptr(mask), _ptr(digests),
+                                      _ptr(host_staging), staging_cap, _ptr(manifest),
+                                      manifest_cap, counts, _stream(stream))
+        out = {"ndirty": int(counts[0]), "staged_bytes": int(counts[1]), "overflow": int(counts[2])}
+        if status == -5:
+            out["status"] = status
+            return out
+        _check(status, "ckpt_swap_out")
+        out["status"] = 0
+        return out
+
+    def swap_in(self, dst_plan: Plan, host_staging, staged_bytes: int, manifest, nentries: int,
+                stream=None) -> int:
+        """``ckpt_swap_in``: returns the number of rejected entries."""
+        rejected = ctypes.c_uint64(0)
+        _check(_lib().ckpt_swap_in(self._h, dst_plan._h, _ptr(host_staging), staged_bytes,
+                                   _ptr(manifest), nentries, ctypes.byref(rejected),
+                                   _stream(stream)), "ckpt_swap_in")
+        return int(rejected.value)
 
 
 VALIDATION_FIELDS = ("changed_a", "changed_b", "mismatches", "first_mismatch")

@@ -15,7 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckpt.so")
-SOURCES = ["api.hip", "fingerprint.hip", "diff_scan.hip", "copy.hip", "match.hip"]
+SOURCES = ["api.hip", "fingerprint.hip", "diff_scan.hip", "copy.hip", "match.hip",
+           "transport.hip", "swap.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

@@ -30,6 +30,15 @@ struct ckpt_plan {
   int device = -1;
 };
 
+namespace ckpt {
+const PlanDev *plan_dev(const ckpt_plan_t *plan) { return &plan->dev; }
+uint64_t *plan_scratch(const ckpt_plan_t *plan) { return plan->d_blocksums; }
+void set_last_device_error(hipError_t e) {
+  g_last_hip_error = (int)e;
+  (void)hipGetLastError();
+}
+}  // namespace ckpt
+
 extern "C" {
 
 int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,

@@ -105,7 +105,16 @@ hipError_t launch_match(const PlanDev &p, const uint64_t *d_dig, const uint64_t 
                         ckpt_match_counts_t *d_counts, hipStream_t s);
 hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev &refp, const int64_t *d_src,
                                 uint64_t *d_rejected, hipStream_t s);
+hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_manifest,
+                        uint64_t nentries, void *d_ring, uint64_t b0, uint64_t b1,
+                        uint64_t *d_rejected, hipStream_t s);
+hipError_t launch_zero_u64(uint64_t *d_value, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
+
+// access to the opaque plan from the other host translation units
+const PlanDev *plan_dev(const ckpt_plan_t *plan);
+uint64_t *plan_scratch(const ckpt_plan_t *plan);
+void set_last_device_error(hipError_t e);
 
 }  // namespace ckpt

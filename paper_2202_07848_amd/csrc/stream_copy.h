@@ -35,8 +35,8 @@ __device__ __forceinline__ void store_partial16(uint8_t *dst, uint4 v, uint32_t 
   for (uint32_t b = 0; b < valid; ++b) dst[b] = (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
 }
 
-// Copies bytes [lo, hi) of a chunk of length len from src to dst; lo, hi are
-// multiples of 16 except that hi may be pad16(len).  The piece that straddles
+// Copies bytes [lo, hi) of a chunk of length len from src to dst and touches
+// nothing outside that range; lo, hi are multiples of 16 (hi at most pad16(len)).  The piece that straddles
 // len is assembled bytewise: ZERO_PAD writes it as a full 16 bytes with zeros
 // above len (staging), otherwise exactly the valid bytes are written.
 template <bool ZERO_PAD>
@@ -47,6 +47,7 @@ __device__ __forceinline__ void move_piece(const uint8_t *src, uint8_t *dst, uin
 #pragma unroll
     for (int u = 0; u < MOVE_UNROLL; ++u) {
       const uint32_t o = base + u * 64 * 16;
+      if (o >= hi) continue;                 // the piece may end before the chunk does
       if (o + 16 <= len)
         v[u] = stream_load16(src + o);
       else if (o < len)
@@ -55,6 +56,7 @@ __device__ __forceinline__ void move_piece(const uint8_t *src, uint8_t *dst, uin
 #pragma unroll
     for (int u = 0; u < MOVE_UNROLL; ++u) {
       const uint32_t o = base + u * 64 * 16;
+      if (o >= hi) continue;
       if (o + 16 <= len) {
         stream_store16(dst + o, v[u]);
       } else if (o < len) {
