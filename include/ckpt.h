@@ -147,6 +147,35 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
                  void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
                  uint64_t manifest_cap, ckpt_counts_t *d_counts, void *stream);
 
+/* The three calls above as one, with the same outputs bit for bit (d_digests,
+ * d_mask, d_staging, d_manifest, d_counts), optionally in a single pass over the
+ * data.  d_hint (N bytes, or NULL) predicts the mask -- at a context switch the
+ * previous switch's mask is the natural prediction, since which buffers are
+ * per-replica state does not change (sec. 5.2.1).  With a hint, the staging
+ * offsets of the predicted chunks are computed first and the fingerprint pass
+ * writes each predicted chunk to its staging place while hashing it, so no byte
+ * is read twice.  Afterwards the real mask is compared with the hint: if they are
+ * equal staging is complete; if not, the ordinary gather runs and overwrites
+ * staging, so a wrong hint costs time, never correctness.  (Measured on MI355X the
+ * single pass wins once the hint marks more than about a fifth of the bytes; below
+ * that, mixing the staging writes into the read stream costs more than the second
+ * read it saves -- pass NULL then.)
+ *   d_hint          may be the same buffer as d_mask (it is copied first)
+ *   d_hint_misses   optional device uint64: chunks where hint and mask differ
+ *                   (0 = the single pass sufficed; always 0 without a hint)
+ *   d_workspace     device scratch, ckpt_snapshot_workspace_bytes(N) bytes, 16-byte
+ *                   aligned; needed only with a hint
+ * d_staging must not overlap d_hint or d_workspace.  Note that without
+ * synchronising, a wrong hint may have written bytes of clean chunks into
+ * staging beyond the final staged_bytes (never beyond staging_cap).
+ * Errors: INVALID_ARG, GEOMETRY, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
+uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks);
+int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                  const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
+                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                  ckpt_counts_t *d_counts, uint64_t *d_hint_misses, void *d_workspace,
+                  uint64_t workspace_bytes, void *stream);
+
 /* Swap-in / restore (sec. 4.5, sec. 5.2.1): for each of the first nentries
  * manifest entries, copy len bytes from d_staging + stage_off to buffer
  * entry.buf of dst_plan at offset buf_off.  Chunks without an entry are not

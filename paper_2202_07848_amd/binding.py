@@ -26,7 +26,7 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_validate_mutations",
+    "ckpt_restore", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_validate_mutations",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -78,6 +78,10 @@ def _lib():
         lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore.restype = ci
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_snapshot_workspace_bytes.restype = u64
+        lib.ckpt_snapshot_workspace_bytes.argtypes = [u64]
+        lib.ckpt_snapshot.restype = ci
+        lib.ckpt_snapshot.argtypes = [vp, vp, u64, vp, vp, vp, vp, u64, vp, u64, vp, vp, vp, u64, vp]
         lib.ckpt_match_workspace_bytes.restype = u64
         lib.ckpt_match_workspace_bytes.argtypes = [u64, u64]
         lib.ckpt_match.restype = ci
@@ -200,6 +204,29 @@ def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,
     _check(_lib().ckpt_compact(plan._h, _ptr(mask), _ptr(digests), _ptr(staging), staging_cap,
                                _ptr(manifest), manifest_cap, _ptr(counts), _stream(stream)),
            "ckpt_compact")
+
+
+def snapshot_workspace_bytes(nchunks: int) -> int:
+    return int(_lib().ckpt_snapshot_workspace_bytes(nchunks))
+
+
+def snapshot(plan: Plan, ref, hint, digests, mask, staging, manifest, counts, hint_misses=None,
+             workspace=None, stream=None, staging_cap: Optional[int] = None,
+             manifest_cap: Optional[int] = None, n_ref: Optional[int] = None) -> None:
+    """``ckpt_snapshot``: fingerprint + diff + compact in one call; with ``hint`` (uint8, N) the
+    predicted chunks are staged during the fingerprint pass."""
+    if n_ref is None:
+        n_ref = 0 if ref is None else ref.numel()
+    if staging_cap is None:
+        staging_cap = 0 if staging is None else staging.numel() * staging.element_size()
+    if manifest_cap is None:
+        manifest_cap = 0 if manifest is None else \
+            manifest.numel() * manifest.element_size() // ENTRY_BYTES
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib().ckpt_snapshot(plan._h, _ptr(ref), n_ref, _ptr(hint), _ptr(digests), _ptr(mask),
+                                _ptr(staging), staging_cap, _ptr(manifest), manifest_cap,
+                                _ptr(counts), _ptr(hint_misses), _ptr(workspace), ws_bytes,
+                                _stream(stream)), "ckpt_snapshot")
 
 
 def restore(dst_plan: Plan, staging, staging_bytes: int, manifest, nentries: int,

@@ -284,7 +284,66 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
   hipError_t e = ckpt::launch_compact_scan(plan->dev, d_mask, d_digests, staging_cap, d_manifest,
                                            manifest_cap, plan->d_blocksums, d_counts, s);
   if (e == hipSuccess)
-    e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, s);
+    e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
+                            nullptr, s);
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) {
+  return 8 * nchunks + ((nchunks + 15) & ~15ull) + 64;
+}
+
+int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                  const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
+                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                  ckpt_counts_t *d_counts, uint64_t *d_hint_misses, void *d_workspace,
+                  uint64_t workspace_bytes, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (d_ref != nullptr && n_ref != n) return CKPT_ERR_GEOMETRY;
+  if (n != 0 && (d_digests == nullptr || d_mask == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (staging_cap != 0 && d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (d_hint != nullptr && d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_staging, 16) || !aligned(d_manifest, 8) || !aligned(d_digests, 8) ||
+      !aligned(d_ref, 8) || !aligned(d_counts, 8) || !aligned(d_workspace, 16) ||
+      !aligned(d_hint_misses, 8))
+    return CKPT_ERR_ALIGNMENT;
+  if (d_hint != nullptr && workspace_bytes < ckpt_snapshot_workspace_bytes(n))
+    return CKPT_ERR_CAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const ckpt::PlanDev &p = plan->dev;
+  hipError_t e;
+  uint64_t *misses = nullptr;
+  if (d_hint != nullptr) {
+    // workspace: [hint offsets: N x u64][misses, tmp counts: 8 x u64][hint copy: N bytes]
+    uint64_t *hoff = static_cast<uint64_t *>(d_workspace);
+    misses = hoff + n;
+    ckpt_counts_t *tmp = reinterpret_cast<ckpt_counts_t *>(misses + 1);
+    uint8_t *hint_copy = reinterpret_cast<uint8_t *>(misses + 8);
+    e = ckpt::launch_hint_offsets(p, d_hint, hint_copy, plan->d_blocksums, tmp, manifest_cap, hoff,
+                                  misses, s);
+    if (e == hipSuccess)
+      e = ckpt::launch_fingerprint_staging(p, d_digests, hint_copy, hoff, d_staging, staging_cap, s);
+    if (e == hipSuccess)
+      e = ckpt::launch_diff(p, d_digests, d_ref, d_mask, plan->d_blocksums, d_counts, s);
+    if (e == hipSuccess) e = ckpt::launch_hint_check(p, d_mask, hint_copy, misses, s);
+  } else {
+    e = ckpt::launch_fingerprint(p, d_digests, s);
+    if (e == hipSuccess)
+      e = ckpt::launch_diff(p, d_digests, d_ref, d_mask, plan->d_blocksums, d_counts, s);
+  }
+  if (e == hipSuccess)
+    e = ckpt::launch_compact_scan(p, d_mask, d_digests, staging_cap, d_manifest, manifest_cap,
+                                  plan->d_blocksums, d_counts, s);
+  if (e == hipSuccess)
+    e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, misses, s);
+  if (e == hipSuccess && d_hint_misses != nullptr) {
+    if (misses != nullptr)
+      e = hipMemcpyAsync(d_hint_misses, misses, sizeof(uint64_t), hipMemcpyDeviceToDevice, s);
+    else
+      e = ckpt::launch_zero_u64(d_hint_misses, s);
+  }
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

@@ -93,7 +93,16 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
                                ckpt_counts_t *d_counts, hipStream_t s);
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
-                         hipStream_t s);
+                         const uint64_t *d_only_if_nonzero, hipStream_t s);
+hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
+                                      const uint64_t *d_hint_off, void *d_staging,
+                                      uint64_t staging_cap, hipStream_t s);
+hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8_t *d_hint_copy,
+                               uint64_t *d_blocksums, ckpt_counts_t *d_tmp_counts,
+                               uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
+                               hipStream_t s);
+hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint8_t *d_hint_copy,
+                             uint64_t *d_misses, hipStream_t s);
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
                           hipStream_t s);

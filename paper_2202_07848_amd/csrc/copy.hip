@@ -31,7 +31,10 @@ __global__ __launch_bounds__(COPY_THREADS) void k_move(PlanDev p,
                                                        const ckpt_counts_t *__restrict__ count_dev,
                                                        uint8_t *__restrict__ staging,
                                                        uint64_t staging_limit,
-                                                       unsigned long long *__restrict__ rejected) {
+                                                       unsigned long long *__restrict__ rejected,
+                                                       const unsigned long long *only_if_nonzero) {
+  // the fused snapshot has already staged everything when its hint was exact
+  if (only_if_nonzero != nullptr && *only_if_nonzero == 0) return;
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
@@ -139,13 +142,14 @@ inline uint32_t move_groups(const PlanDev &p, uint64_t max_entries) {
 
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
-                         hipStream_t s) {
+                         const uint64_t *d_only_if_nonzero, hipStream_t s) {
   const uint64_t most = p.nchunks < manifest_cap ? p.nchunks : manifest_cap;
   const uint32_t groups = move_groups(p, most);
   if (groups == 0) return hipSuccess;
   hipLaunchKernelGGL(k_move<true>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, most,
                      d_counts, reinterpret_cast<uint8_t *>(d_staging), staging_cap,
-                     (unsigned long long *)nullptr);
+                     (unsigned long long *)nullptr,
+                     reinterpret_cast<const unsigned long long *>(d_only_if_nonzero));
   return hipGetLastError();
 }
 
@@ -160,7 +164,8 @@ hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint
   hipLaunchKernelGGL(k_move<false>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, nentries,
                      (const ckpt_counts_t *)nullptr,
                      const_cast<uint8_t *>(reinterpret_cast<const uint8_t *>(d_staging)),
-                     staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected));
+                     staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected),
+                     (const unsigned long long *)nullptr);
   return hipGetLastError();
 }
 

@@ -192,6 +192,59 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
                         (unsigned long long)missed);
 }
 
+// Fused snapshot, before the pass: staging offset of every hinted chunk (the
+// exclusive prefix sum over the hint, as k_emit_manifest computes it for a mask).
+__global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(PlanDev p,
+                                                               const uint8_t *__restrict__ hint,
+                                                               const uint64_t *__restrict__ blockoff,
+                                                               uint64_t manifest_cap,
+                                                               uint64_t *__restrict__ hoff) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  ChunkRef refs[SCAN_PER_THREAD];
+  int n = 0;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    if (k < p.nchunks) {
+      m[i] = hint[k] != 0;
+      n = i + 1;
+    }
+  }
+  Pair mine = sum_marked(p, k0, m, n, refs), total;
+  Pair pos = block_exclusive_scan(mine, &total);
+  pos.cnt += blockoff[2 * (uint64_t)blockIdx.x];
+  pos.bytes += blockoff[2 * (uint64_t)blockIdx.x + 1];
+  for (int i = 0; i < n; ++i) {
+    // a chunk whose entry would not fit the manifest is not staged either (all-ones = never fits)
+    hoff[k0 + i] = pos.cnt < manifest_cap ? pos.bytes : ~0ull;
+    if (m[i]) {
+      pos.cnt += 1;
+      pos.bytes += pad16(refs[i].len);
+    }
+  }
+}
+
+// Fused snapshot, after the pass: in how many chunks does the mask differ from the hint?
+// (also keeps a private copy of the hint, so that hint and mask may be one buffer)
+__global__ __launch_bounds__(256) void k_copy_bytes(uint8_t *__restrict__ dst,
+                                                    const uint8_t *__restrict__ src, uint64_t n,
+                                                    unsigned long long *zero_me) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;
+}
+
+__global__ __launch_bounds__(256) void k_hint_check(const uint8_t *__restrict__ mask,
+                                                    const uint8_t *__restrict__ hint, uint64_t n,
+                                                    unsigned long long *misses) {
+  uint32_t bad = 0;
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+    bad += (mask[i] != 0) != (hint[i] != 0);
+  for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
+  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
+}
+
 // Squashing validation (paper sec. 5.2.3): per chunk, did rank a and rank b
 // change it alike?  Counters are zeroed by k_validate_init on the same stream.
 __global__ void k_validate_init(ckpt_validation_t *r) {
@@ -251,6 +304,37 @@ hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *
                        d_blocksums);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
                      (uint64_t)nblocks, 0, d_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8_t *d_hint_copy,
+                               uint64_t *d_blocksums, ckpt_counts_t *d_tmp_counts,
+                               uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
+                               hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  uint32_t groups = (uint32_t)((p.nchunks + 255) / 256);
+  if (groups > 4096) groups = 4096;
+  if (groups == 0) groups = 1;
+  hipLaunchKernelGGL(k_copy_bytes, dim3(groups), dim3(256), 0, s, d_hint_copy, d_hint_in, p.nchunks,
+                     reinterpret_cast<unsigned long long *>(d_misses));
+  if (nblocks)
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_copy,
+                       d_blocksums);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
+                     (uint64_t)nblocks, 1, d_tmp_counts);
+  if (nblocks)
+    hipLaunchKernelGGL(k_hint_offsets, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_copy,
+                       d_blocksums, manifest_cap, d_hoff);
+  return hipGetLastError();
+}
+
+hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint8_t *d_hint_copy,
+                             uint64_t *d_misses, hipStream_t s) {
+  if (p.nchunks == 0) return hipSuccess;
+  uint32_t groups = (uint32_t)((p.nchunks + 255) / 256);
+  if (groups > 4096) groups = 4096;
+  hipLaunchKernelGGL(k_hint_check, dim3(groups), dim3(256), 0, s, d_mask, d_hint_copy, p.nchunks,
+                     reinterpret_cast<unsigned long long *>(d_misses));
   return hipGetLastError();
 }
 

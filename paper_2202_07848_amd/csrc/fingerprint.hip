@@ -22,6 +22,7 @@
 // shorter chunks are masked.  Residual stripes and the tail are read straight
 // from global memory (they are < 256 bytes per chunk).
 #include "ckpt_internal.h"
+#include "stream_copy.h"
 #include "xxh64_device.h"
 
 namespace ckpt {
@@ -32,7 +33,9 @@ constexpr int TILE = 256;              // bytes of one chunk staged per step
 constexpr int TILE_LOG2 = 8;
 constexpr int LDS_PITCH = TILE + 32;   // per-chunk pitch; the 32-byte skew spreads chunks over banks
 constexpr int LOADS = GROUP * TILE / (64 * 16);   // dwordx4 loads per lane per step (= 4)
-constexpr int DEPTH = 4;               // tiles in flight per lane (registers)
+// Tiles in flight per lane.  2, 3 and 4 measure the same within noise on MI355X;
+// 2 keeps the kernel at 95 VGPRs (five waves per SIMD).
+constexpr int DEPTH = 2;
 
 __device__ __forceinline__ void lds_phase_fence() {
   // Orders this wave's LDS writes and reads in the compiler; the hardware
@@ -47,10 +50,11 @@ __device__ __forceinline__ void lds_phase_fence() {
 // Every byte is read exactly once, so the load is non-temporal: measured on
 // MI355X a plain streaming read reaches 7.2 TB/s with the nt hint and 6.4 TB/s
 // without it.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef const u32x4 __attribute__((address_space(1))) *global_u32x4_ptr;
 __device__ __forceinline__ u32x4 gload16(const uint8_t *p) {
-  return __builtin_nontemporal_load((global_u32x4_ptr)(p));
+  return __builtin_nontemporal_load((global_load_ptr)(p));
+}
+__device__ __forceinline__ void gstore16(uint8_t *p, u32x4 v) {
+  __builtin_nontemporal_store(v, (global_store_ptr)(p));
 }
 
 // One step of the tile pipeline: the prefetched tile in q goes to LDS, the
@@ -58,15 +62,26 @@ __device__ __forceinline__ u32x4 gload16(const uint8_t *p) {
 // In the non-uniform case a loader lane whose chunk has no tile `next` reads
 // the plan's spare block instead, and a hashing lane whose chunk is already
 // finished sits the step out; nothing in the step is a branch around a load,
-// so the compiler can count outstanding loads exactly.
-template <bool UNIFORM, bool REFILL>
+// so the compiler can count outstanding loads exactly.  With STAGE the tile
+// is also written to the staging position of its chunk (sptr, null for chunks
+// that are not staged) straight from the registers it was loaded into: the
+// single-pass snapshot never reads a byte twice.
+template <bool UNIFORM, bool REFILL, bool STAGE>
 __device__ __forceinline__ uint64_t tile_step(u32x4 (&q)[LOADS], uint8_t *wr, const uint8_t *rd,
                                               const uint8_t *const (&lptr)[LOADS],
+                                              uint8_t *const (&sptr)[LOADS],
                                               const uint32_t (&ltiles)[LOADS],
                                               const uint8_t *spare, uint32_t my_tiles, uint32_t tt,
                                               uint32_t next, uint64_t acc) {
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) *reinterpret_cast<u32x4 *>(wr + i * 4 * LDS_PITCH) = q[i];
+  if (STAGE) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      if (sptr[i] != nullptr && (UNIFORM || tt < ltiles[i]))
+        gstore16(sptr[i] + (uint64_t)tt * TILE, q[i]);
+    }
+  }
   lds_phase_fence();
   if (REFILL) {
 #pragma unroll
@@ -85,8 +100,9 @@ __device__ __forceinline__ uint64_t tile_step(u32x4 (&q)[LOADS], uint8_t *wr, co
   return acc;
 }
 
-template <bool UNIFORM>
+template <bool UNIFORM, bool STAGE>
 __device__ __forceinline__ uint64_t hash_tiles(uint8_t *s_tile, const uint8_t *const (&lptr)[LOADS],
+                                               uint8_t *const (&sptr)[LOADS],
                                                const uint32_t (&ltiles)[LOADS],
                                                const uint8_t *spare, uint32_t my_tiles,
                                                uint32_t max_tiles, int lane, uint64_t acc) {
@@ -112,8 +128,8 @@ __device__ __forceinline__ uint64_t hash_tiles(uint8_t *s_tile, const uint8_t *c
   for (; tile < steady; tile += DEPTH) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-      acc = tile_step<UNIFORM, true>(q[d], wr, rd, lptr, ltiles, spare, my_tiles, tile + d,
-                                     tile + d + DEPTH, acc);
+      acc = tile_step<UNIFORM, true, STAGE>(q[d], wr, rd, lptr, sptr, ltiles, spare, my_tiles,
+                                            tile + d, tile + d + DEPTH, acc);
   }
   // drain: the last DEPTH..2*DEPTH-1 tiles (or all of them if there are fewer)
 #pragma unroll
@@ -121,20 +137,33 @@ __device__ __forceinline__ uint64_t hash_tiles(uint8_t *s_tile, const uint8_t *c
     const uint32_t tt = steady + d;              // wave-uniform
     if (tt < max_tiles) {
       if (tt + DEPTH < max_tiles)
-        acc = tile_step<UNIFORM, true>(q[d % DEPTH], wr, rd, lptr, ltiles, spare, my_tiles, tt,
-                                       tt + DEPTH, acc);
+        acc = tile_step<UNIFORM, true, STAGE>(q[d % DEPTH], wr, rd, lptr, sptr, ltiles, spare,
+                                              my_tiles, tt, tt + DEPTH, acc);
       else
-        acc = tile_step<UNIFORM, false>(q[d % DEPTH], wr, rd, lptr, ltiles, spare, my_tiles, tt, 0,
-                                        acc);
+        acc = tile_step<UNIFORM, false, STAGE>(q[d % DEPTH], wr, rd, lptr, sptr, ltiles, spare,
+                                               my_tiles, tt, 0, acc);
     }
   }
   return acc;
 }
 
-__global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restrict__ dig) {
+// STAGE: the fused snapshot.  A chunk k with hint[k] != 0 is copied, while it is
+// hashed, to staging + hoff[k] (zero padded to 16 bytes) provided it ends at or
+// before staging_cap -- the same rule ckpt_compact applies.
+struct StageArgs {
+  const uint8_t *hint;      // [N]
+  const uint64_t *hoff;     // [N] staging offset of every hinted chunk
+  uint8_t *staging;
+  uint64_t staging_cap;
+};
+
+template <bool STAGE>
+__global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restrict__ dig,
+                                                    StageArgs st) {
   __shared__ __align__(16) uint8_t s_tile[GROUP * LDS_PITCH];
   __shared__ uint64_t s_ptr[GROUP];
   __shared__ uint64_t s_chunk[GROUP];
+  __shared__ uint64_t s_stage[STAGE ? GROUP : 1];
   __shared__ uint32_t s_len[GROUP];
 
   const int lane = threadIdx.x;
@@ -166,6 +195,15 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
     s_ptr[lane] = ptr;
     s_chunk[lane] = k;
     s_len[lane] = len;
+    if (STAGE) {
+      uint64_t stage = 0;
+      if (len != 0 && st.hint[k] != 0) {
+        const uint64_t off = st.hoff[k];
+        if (off <= st.staging_cap && pad16(len) <= st.staging_cap - off)
+          stage = reinterpret_cast<uint64_t>(st.staging) + off;
+      }
+      s_stage[lane] = stage;
+    }
   }
   __syncthreads();
 
@@ -176,12 +214,16 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
 
   // loader role: load i of this lane serves chunk 4*i + lane/16, bytes 16*(lane%16)..+15 of a tile
   const uint8_t *lptr[LOADS];
+  uint8_t *sptr[LOADS];
   uint32_t ltiles[LOADS];
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int lc = 4 * i + (lane >> 4);
     lptr[i] = reinterpret_cast<const uint8_t *>(s_ptr[lc]) + 16 * (lane & 15);
     ltiles[i] = s_len[lc] >> TILE_LOG2;
+    sptr[i] = nullptr;
+    if (STAGE && s_stage[lc] != 0)
+      sptr[i] = reinterpret_cast<uint8_t *>(s_stage[lc]) + 16 * (lane & 15);
   }
   uint32_t max_tiles = 0, min_tiles = 0xFFFFFFFFu;
 #pragma unroll
@@ -195,9 +237,11 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
 
   uint64_t acc = xxh::acc_init(t);
   if (max_tiles == min_tiles)
-    acc = hash_tiles<true>(s_tile, lptr, ltiles, p.spare, my_tiles, max_tiles, lane, acc);
+    acc = hash_tiles<true, STAGE>(s_tile, lptr, sptr, ltiles, p.spare, my_tiles, max_tiles, lane,
+                                  acc);
   else
-    acc = hash_tiles<false>(s_tile, lptr, ltiles, p.spare, my_tiles, max_tiles, lane, acc);
+    acc = hash_tiles<false, STAGE>(s_tile, lptr, sptr, ltiles, p.spare, my_tiles, max_tiles, lane,
+                                   acc);
 
   // up to 7 stripes between the last full tile and the tail
   const uint32_t rem = my_len & (TILE - 1);
@@ -207,6 +251,22 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
   for (int s = 0; s < TILE / 32 - 1; ++s) {
     if ((uint32_t)s < rstripes)
       acc = xxh::round(acc, *reinterpret_cast<const uint64_t *>(rp + 32 * s + 8 * t));
+  }
+
+  // staged copy of what follows the last full tile (< 256 bytes), zero padded to 16:
+  // the quad's four lanes take the 16-byte units round-robin
+  if (STAGE && s_stage[c] != 0) {
+    uint8_t *sp = reinterpret_cast<uint8_t *>(s_stage[c]);
+    const uint32_t done = my_tiles << TILE_LOG2, padded = (uint32_t)pad16(my_len);
+#pragma unroll
+    for (int j = 0; j < TILE / 64; ++j) {
+      const uint32_t o = done + 16 * (t + 4 * j);
+      if (o < padded) {
+        const uint4 v = o + 16 <= my_len ? stream_load16(my_ptr + o)
+                                         : load_partial16(my_ptr + o, my_len - o);
+        stream_store16(sp + o, v);
+      }
+    }
   }
 
   // gather the quad's four accumulators (every lane of the quad gets all four)
@@ -246,7 +306,20 @@ hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t
   if (p.nchunks == 0) return hipSuccess;
   const uint64_t groups = (p.nfull + GROUP - 1) / GROUP + (p.nshort + GROUP - 1) / GROUP;
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_fingerprint, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests);
+  hipLaunchKernelGGL(k_fingerprint<false>, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests,
+                     StageArgs{nullptr, nullptr, nullptr, 0});
+  return hipGetLastError();
+}
+
+hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
+                                      const uint64_t *d_hint_off, void *d_staging,
+                                      uint64_t staging_cap, hipStream_t s) {
+  if (p.nchunks == 0) return hipSuccess;
+  const uint64_t groups = (p.nfull + GROUP - 1) / GROUP + (p.nshort + GROUP - 1) / GROUP;
+  if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_fingerprint<true>, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests,
+                     StageArgs{d_hint, d_hint_off, reinterpret_cast<uint8_t *>(d_staging),
+                               staging_cap});
   return hipGetLastError();
 }
 

@@ -1,0 +1,158 @@
+"""GPU parity of the fused ckpt_snapshot (fingerprint + diff + compact in one
+call, optionally in one pass over the data guided by a hint) against the
+oracle's three separate steps: same digests, mask, counts, manifest and staging
+bytes whatever the hint says -- exact, absent, wrong, all ones, all zeros -- and
+under capacity limits."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_07848_amd import binding as ck
+from paper_2202_07848_amd import workloads as wl
+from gpu_util import DeviceBuffers, counts_dict, u64
+
+pytestmark = pytest.mark.gpu
+
+ODD_SIZES = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 288, 511, 512, 1000, 4095, 4096, 4097,
+             8191, 8192, 12289, 0, 31, 100000, 7, 65536, 65537, 3, 262144 + 40, 5000]
+
+
+def host_bufs(seed, sizes):
+    rng = np.random.default_rng(seed)
+    return [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+
+
+def run_snapshot(dev, ref, hint, staging_cap, manifest_cap, alias_hint_and_mask=False):
+    n = dev.plan.nchunks
+    dig = torch.zeros(max(1, n), dtype=torch.int64, device="cuda")
+    mask = torch.full((max(1, n),), 0x77, dtype=torch.uint8, device="cuda")
+    if hint is not None and alias_hint_and_mask:
+        mask[:n] = hint[:n]
+        hint = mask
+    staging = torch.full((staging_cap + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    manifest = torch.full((manifest_cap * 32 + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    misses = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ws = torch.full((ck.snapshot_workspace_bytes(n),), 0x11, dtype=torch.uint8, device="cuda")
+    ck.snapshot(dev.plan, ref, hint, dig, mask, staging, manifest, counts, misses, ws,
+                staging_cap=staging_cap, manifest_cap=manifest_cap,
+                n_ref=None if ref is None else n)
+    torch.cuda.synchronize()
+    return dig, mask, staging, manifest, counts_dict(counts), int(misses.item())
+
+
+def check_against_oracle(snap, ref_bufs, chunk, hint_kind, staging_cap=None, manifest_cap=None,
+                         alias=False):
+    dev = DeviceBuffers(snap, chunk)
+    n = dev.plan.nchunks
+    o_dig = oracle.fingerprint(snap, chunk, 8)
+    o_ref = None if ref_bufs is None else oracle.fingerprint(ref_bufs, chunk, 8)
+    o_mask, o_cnt = oracle.diff(snap, chunk, o_dig, o_ref)
+    o_st, o_man, o_cnt2 = oracle.compact(snap, chunk, o_mask, o_dig, staging_cap=staging_cap,
+                                         manifest_cap=manifest_cap)
+    rng = np.random.default_rng(n)
+    if hint_kind == "exact":
+        h = o_mask.copy()
+    elif hint_kind == "none":
+        h = None
+    elif hint_kind == "ones":
+        h = np.ones(n, dtype=np.uint8)
+    elif hint_kind == "zeros":
+        h = np.zeros(n, dtype=np.uint8)
+    elif hint_kind == "one_flip":
+        h = o_mask.copy()
+        h[n // 2] ^= 1
+    else:
+        h = (rng.random(n) < 0.5).astype(np.uint8) * 7          # any non-zero byte marks
+    hint = None if h is None else torch.from_numpy(h if h.size else np.zeros(1, np.uint8)).cuda()
+    ref = None if o_ref is None else torch.from_numpy(o_ref.view(np.int64)).cuda()
+    dig, mask, staging, manifest, cnt, misses = run_snapshot(
+        dev, ref, hint, o_st.size, o_man.size, alias_hint_and_mask=alias)
+    assert np.array_equal(u64(dig, n), o_dig)
+    assert np.array_equal(mask[:n].cpu().numpy(), o_mask)
+    assert cnt == o_cnt2
+    want_misses = 0 if h is None else int(((h != 0) != (o_mask != 0)).sum())
+    assert misses == want_misses
+    man_raw = manifest.cpu().numpy()
+    assert np.array_equal(man_raw[:32 * o_man.size].view(oracle.ENTRY_DTYPE), o_man)
+    assert np.all(man_raw[32 * o_man.size:] == 0xA5)
+    st = staging.cpu().numpy()
+    if want_misses == 0:
+        # single pass: exactly the oracle's staging, unwritten bytes included
+        assert np.array_equal(st[:o_st.size], o_st)
+    elif staging_cap is None and manifest_cap is None:
+        # wrong hint, enough room: the gather that followed made the staged range exact
+        assert np.array_equal(st[:o_cnt2["staged_bytes"]], o_st)
+    assert np.all(st[o_st.size:] == 0xA5)                      # never past the capacity
+    assert dev.canaries_intact()
+    return cnt, misses
+
+
+HINTS = ["exact", "none", "ones", "zeros", "one_flip", "random"]
+
+
+@pytest.mark.parametrize("hint_kind", HINTS)
+@pytest.mark.parametrize("chunk", [256, 4096])
+def test_snapshot_against_reference(chunk, hint_kind):
+    ref = host_bufs(2, ODD_SIZES)
+    snap = [b.copy() for b in ref]
+    rng = np.random.default_rng(3)
+    for i, b in enumerate(snap):
+        if b.size and i % 3 == 0:
+            for off in rng.integers(0, b.size, size=3):
+                b[off] ^= 0x5A
+    snap[23][99999] ^= 1
+    cnt, misses = check_against_oracle(snap, ref, chunk, hint_kind)
+    assert 0 < cnt["ndirty"] < oracle.nchunks(snap, chunk)
+    assert (misses == 0) == (hint_kind in ("exact", "none"))
+
+
+@pytest.mark.parametrize("hint_kind", ["exact", "ones", "zeros"])
+def test_snapshot_without_reference(hint_kind):
+    cnt, misses = check_against_oracle(host_bufs(1, ODD_SIZES), None, 1024, hint_kind)
+    assert cnt["ndirty"] == oracle.nchunks(host_bufs(1, ODD_SIZES), 1024)
+    assert (misses == 0) == (hint_kind != "zeros")
+
+
+def test_snapshot_hint_and_mask_in_one_buffer():
+    ref = host_bufs(4, ODD_SIZES)
+    snap = [b.copy() for b in ref]
+    snap[15][7] ^= 1
+    snap[28][200000] ^= 1
+    check_against_oracle(snap, ref, 4096, "exact", alias=True)
+    check_against_oracle(snap, ref, 4096, "random", alias=True)
+
+
+@pytest.mark.parametrize("caps", [(700, None), (None, 5), (0, 0), (1024, 3)])
+@pytest.mark.parametrize("hint_kind", ["exact", "ones"])
+def test_snapshot_capacity_limits(caps, hint_kind):
+    snap = host_bufs(8, [1000, 1000, 5000, 4096 * 3 + 1])
+    n = oracle.nchunks(snap, 256)
+    staging_cap, manifest_cap = caps
+    full_st, full_man, _ = oracle.compact(snap, 256, np.ones(n, np.uint8),
+                                          oracle.fingerprint(snap, 256))
+    check_against_oracle(snap, None, 256, hint_kind,
+                         staging_cap=full_st.size if staging_cap is None else staging_cap,
+                         manifest_cap=n if manifest_cap is None else manifest_cap)
+
+
+def test_snapshot_config1_full_size_exact_hint_single_pass():
+    w = wl.config(1)
+    rep0, rep1 = wl.numpy_replica(w, 0), wl.numpy_replica(w, 1)
+    cnt, misses = check_against_oracle(rep1, rep0, w.chunk, "exact")
+    assert misses == 0 and cnt["staged_bytes"] == w.distinct_bytes
+
+
+def test_snapshot_empty_plan_and_argument_errors():
+    check_against_oracle([], None, 4096, "exact")
+    dev = DeviceBuffers(host_bufs(9, [4096]), 1024)
+    t = lambda n, dt=torch.uint8: torch.zeros(n, dtype=dt, device="cuda")
+    with pytest.raises(ck.CkptError) as e:     # workspace too small for a hinted call
+        ck.snapshot(dev.plan, None, t(4), t(4, torch.int64), t(4), t(4096), t(4 * 32),
+                    t(3, torch.int64), None, t(16))
+    assert e.value.status == -5
+    with pytest.raises(ck.CkptError) as e:     # reference of another geometry
+        ck.snapshot(dev.plan, t(3, torch.int64), None, t(4, torch.int64), t(4), t(4096),
+                    t(4 * 32), t(3, torch.int64), n_ref=3)
+    assert e.value.status == -4
