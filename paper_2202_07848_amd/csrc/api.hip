@@ -340,7 +340,7 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
     e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, misses, s);
   if (e == hipSuccess && d_hint_misses != nullptr) {
     if (misses != nullptr)
-      e = hipMemcpyAsync(d_hint_misses, misses, sizeof(uint64_t), hipMemcpyDeviceToDevice, s);
+      e = ckpt::launch_copy_u64(d_hint_misses, misses, s);   // a kernel, so the call stays capturable
     else
       e = ckpt::launch_zero_u64(d_hint_misses, s);
   }

@@ -118,6 +118,7 @@ hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_man
                         uint64_t nentries, void *d_ring, uint64_t b0, uint64_t b1,
                         uint64_t *d_rejected, hipStream_t s);
 hipError_t launch_zero_u64(uint64_t *d_value, hipStream_t s);
+hipError_t launch_copy_u64(uint64_t *d_dst, const uint64_t *d_src, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
 

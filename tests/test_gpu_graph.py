@@ -1,0 +1,74 @@
+"""The data calls only enqueue kernels (no allocation, no host synchronisation,
+no memset or memcpy nodes), so a whole snapshot + restore can be captured in a
+HIP graph and replayed -- what a launch-bound context switch over few small
+buffers wants.  Every replay is checked against the eager result, with eager
+work and synchronisations between replays."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_07848_amd import binding as ck
+from gpu_util import DeviceBuffers, counts_dict, u64
+
+pytestmark = pytest.mark.gpu
+
+
+def test_snapshot_and_restore_replay_from_a_hip_graph():
+    chunk = 4096
+    rng = np.random.default_rng(1)
+    sizes = [300000, 4096, 70001, 0, 123456]
+    ref_host = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+    snap_host = [b.copy() for b in ref_host]
+    snap_host[0][5000] ^= 1
+    snap_host[2][70000] ^= 1
+    snap_host[4][::4100] ^= 3
+    snap, dst = DeviceBuffers(snap_host, chunk), DeviceBuffers(ref_host, chunk)
+    n = snap.plan.nchunks
+    o_ref = oracle.fingerprint(ref_host, chunk)
+    ref = torch.from_numpy(o_ref.view(np.int64)).cuda()
+    dig = torch.zeros(n, dtype=torch.int64, device="cuda")
+    mask = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    misses = torch.zeros(1, dtype=torch.int64, device="cuda")
+    staging = torch.zeros(n * chunk, dtype=torch.uint8, device="cuda")
+    manifest = torch.zeros(n * 32, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+
+    def enqueue(stream):
+        ck.snapshot(snap.plan, ref, mask, dig, mask, staging, manifest, counts, misses, ws,
+                    stream=stream)
+        # the entry count is a host-side launch parameter, so it is fixed at capture time
+        ck.restore(dst.plan, staging, staging.numel(), manifest, want_cnt["ndirty"], stream=stream)
+
+    o_dig = oracle.fingerprint(snap_host, chunk)
+    o_mask, _ = oracle.diff(snap_host, chunk, o_dig, o_ref)
+    o_st, o_man, want_cnt = oracle.compact(snap_host, chunk, o_mask, o_dig)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(side)                                   # eager warm-up on the capture stream
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(side)
+    torch.cuda.synchronize()
+
+    for replay in range(4):
+        # eager work between replays: scribble over every output and the destination
+        dig.zero_(); counts.fill_(-1); staging.fill_(0xEE); manifest.fill_(0xEE)
+        mask.copy_(torch.from_numpy(o_mask).cuda() if replay % 2 else torch.zeros_like(mask))
+        dst.arena.copy_(DeviceBuffers(ref_host, chunk).arena)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(u64(dig, n), o_dig), replay
+        assert np.array_equal(mask.cpu().numpy(), o_mask), replay
+        assert counts_dict(counts) == want_cnt, replay
+        assert int(misses.item()) == (0 if replay % 2 else int(o_mask.sum())), replay
+        assert np.array_equal(staging.cpu().numpy()[:o_st.size], o_st), replay
+        assert np.array_equal(ck.manifest_to_numpy(manifest, want_cnt["ndirty"]), o_man), replay
+        got, img = dst.host()
+        assert all(np.array_equal(g, s) for g, s in zip(got, snap_host)), replay
+        assert dst.canaries_intact(img)
