@@ -119,6 +119,26 @@ def test_single_long_ragged_chunk():
     full_pipeline_check(host_bufs(7, [3 * 1024 * 1024 + 5, 100]), None, 4 * 1024 * 1024)
 
 
+def test_maximum_chunk_size():
+    # the largest chunk the plan accepts (1 GiB): one full chunk hashed by a single quad of
+    # lanes for 2**25 stripes, and a short second chunk that ends mid-stripe
+    chunk = 1 << 30
+    rng = np.random.default_rng(11)
+    big = rng.integers(0, 256, size=chunk + 4096 + 5, dtype=np.uint8)
+    dev = DeviceBuffers([big], chunk)
+    assert dev.plan.nchunks == 2
+    dig = run_fingerprint(dev.plan)
+    assert np.array_equal(u64(dig, 2), oracle.fingerprint([big], chunk, 2))
+    # only the short chunk is marked: compact and restore it
+    mask = torch.tensor([0, 1], dtype=torch.uint8, device="cuda")
+    staging, manifest, counts = run_compact(dev.plan, mask, dig, 4112, 1)
+    assert counts_dict(counts) == {"ndirty": 1, "staged_bytes": 4112, "overflow": 0}
+    st = staging.cpu().numpy()
+    assert np.array_equal(st[:4101], big[chunk:]) and not st[4101:4112].any()
+    man = ck.manifest_to_numpy(manifest, 1)
+    assert (int(man["buf"][0]), int(man["len"][0]), int(man["buf_off"][0])) == (0, 4101, chunk)
+
+
 def test_config1_tiny_spliced_pair_full_size():
     w = wl.config(1)
     rep0, rep1 = wl.numpy_replica(w, 0), wl.numpy_replica(w, 1)
