@@ -233,11 +233,33 @@ int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_
  * does not exist, is not earlier (duplicates), or has another length is skipped
  * and counted in *d_rejected (optional, device uint64).
  * ref_plan's buffers must not overlap dst_plan's unless every match is in place
- * (moves inside one memory image would need the phased copy the paper
- * describes; not provided).  d_src must come from ckpt_match.
+ * (for moves inside one memory image use ckpt_apply_moves_inplace).  ref_plan may
+ * be NULL: then only the duplicates are filled in.  d_src must come from ckpt_match.
  * Errors: INVALID_ARG, CHUNK (the plans' chunk sizes differ), ALIGNMENT, DEVICE. */
 int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
                        const int64_t *d_src, uint64_t *d_rejected, void *stream);
+
+/* The moves when the destination IS the reference's memory (sec. 5.2.1: the
+ * buffers of the rank that ran before are turned into those of the rank that runs
+ * next; "cyclic dependencies between source and destination buffers force the
+ * copy to happen in phases").  plan's buffers hold the reference image, chunk for
+ * chunk (n_ref == N); afterwards every chunk k with d_src[k] = j >= 0, j != k holds
+ * what chunk j held BEFORE the call.  Two phases through d_temp break every cycle:
+ * all sources are gathered, then all destinations written.  Chunks with
+ * d_src[k] == k, -1 or <= -2 are not touched: call this first, then ckpt_restore
+ * (new chunks), then ckpt_apply_matches(plan, NULL, ...) (duplicates).
+ *   d_temp       device buffer of temp_cap bytes, 16-byte aligned, not overlapping
+ *                the buffers; needs sum of pad16(len) over the moved chunks
+ *   d_workspace  device scratch, ckpt_moves_workspace_bytes(N) bytes, 16-byte aligned
+ *   d_counts     ndirty = chunks to move, staged_bytes = temp bytes they need,
+ *                overflow != 0 if temp_cap is too small -- then NOTHING is moved
+ *                (half a permutation would lose data)
+ *   d_rejected   optional: moves whose source is no chunk or has another length
+ * Errors: INVALID_ARG, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
+uint64_t ckpt_moves_workspace_bytes(uint64_t nchunks);
+int ckpt_apply_moves_inplace(const ckpt_plan_t *plan, const int64_t *d_src, void *d_temp,
+                             uint64_t temp_cap, void *d_workspace, uint64_t workspace_bytes,
+                             ckpt_counts_t *d_counts, uint64_t *d_rejected, void *stream);
 
 /* ---- swap-out to / swap-in from host memory --------------------------------- */
 

@@ -26,7 +26,8 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_validate_mutations",
+    "ckpt_restore", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
+    "ckpt_validate_mutations",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -88,6 +89,10 @@ def _lib():
         lib.ckpt_match.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp, vp]
         lib.ckpt_apply_matches.restype = ci
         lib.ckpt_apply_matches.argtypes = [vp, vp, vp, vp, vp]
+        lib.ckpt_moves_workspace_bytes.restype = u64
+        lib.ckpt_moves_workspace_bytes.argtypes = [u64]
+        lib.ckpt_apply_moves_inplace.restype = ci
+        lib.ckpt_apply_moves_inplace.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp]
         lib.ckpt_validate_mutations.restype = ci
         lib.ckpt_validate_mutations.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.ckpt_swapper_create.restype = ci
@@ -254,10 +259,29 @@ def match(plan: Plan, digests, ref, workspace, src, mask, counts, stream=None,
                              _ptr(counts), _stream(stream)), "ckpt_match")
 
 
-def apply_matches(dst_plan: Plan, ref_plan: Plan, src, rejected=None, stream=None) -> None:
-    """``ckpt_apply_matches``: device-to-device moves of the matched chunks into dst_plan."""
-    _check(_lib().ckpt_apply_matches(dst_plan._h, ref_plan._h, _ptr(src), _ptr(rejected),
-                                     _stream(stream)), "ckpt_apply_matches")
+def apply_matches(dst_plan: Plan, ref_plan: Optional[Plan], src, rejected=None,
+                  stream=None) -> None:
+    """``ckpt_apply_matches``: device-to-device moves of the matched chunks into dst_plan
+    (ref_plan None: only the duplicates)."""
+    _check(_lib().ckpt_apply_matches(dst_plan._h, None if ref_plan is None else ref_plan._h,
+                                     _ptr(src), _ptr(rejected), _stream(stream)),
+           "ckpt_apply_matches")
+
+
+def moves_workspace_bytes(nchunks: int) -> int:
+    return int(_lib().ckpt_moves_workspace_bytes(nchunks))
+
+
+def apply_moves_inplace(plan: Plan, src, temp, workspace, counts, rejected=None, stream=None,
+                        temp_cap: Optional[int] = None) -> None:
+    """``ckpt_apply_moves_inplace``: two-phase moves inside the memory that holds the reference."""
+    if temp_cap is None:
+        temp_cap = 0 if temp is None else temp.numel() * temp.element_size()
+    _check(_lib().ckpt_apply_moves_inplace(plan._h, _ptr(src), _ptr(temp), temp_cap,
+                                           _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(),
+                                           _ptr(counts), _ptr(rejected), _stream(stream)),
+           "ckpt_apply_moves_inplace")
 
 
 class Swapper:

@@ -385,11 +385,30 @@ int ckpt_match(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_
 
 int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
                        const int64_t *d_src, uint64_t *d_rejected, void *stream) {
-  if (dst_plan == nullptr || ref_plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (dst_plan == nullptr) return CKPT_ERR_INVALID_ARG;
   if (dst_plan->dev.nchunks != 0 && d_src == nullptr) return CKPT_ERR_INVALID_ARG;
-  if (dst_plan->chunk != ref_plan->chunk) return CKPT_ERR_CHUNK;
+  if (ref_plan != nullptr && dst_plan->chunk != ref_plan->chunk) return CKPT_ERR_CHUNK;
   if (!aligned(d_src, 8) || !aligned(d_rejected, 8)) return CKPT_ERR_ALIGNMENT;
-  hipError_t e = ckpt::launch_apply_matches(dst_plan->dev, ref_plan->dev, d_src, d_rejected,
+  hipError_t e = ckpt::launch_apply_matches(dst_plan->dev, ref_plan ? &ref_plan->dev : nullptr,
+                                            d_src, d_rejected, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+uint64_t ckpt_moves_workspace_bytes(uint64_t nchunks) { return ckpt::moves_workspace_bytes(nchunks); }
+
+int ckpt_apply_moves_inplace(const ckpt_plan_t *plan, const int64_t *d_src, void *d_temp,
+                             uint64_t temp_cap, void *d_workspace, uint64_t workspace_bytes,
+                             ckpt_counts_t *d_counts, uint64_t *d_rejected, void *stream) {
+  if (plan == nullptr || d_counts == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && d_src == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (temp_cap != 0 && d_temp == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_src, 8) || !aligned(d_temp, 16) || !aligned(d_workspace, 16) ||
+      !aligned(d_counts, 8) || !aligned(d_rejected, 8))
+    return CKPT_ERR_ALIGNMENT;
+  if (workspace_bytes < ckpt::moves_workspace_bytes(n)) return CKPT_ERR_CAPACITY;
+  hipError_t e = ckpt::launch_moves_inplace(plan->dev, d_src, d_temp, temp_cap, d_workspace,
+                                            plan->d_blocksums, d_counts, d_rejected,
                                             static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }

@@ -112,8 +112,12 @@ uint64_t match_workspace_bytes(uint64_t n_ref, uint64_t n);
 hipError_t launch_match(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
                         uint64_t n_ref, void *d_workspace, int64_t *d_src, uint8_t *d_mask,
                         ckpt_match_counts_t *d_counts, hipStream_t s);
-hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev &refp, const int64_t *d_src,
+hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev *refp, const int64_t *d_src,
                                 uint64_t *d_rejected, hipStream_t s);
+uint64_t moves_workspace_bytes(uint64_t n);
+hipError_t launch_moves_inplace(const PlanDev &p, const int64_t *d_src, void *d_temp,
+                                uint64_t temp_cap, void *d_workspace, uint64_t *d_blocksums,
+                                ckpt_counts_t *d_counts, uint64_t *d_rejected, hipStream_t s);
 hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_manifest,
                         uint64_t nentries, void *d_ring, uint64_t b0, uint64_t b1,
                         uint64_t *d_rejected, hipStream_t s);

@@ -194,6 +194,70 @@ __global__ __launch_bounds__(COPY_THREADS) void k_apply_matches(PlanDev dstp, Pl
   }
 }
 
+// ---- moves inside one memory image ------------------------------------------
+// When the destination already holds the reference (the paper's case: the next
+// rank's data is assembled in the memory the previous rank left), chunk k must
+// receive what chunk src[k] held *before* anything was overwritten, and moves
+// can form cycles (a -> b -> a).  Two phases through a temporary buffer break
+// every cycle: first all sources are gathered, then all destinations written.
+
+__global__ __launch_bounds__(256) void k_mark_moves(const int64_t *__restrict__ src, uint64_t n,
+                                                    uint8_t *__restrict__ moved) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) {
+    const int64_t s = src[k];
+    moved[k] = (s >= 0 && (uint64_t)s != k) ? 1 : 0;
+  }
+}
+
+// moves[e] (written by the manifest scan with the src array in place of the digests) names
+// destination chunk (buf, buf_off), its place in temp (stage_off) and, in `digest`, the source
+// chunk id.  SCATTER = false: source chunk -> temp.  SCATTER = true: temp -> destination chunk.
+// Nothing is done unless every move fits temp (counts->overflow == 0): half a permutation
+// would destroy sources that have not been read yet.
+template <bool SCATTER>
+__global__ __launch_bounds__(COPY_THREADS) void k_moves(PlanDev p,
+                                                        const ckpt_entry_t *__restrict__ moves,
+                                                        const ckpt_counts_t *__restrict__ counts,
+                                                        uint8_t *__restrict__ temp,
+                                                        unsigned long long *rejected) {
+  if (counts->overflow != 0) return;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
+  const uint64_t nitems = counts->ndirty << ppc_log2;
+  for (uint64_t item = (uint64_t)blockIdx.x * (COPY_THREADS / 64) + wave_in_group; item < nitems;
+       item += nwaves) {
+    const ckpt_entry_t ent = moves[item >> ppc_log2];
+    const uint32_t piece = (uint32_t)(item & ((1ull << ppc_log2) - 1));
+    const uint32_t lo = piece << piece_log2;
+    uint32_t hi = lo + (1u << piece_log2);
+    const uint32_t padded = (uint32_t)pad16(ent.len);
+    if (hi > padded) hi = padded;
+    uint8_t *slot = temp + ent.stage_off;
+    if (SCATTER) {
+      uint8_t *to = reinterpret_cast<uint8_t *>(p.list_ptr[ent.buf]) + ent.buf_off;
+      move_piece<false>(slot, to, lo, hi, ent.len, lane);
+    } else {
+      const uint64_t j = ent.digest;                      // source chunk id
+      bool ok = j < p.nchunks;
+      ChunkRef from = {0, 0, 0};
+      if (ok) {
+        from = locate_chunk(p, j);
+        ok = from.len == ent.len;
+      }
+      if (!ok) {          // leaves the slot's old bytes; counted so that the caller can tell
+        if (rejected != nullptr && piece == 0 && lane == 0) atomicAdd(rejected, 1ull);
+        continue;
+      }
+      const uint8_t *sp = reinterpret_cast<const uint8_t *>(p.dense_ptr[from.row]) + from.off;
+      move_piece<true>(sp, slot, lo, hi, ent.len, lane);
+    }
+  }
+}
+
 __global__ void k_zero_rejected(unsigned long long *p) { *p = 0; }
 
 inline uint64_t pow2_at_least(uint64_t x) {
@@ -241,7 +305,35 @@ hipError_t launch_match(const PlanDev &p, const uint64_t *d_dig, const uint64_t 
   return hipGetLastError();
 }
 
-hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev &refp, const int64_t *d_src,
+uint64_t moves_workspace_bytes(uint64_t n) { return ((n + 15) & ~15ull) + 32 * n + 64; }
+
+hipError_t launch_moves_inplace(const PlanDev &p, const int64_t *d_src, void *d_temp,
+                                uint64_t temp_cap, void *d_workspace, uint64_t *d_blocksums,
+                                ckpt_counts_t *d_counts, uint64_t *d_rejected, hipStream_t s) {
+  unsigned long long *rej = reinterpret_cast<unsigned long long *>(d_rejected);
+  if (rej) hipLaunchKernelGGL(k_zero_rejected, dim3(1), dim3(1), 0, s, rej);
+  const uint64_t n = p.nchunks;
+  uint8_t *moved = static_cast<uint8_t *>(d_workspace);
+  ckpt_entry_t *moves = reinterpret_cast<ckpt_entry_t *>(moved + ((n + 15) & ~15ull));
+  uint32_t groups = (uint32_t)((n + 255) / 256);
+  if (groups > 4096) groups = 4096;
+  if (groups) hipLaunchKernelGGL(k_mark_moves, dim3(groups), dim3(256), 0, s, d_src, n, moved);
+  // the manifest scan, with src[k] travelling in the digest field of each entry
+  hipError_t e = launch_compact_scan(p, moved, reinterpret_cast<const uint64_t *>(d_src), temp_cap,
+                                     moves, n, d_blocksums, d_counts, s);
+  if (e != hipSuccess || n == 0) return e;
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint64_t items = n << (p.chunk_log2 - piece_log2);
+  uint64_t cgroups = (items + COPY_THREADS / 64 - 1) / (COPY_THREADS / 64);
+  if (cgroups > COPY_MAX_GROUPS) cgroups = COPY_MAX_GROUPS;
+  hipLaunchKernelGGL(k_moves<false>, dim3((uint32_t)cgroups), dim3(COPY_THREADS), 0, s, p, moves,
+                     d_counts, static_cast<uint8_t *>(d_temp), rej);
+  hipLaunchKernelGGL(k_moves<true>, dim3((uint32_t)cgroups), dim3(COPY_THREADS), 0, s, p, moves,
+                     d_counts, static_cast<uint8_t *>(d_temp), rej);
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev *refp, const int64_t *d_src,
                                 uint64_t *d_rejected, hipStream_t s) {
   unsigned long long *rej = reinterpret_cast<unsigned long long *>(d_rejected);
   if (rej) hipLaunchKernelGGL(k_zero_rejected, dim3(1), dim3(1), 0, s, rej);
@@ -252,10 +344,11 @@ hipError_t launch_apply_matches(const PlanDev &dstp, const PlanDev &refp, const 
   if (groups > COPY_MAX_GROUPS) groups = COPY_MAX_GROUPS;
   // first everything that comes from the reference, then the duplicates, which may
   // read destination chunks the first pass (or an earlier restore) has written
-  hipLaunchKernelGGL(k_apply_matches<true>, dim3((uint32_t)groups), dim3(COPY_THREADS), 0, s, dstp,
-                     refp, d_src, rej);
+  if (refp != nullptr)
+    hipLaunchKernelGGL(k_apply_matches<true>, dim3((uint32_t)groups), dim3(COPY_THREADS), 0, s, dstp,
+                       *refp, d_src, rej);
   hipLaunchKernelGGL(k_apply_matches<false>, dim3((uint32_t)groups), dim3(COPY_THREADS), 0, s, dstp,
-                     refp, d_src, rej);
+                     dstp, d_src, rej);
   return hipGetLastError();
 }
 

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_2202_07848_amd import binding as ck
-from gpu_util import DeviceBuffers, run_compact, run_fingerprint, u64
+from gpu_util import DeviceBuffers, counts_dict, run_compact, run_fingerprint, u64
 from test_oracle_match import make_case
 
 pytestmark = pytest.mark.gpu
@@ -128,3 +128,76 @@ def test_apply_matches_rejects_impossible_sources_and_checks_arguments():
                  torch.zeros(3, dtype=torch.uint8, device="cuda"),
                  torch.zeros(6, dtype=torch.int64, device="cuda"))
     assert e.value.status == -5
+
+
+def permuted_case(rng, chunk):
+    """Same geometry for reference and snapshot; the snapshot's chunks are the reference's
+    after a permutation with 2-cycles and 3-cycles, plus new, duplicated and unchanged chunks."""
+    sizes = [6 * chunk, 3 * chunk + 100, 5 * chunk, 2 * chunk + 100, 4 * chunk]
+    ref = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+    snap = [b.copy() for b in ref]
+
+    def ch(bufs, b, j):
+        return bufs[b][j * chunk:(j + 1) * chunk]
+
+    # 2-cycle, 3-cycle, a chain into a chunk that becomes new, the two equal-length tails swapped
+    snap[0][0:chunk], snap[2][0:chunk] = ch(ref, 2, 0).copy(), ch(ref, 0, 0).copy()
+    snap[0][chunk:2 * chunk] = ch(ref, 2, 1)
+    snap[2][chunk:2 * chunk] = ch(ref, 4, 1)
+    snap[4][chunk:2 * chunk] = ch(ref, 0, 1)
+    snap[4][2 * chunk:3 * chunk] = ch(ref, 4, 3)
+    fresh = rng.integers(0, 256, size=chunk, dtype=np.uint8)
+    snap[4][3 * chunk:4 * chunk] = fresh
+    snap[0][5 * chunk:6 * chunk] = fresh
+    snap[1][3 * chunk:], snap[3][2 * chunk:] = ref[3][2 * chunk:].copy(), ref[1][3 * chunk:].copy()
+    return ref, snap
+
+
+@pytest.mark.parametrize("chunk", [256, 65536])
+def test_moves_inside_one_memory_image(chunk):
+    rng = np.random.default_rng(chunk)
+    ref, snap = permuted_case(rng, chunk)
+    d_snap = DeviceBuffers(snap, chunk)
+    image = DeviceBuffers(ref, chunk)                 # holds the reference; becomes the snapshot
+    n = image.plan.nchunks
+    rdig, sdig = run_fingerprint(image.plan), run_fingerprint(d_snap.plan)
+    o_rdig, o_sdig = oracle.fingerprint(ref, chunk), oracle.fingerprint(snap, chunk)
+    want_src, want_mask, want_cnt = oracle.match(snap, chunk, o_sdig, o_rdig)
+    src, mask, cnt = run_match(d_snap.plan, sdig, rdig, n)
+    assert np.array_equal(src[:n].cpu().numpy(), want_src) and cnt == want_cnt
+    assert cnt["nmoved"] >= 8 and cnt["ndup"] == 1 and cnt["nnew"] == 1
+    want_st, want_man, _ = oracle.compact(snap, chunk, want_mask, o_sdig)
+    staging, manifest, _ = run_compact(d_snap.plan, mask, sdig, want_st.size, want_man.size)
+
+    moved = (want_src >= 0) & (want_src != np.arange(n))
+    lens = oracle.chunk_lens(snap, chunk).astype(np.int64)
+    need = int(((lens + 15) // 16 * 16)[moved].sum())
+    temp = torch.full((need + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ck.moves_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+
+    # too little room: nothing at all may move
+    ck.apply_moves_inplace(image.plan, src, temp, ws, counts, rejected, temp_cap=need - 16)
+    torch.cuda.synchronize()
+    c = counts_dict(counts)
+    assert c["ndirty"] == int(moved.sum()) and c["staged_bytes"] == need and c["overflow"] > 0
+    got, _ = image.host()
+    assert all(np.array_equal(g, r) for g, r in zip(got, ref))
+
+    ck.apply_moves_inplace(image.plan, src, temp, ws, counts, rejected, temp_cap=need)
+    ck.restore(image.plan, staging, want_st.size, manifest, want_man.size)
+    ck.apply_matches(image.plan, None, src)
+    torch.cuda.synchronize()
+    assert counts_dict(counts) == {"ndirty": int(moved.sum()), "staged_bytes": need, "overflow": 0}
+    assert int(rejected.item()) == 0
+    assert bool((temp[need:] == 0xA5).all())
+    # the oracle rebuilds out of place: sources are read from an untouched copy of the reference
+    want = [b.copy() for b in ref]
+    assert oracle.restore(want, chunk, want_st, want_man) == 0
+    assert oracle.apply_matches(want, ref, chunk, want_src) == 0
+    got, img = image.host()
+    for g, w, s in zip(got, want, snap):
+        assert np.array_equal(g, w) and np.array_equal(g, s)
+    assert image.canaries_intact(img)
+
