@@ -5,8 +5,8 @@
 // calibrate bandwidth and HBM counters.
 //
 // Work item = one piece (min(C, 16 KiB)) of one manifest entry, handled by one
-// wavefront: 64 lanes x 16 B = 1 KiB per instruction, four loads in flight per
-// lane.  Items are dealt to wavefronts round-robin (item = wave id + i * number
+// wavefront: 64 lanes x 16 B = 1 KiB per instruction, all sixteen loads of a
+// piece issued before its stores, non-temporal both ways.  Items are dealt to wavefronts round-robin (item = wave id + i * number
 // of waves), so neighbouring waves stream neighbouring 16 KiB pieces of source
 // and staging.  The gather does not know the entry count on the host (it sits
 // in device memory right after the scan), so the grid is fixed and every wave

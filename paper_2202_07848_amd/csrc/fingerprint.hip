@@ -4,23 +4,28 @@
 //
 // Mapping.  XXH64 offers four independent chains per chunk and nothing more, so
 // a wavefront takes GROUP = 16 chunks of equal (or, for short last chunks,
-// similar) length and gives each chunk a quad of lanes: lane 4c+t owns accumulator t of chunk c.  That lane needs the t-th
-// 8-byte word of every 32-byte stripe -- 8 bytes at stride 32 -- which is the
-// opposite of what coalesces.  So the wave loads in a different role: each
-// global_load_dwordx4 instruction fetches 256 contiguous bytes (one TILE) from
-// each of four chunks, 16 lanes x 16 B per chunk, the tile goes through LDS,
-// and the hashing lanes read their words back with ds_read_b64.  Tiles are
-// prefetched DEPTH deep in registers, so LDS only ever holds the tile being
-// hashed (4.5 KiB per wave).  Loads are never inside a branch: a loader lane
-// with nothing left to fetch reads a 256-byte spare block owned by the plan.
-// The workgroup is a single wavefront: LDS traffic of one wave is executed in order, so only compiler-level (wavefront-scope)
-// fences are needed between the write and read phases, never s_barrier and
-// never a wait on outstanding global loads.
+// similar) length and gives each chunk a quad of lanes: lane 4c+t owns
+// accumulator t of chunk c.  That lane needs the t-th 8-byte word of every
+// 32-byte stripe -- 8 bytes at stride 32 -- which is the opposite of what
+// coalesces.  So the wave loads in a different role: each global_load_dwordx4
+// instruction fetches 256 contiguous bytes (one TILE) from each of four chunks,
+// 16 lanes x 16 B per chunk, the tile goes through LDS, and the hashing lanes
+// read their words back with ds_read2_b64.  Tiles are prefetched DEPTH deep in
+// registers, so LDS only ever holds the tile being hashed (4.5 KiB per wave).
+// Loads are never inside a branch: a loader lane with nothing left to fetch
+// reads a 256-byte spare block owned by the plan.  The workgroup is a single
+// wavefront: LDS traffic of one wave is executed in order, so only
+// compiler-level (wavefront-scope) fences are needed between the write and
+// read phases, never s_barrier and never a wait on outstanding global loads.
 //
 // A chunk of length len is split as  full tiles | up to 7 stripes | < 32 bytes.
 // The tile loop is wave-uniform up to the longest chunk in the group; lanes of
 // shorter chunks are masked.  Residual stripes and the tail are read straight
 // from global memory (they are < 256 bytes per chunk).
+//
+// The same kernel, instantiated with STAGE, is the single pass of
+// ckpt_snapshot: the loader lanes also write each tile of a hinted chunk to its
+// place in the staging buffer from the registers they loaded it into.
 #include "ckpt_internal.h"
 #include "stream_copy.h"
 #include "xxh64_device.h"
