@@ -38,7 +38,9 @@ class Rep:
                 for o, b in zip(self.offs, self.w.bufs)]
 
 
-def snapshot(rep, ref):
+def snapshot(rep, ref, fused=False):
+    """The launch configurations bench.py times: three calls, or (fused) one ckpt_snapshot whose
+    hint is the mask of a previous snapshot of the same state."""
     n = rep.plan.nchunks
     dig = torch.zeros(n, dtype=torch.int64, device="cuda")
     mask = torch.zeros(n, dtype=torch.uint8, device="cuda")
@@ -49,8 +51,17 @@ def snapshot(rep, ref):
     ndirty, staged = int(counts[0]), int(counts[1])
     staging = torch.empty(max(16, staged), dtype=torch.uint8, device="cuda")
     manifest = torch.empty(max(1, ndirty) * 32, dtype=torch.uint8, device="cuda")
-    ck.compact(rep.plan, mask, dig, staging, manifest, counts, staging_cap=staged,
-               manifest_cap=ndirty)
+    if fused:
+        misses = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        dig.zero_()
+        ck.snapshot(rep.plan, ref, mask, dig, mask, staging, manifest, counts, misses, ws,
+                    staging_cap=staged, manifest_cap=ndirty)
+        torch.cuda.synchronize()
+        assert int(misses.item()) == 0
+    else:
+        ck.compact(rep.plan, mask, dig, staging, manifest, counts, staging_cap=staged,
+                   manifest_cap=ndirty)
     torch.cuda.synchronize()
     c = counts.cpu().numpy().view(np.uint64)
     assert (int(c[0]), int(c[1]), int(c[2])) == (ndirty, staged, 0)
@@ -145,8 +156,9 @@ def test_config2_full_size_exact_against_oracle():
     assert device_equal(r0, r1)
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "fused"])
 @pytest.mark.parametrize("cfg", [5, 4])
-def test_replica_configs_full_size_sampled(cfg):
+def test_replica_configs_full_size_sampled(cfg, fused):
     w = wl.config(cfg)
     a0, offs = wl.torch_replica(w, 0, "cuda")
     r0 = Rep(w, a0, offs)
@@ -160,7 +172,7 @@ def test_replica_configs_full_size_sampled(cfg):
     for r in range(1, w.nreplicas):
         a, _ = wl.torch_replica(w, r, "cuda", shared_from=a0)
         rep = Rep(w, a, offs)
-        dig, mask, staging, manifest, ndirty, staged = snapshot(rep, ref)
+        dig, mask, staging, manifest, ndirty, staged = snapshot(rep, ref, fused)
         check_sampled(w, rep, dig, mask, staging, manifest, ndirty, staged, expect, 100 * cfg + r)
         staged_sizes.append(staged)
         if r == w.nreplicas - 1:
@@ -182,6 +194,7 @@ def test_replica_configs_full_size_sampled(cfg):
 
 @pytest.mark.parametrize("fraction", [0.01, 0.10, 0.50])
 def test_config3_full_size_sampled(fraction):
+    fused = fraction >= 0.2            # as bench.py chooses
     w = wl.config(3)
     a0, offs = wl.torch_replica(w, 0, "cuda")
     t0 = Rep(w, a0, offs)
@@ -196,7 +209,7 @@ def test_config3_full_size_sampled(fraction):
     t1 = Rep(w, a1, offs)
     expect = np.zeros(n, dtype=bool)
     expect[ids] = True
-    dig, mask, staging, manifest, ndirty, staged = snapshot(t1, ref)
+    dig, mask, staging, manifest, ndirty, staged = snapshot(t1, ref, fused)
     assert ndirty == ids.size == round(fraction * n)
     check_sampled(w, t1, dig, mask, staging, manifest, ndirty, staged, expect, 300 + step)
     # the all-zero 4 KiB chunks of t0 carry the stored vector for 4096 zero bytes
