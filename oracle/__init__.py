@@ -77,6 +77,8 @@ def _load():
         lib.ora_apply_matches.argtypes = [vp, u64, vp, u64, u64, vp]
         lib.ora_validate_mutations.restype = None
         lib.ora_validate_mutations.argtypes = [u64, vp, vp, vp, vp, vp]
+        lib.ora_upload_owners.restype = ctypes.c_int
+        lib.ora_upload_owners.argtypes = [vp, u64, u64, vp, ctypes.c_uint32, ctypes.c_uint32, vp, vp]
         lib.ora_restore.restype = ctypes.c_uint64
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         _lib = lib
@@ -212,6 +214,23 @@ def validate_mutations(before_a, after_a, before_b, after_b) -> dict:
     _load().ora_validate_mutations(arrs[0].size, *[_p(a) for a in arrs], _p(res))
     return {"changed_a": int(res[0]), "changed_b": int(res[1]), "mismatches": int(res[2]),
             "first_mismatch": int(res[3])}
+
+
+def upload_owners(bufs: Sequence[np.ndarray], chunk: int, gathered: np.ndarray,
+                  rank: int) -> Tuple[np.ndarray, dict]:
+    """Which chunks worker ``rank`` uploads, from the checksums of all workers
+    (``gathered`` has shape (world, N)).  Returns (mask[N], counts)."""
+    n = nchunks(bufs, chunk)
+    gathered = np.ascontiguousarray(gathered, dtype=np.uint64)
+    if gathered.ndim != 2 or gathered.shape[1] != n:
+        raise ValueError("gathered checksums must have shape (world, N)")
+    mask = np.zeros(n, dtype=np.uint8)
+    c = _Counts()
+    rc = _load().ora_upload_owners(_desc(bufs), len(bufs), chunk, _p(gathered), gathered.shape[0],
+                                   rank, _p(mask), ctypes.byref(c))
+    if rc != 0:
+        raise ValueError("rank outside the world")
+    return mask, {"ndirty": c.ndirty, "staged_bytes": c.staged_bytes, "overflow": c.overflow}
 
 
 def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np.ndarray,

@@ -514,3 +514,47 @@ void ora_validate_mutations(uint64_t nchunks, const uint64_t *before_a, const ui
   result[2] = bad;
   result[3] = first;
 }
+
+/* ------------------------------------------------- cross-worker upload owner */
+/* Checkpoint de-duplication across workers (sec. 4.6): a worker uploads a
+ * piece of device state only if no other worker uploads the same content.
+ * With the checksums of all `world` workers gathered (gathered[r*N + k] is
+ * worker r's checksum of chunk k; one chunk geometry for all, the replicas
+ * being consistent by sec. 5.2.2), the decision is taken per chunk position
+ * and without further communication: the workers whose checksum at k equals
+ * this worker's form a group, listed by ascending rank; the group's member
+ * number (k mod group size) uploads that content, the others skip it.  Every
+ * distinct content at every position is thus uploaded exactly once, and the
+ * content all replicas share is spread evenly over them.
+ * mask[k] = 1 when worker `rank` uploads chunk k; counts as ora_diff. */
+int ora_upload_owners(const ora_buf_t *bufs, uint64_t nbufs, uint64_t chunk,
+                      const uint64_t *gathered, uint32_t world, uint32_t rank, uint8_t *mask,
+                      ora_counts_t *counts) {
+  if (world == 0 || rank >= world) return -1;
+  uint64_t N = ora_nchunks(bufs, nbufs, chunk);
+  uint64_t k = 0, nup = 0, bytes = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = chunks_of(bufs[i].nbytes, chunk);
+    for (uint64_t j = 0; j < n; ++j, ++k) {
+      uint64_t len = bufs[i].nbytes - j * chunk;
+      if (len > chunk) len = chunk;
+      uint64_t mine = gathered[(uint64_t)rank * N + k];
+      uint32_t size = 0, my_place = 0;
+      for (uint32_t r = 0; r < world; ++r) {
+        if (gathered[(uint64_t)r * N + k] != mine) continue;
+        if (r == rank) my_place = size;
+        size += 1;
+      }
+      uint8_t m = (k % size == my_place) ? 1 : 0;
+      mask[k] = m;
+      if (m) {
+        nup += 1;
+        bytes += pad16(len);
+      }
+    }
+  }
+  counts->ndirty = nup;
+  counts->staged_bytes = bytes;
+  counts->overflow = 0;
+  return 0;
+}

@@ -63,9 +63,74 @@ def pins_hold() -> bool:
         assert oracle.restore(dst, chunk, staging, man) == 0
         for a, d, b in zip(arenas, dst, bufs):
             assert np.array_equal(d, b) and np.all(a[:32] == 0xEE) and np.all(a[32 + b.size:] == 0xEE)
+        owner_pins()
         return True
     except AssertionError:
         return False
+
+
+def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
+    """States of `world` workers: a common base, then per worker a few private rewrites, some of
+    them shared by two workers (so groups of every size between 1 and world appear)."""
+    rng = np.random.default_rng(seed)
+    base = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+    states = [[b.copy() for b in base] for _ in range(world)]
+    for r in range(world):
+        for _ in range(4):
+            i = int(rng.choice([0, 1, 3, 4]))
+            off = int(rng.integers(0, base[i].size))
+            patch = rng.integers(0, 256, size=min(300, base[i].size - off), dtype=np.uint8)
+            for q in {r, int(rng.integers(0, world))}:        # sometimes one more worker gets it
+                states[q][i][off:off + patch.size] = patch
+    return states, chunk
+
+
+def owner_pins():
+    """Cross-worker upload ownership against what its purpose fixes, by brute force:
+    (1) at every chunk position every distinct content is uploaded by exactly one of the workers
+    that hold it; (2) a store filled from the uploads alone restores every worker's state;
+    (3) content all workers share is spread evenly (rank r takes positions k = r mod world);
+    (4) all-different content: every worker uploads everything; (5) a world of one likewise."""
+    for world, seed in ((1, 5), (2, 6), (3, 7), (5, 8)):
+        states, chunk = worker_states(world, seed)
+        digs = np.stack([oracle.fingerprint(st, chunk) for st in states])
+        n = digs.shape[1]
+        lens = oracle.chunk_lens(states[0], chunk)
+        masks, store = [], {}
+        for r in range(world):
+            mask, cnt = oracle.upload_owners(states[r], chunk, digs, r)
+            masks.append(mask)
+            assert cnt["ndirty"] == int(mask.sum())
+            assert cnt["staged_bytes"] == int(((lens[mask == 1] + 15) // 16 * 16).sum())
+            staging, man, _ = oracle.compact(states[r], chunk, mask, digs[r])
+            for e in man:                                      # the upload: keyed by place and checksum
+                key = (int(e["buf"]), int(e["buf_off"]), int(e["digest"]))
+                assert key not in store, "content uploaded twice"
+                store[key] = staging[int(e["stage_off"]):int(e["stage_off"]) + int(e["len"])]
+        masks = np.stack(masks)
+        sizes_seen = set()
+        for k in range(n):
+            for value in set(digs[:, k].tolist()):
+                holders = [r for r in range(world) if int(digs[r, k]) == value]
+                sizes_seen.add(len(holders))
+                assert sum(int(masks[r, k]) for r in holders) == 1
+        assert world < 3 or {1, 2, world} <= sizes_seen         # the input really has mixed groups
+        for r in range(world):                                  # download: rebuild from the store
+            pos = 0
+            for i, b in enumerate(states[r]):
+                for off in range(0, b.size, chunk):
+                    got = store[(i, off, int(digs[r, pos]))]
+                    assert np.array_equal(got, b[off:off + chunk])
+                    pos += 1
+    states, chunk = worker_states(1, 9)
+    same = np.stack([oracle.fingerprint(states[0], chunk)] * 4)
+    for r in range(4):
+        mask, _ = oracle.upload_owners(states[0], chunk, same, r)
+        assert np.array_equal(np.flatnonzero(mask), np.arange(r, same.shape[1], 4))
+    apart = same + np.arange(4, dtype=np.uint64)[:, None]
+    for r in range(4):
+        mask, cnt = oracle.upload_owners(states[0], chunk, apart, r)
+        assert mask.all() and cnt["ndirty"] == same.shape[1]
 
 
 
@@ -74,7 +139,7 @@ def use_library(path):
     good = oracle._load()
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
-               "ora_compact", "ora_restore"):
+               "ora_compact", "ora_restore", "ora_upload_owners"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     oracle._lib = other

@@ -52,6 +52,15 @@ MUTATIONS = [
     ("restore to wrong offset", "(uint8_t *)dst[m->buf].ptr + m->buf_off, in", "(uint8_t *)dst[m->buf].ptr + m->stage_off, in"),
     ("thread split loses the boundary chunk", "if (k < job->k_lo || k >= job->k_hi) continue;",
      "if (k <= job->k_lo || k >= job->k_hi) continue;"),
+    ("owner: lowest rank always uploads", "(k % size == my_place) ? 1 : 0", "(0 == my_place) ? 1 : 0"),
+    ("owner: group taken against rank 0", "uint64_t mine = gathered[(uint64_t)rank * N + k];",
+     "uint64_t mine = gathered[k];"),
+    ("owner: place counted after the increment", "if (r == rank) my_place = size;\n        size += 1;",
+     "size += 1;\n        if (r == rank) my_place = size;"),
+    ("owner: rotation by rank count instead of group size", "(k % size == my_place)",
+     "(k % world == my_place)"),
+    ("owner: row stride of gathered checksums", "if (gathered[(uint64_t)r * N + k] != mine) continue;",
+     "if (gathered[(uint64_t)r * (N - 1) + k] != mine) continue;"),
 ]
 
 
