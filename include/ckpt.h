@@ -128,6 +128,22 @@ int ckpt_fingerprint(const ckpt_plan_t *plan, uint64_t *d_digests, void *stream)
 int ckpt_diff(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t *d_ref,
               uint64_t n_ref, uint8_t *d_mask, ckpt_counts_t *d_counts, void *stream);
 
+/* Which chunks this worker uploads into a checkpoint when `world` workers hold
+ * replicas of the job (sec. 4.6: a worker uploads a buffer only if no other
+ * worker uploads the same content).  d_gathered holds the checksums of all
+ * workers, row r = worker r's N checksums (one chunk geometry for all workers,
+ * as consistent allocation gives, sec. 5.2.2; how the rows were exchanged is
+ * the caller's business).  Per chunk k the workers whose checksum equals this
+ * worker's form a group in ascending rank order, and member number
+ * (k mod group size) uploads:
+ *   d_mask[k] = 1 if that member is `rank`, else 0;  d_counts as ckpt_diff.
+ * Every distinct content at every position is uploaded by exactly one worker;
+ * content shared by all is spread evenly.  The mask feeds ckpt_compact.
+ *   d_gathered  device array of world*N uint64, row-major, 8-byte aligned
+ * Errors: INVALID_ARG (world == 0, rank >= world, NULL), ALIGNMENT, DEVICE. */
+int ckpt_upload_owners(const ckpt_plan_t *plan, const uint64_t *d_gathered, uint32_t world,
+                       uint32_t rank, uint8_t *d_mask, ckpt_counts_t *d_counts, void *stream);
+
 /* Swap-out of what is not de-duplicated (sec. 5.2.1), as a gather into one
  * contiguous staging buffer: walking k upwards, each chunk with d_mask[k] != 0
  * gets the next manifest entry e and the next pad16(len_k) bytes of staging

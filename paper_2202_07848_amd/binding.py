@@ -27,7 +27,7 @@ EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
     "ckpt_restore", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
-    "ckpt_validate_mutations",
+    "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -75,6 +75,8 @@ def _lib():
         lib.ckpt_fingerprint.argtypes = [vp, vp, vp]
         lib.ckpt_diff.restype = ci
         lib.ckpt_diff.argtypes = [vp, vp, vp, u64, vp, vp, vp]
+        lib.ckpt_upload_owners.restype = ci
+        lib.ckpt_upload_owners.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp]
         lib.ckpt_compact.restype = ci
         lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore.restype = ci
@@ -196,6 +198,13 @@ def diff(plan: Plan, digests, ref, mask, counts, stream=None, n_ref: Optional[in
         n_ref = 0 if ref is None else ref.numel()
     _check(_lib().ckpt_diff(plan._h, _ptr(digests), _ptr(ref), n_ref, _ptr(mask), _ptr(counts),
                             _stream(stream)), "ckpt_diff")
+
+
+def upload_owners(plan: Plan, gathered, world: int, rank: int, mask, counts, stream=None) -> None:
+    """``ckpt_upload_owners``: gathered is int64 (world, N) checksums of all workers; mask (uint8, N)
+    marks the chunks worker ``rank`` uploads; counts as for ``diff``."""
+    _check(_lib().ckpt_upload_owners(plan._h, _ptr(gathered), world, rank, _ptr(mask), _ptr(counts),
+                                     _stream(stream)), "ckpt_upload_owners")
 
 
 def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,

@@ -269,6 +269,19 @@ int ckpt_diff(const ckpt_plan_t *plan, const uint64_t *d_digests, const uint64_t
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+int ckpt_upload_owners(const ckpt_plan_t *plan, const uint64_t *d_gathered, uint32_t world,
+                       uint32_t rank, uint8_t *d_mask, ckpt_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (world == 0 || rank >= world) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && (d_gathered == nullptr || d_mask == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_gathered, 8) || !aligned(d_counts, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_upload_owners(plan->dev, d_gathered, world, rank, d_mask,
+                                            plan->d_blocksums, d_counts,
+                                            static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
                  void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
                  uint64_t manifest_cap, ckpt_counts_t *d_counts, void *stream) {

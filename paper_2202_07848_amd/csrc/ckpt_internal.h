@@ -106,6 +106,9 @@ hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
                           hipStream_t s);
+hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
+                                uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
+                                ckpt_counts_t *d_counts, hipStream_t s);
 hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a, const uint64_t *b_b,
                            const uint64_t *a_b, ckpt_validation_t *d_result, hipStream_t s);
 uint64_t match_workspace_bytes(uint64_t n_ref, uint64_t n);

@@ -99,6 +99,39 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t
   }
 }
 
+// Cross-worker upload ownership (sec. 4.6): gathered holds `world` rows of N
+// checksums.  The workers whose checksum at k equals this worker's form a
+// group in rank order; member number (k mod group size) uploads the chunk.
+// A thread reads `world` values per chunk, each row access coalesced over k.
+__global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
+    PlanDev p, const uint64_t *__restrict__ gathered, uint32_t world, uint32_t rank,
+    uint8_t *__restrict__ mask, uint64_t *__restrict__ blocksums) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  int n = 0;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    if (k < p.nchunks) {
+      const uint64_t mine = gathered[(uint64_t)rank * p.nchunks + k];
+      uint32_t size = 0, place = 0;
+      for (uint32_t r = 0; r < world; ++r) {
+        const bool same = gathered[(uint64_t)r * p.nchunks + k] == mine;
+        place += (same && r < rank) ? 1u : 0u;
+        size += same ? 1u : 0u;
+      }
+      m[i] = (uint32_t)(k % size) == place ? 1 : 0;   // size >= 1: the worker's own row matches
+      mask[k] = m[i];
+      n = i + 1;
+    }
+  }
+  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  block_exclusive_scan(mine, &total);
+  if (threadIdx.x == 0) {
+    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
+    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  }
+}
+
 // Same sums for a caller-supplied mask (any non-zero byte marks a chunk).
 __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(PlanDev p,
                                                              const uint8_t *__restrict__ mask,
@@ -302,6 +335,18 @@ hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *
   if (nblocks)
     hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
                        d_blocksums);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
+                     (uint64_t)nblocks, 0, d_counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
+                                uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
+                                ckpt_counts_t *d_counts, hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  if (nblocks)
+    hipLaunchKernelGGL(k_upload_owners, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_gathered,
+                       world, rank, d_mask, d_blocksums);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
                      (uint64_t)nblocks, 0, d_counts);
   return hipGetLastError();

@@ -77,7 +77,7 @@ def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
     states = [[b.copy() for b in base] for _ in range(world)]
     for r in range(world):
         for _ in range(4):
-            i = int(rng.choice([0, 1, 3, 4]))
+            i = int(rng.choice([q for q, b in enumerate(base) if b.size]))
             off = int(rng.integers(0, base[i].size))
             patch = rng.integers(0, 256, size=min(300, base[i].size - off), dtype=np.uint8)
             for q in {r, int(rng.integers(0, world))}:        # sometimes one more worker gets it
