@@ -207,6 +207,21 @@ int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t st
                  const ckpt_entry_t *d_manifest, uint64_t nentries, uint64_t *d_rejected,
                  void *stream);
 
+/* ckpt_restore whose entry count is read on the device when the kernel runs:
+ * the first min(manifest_cap, d_counts->ndirty) entries are applied, d_counts
+ * being what ckpt_compact / ckpt_snapshot wrote earlier on the stream.  With
+ * it a whole switch (checksum, compare, swap-out, swap-in) is enqueued without
+ * the host ever reading a result, so the next rank's operations can be
+ * dispatched at once behind an event (the eager dispatch of sec. 6), and a
+ * captured graph replays correctly when the number of dirty chunks changes.
+ *   manifest_cap  entries d_manifest can hold (upper bound on what is read)
+ *   d_counts      device ckpt_counts_t, 8-byte aligned; only ndirty is read
+ * Everything else as ckpt_restore.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,
+                         const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                         const ckpt_counts_t *d_counts, uint64_t *d_rejected, void *stream);
+
 /* ---- content-addressed comparison (the paper's own rule) ------------------- */
 
 /* Sec. 5.2.1 looks a checksum up by content wherever it lives: a hit at the same

@@ -26,7 +26,7 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
+    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
@@ -81,6 +81,8 @@ def _lib():
         lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore.restype = ci
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_restore_counted.restype = ci
+        lib.ckpt_restore_counted.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
         lib.ckpt_snapshot_workspace_bytes.restype = u64
         lib.ckpt_snapshot_workspace_bytes.argtypes = [u64]
         lib.ckpt_snapshot.restype = ci
@@ -248,6 +250,14 @@ def restore(dst_plan: Plan, staging, staging_bytes: int, manifest, nentries: int
     """``ckpt_restore``: scatter the first nentries manifest entries into dst_plan's buffers."""
     _check(_lib().ckpt_restore(dst_plan._h, _ptr(staging), staging_bytes, _ptr(manifest), nentries,
                                _ptr(rejected), _stream(stream)), "ckpt_restore")
+
+
+def restore_counted(dst_plan: Plan, staging, staging_bytes: int, manifest, manifest_cap: int, counts,
+                    rejected=None, stream=None) -> None:
+    """``ckpt_restore_counted``: as ``restore``, the entry count taken from ``counts`` on the device."""
+    _check(_lib().ckpt_restore_counted(dst_plan._h, _ptr(staging), staging_bytes, _ptr(manifest),
+                                       manifest_cap, _ptr(counts), _ptr(rejected), _stream(stream)),
+           "ckpt_restore_counted")
 
 
 MATCH_COUNT_FIELDS = ("nsame", "nmoved", "ndup", "nnew", "staged_bytes", "table_full")

@@ -369,8 +369,23 @@ int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t st
   if (nentries > (1ull << 40)) return CKPT_ERR_INVALID_ARG;
   if (!aligned(d_staging, 16) || !aligned(d_manifest, 8) || !aligned(d_rejected, 8))
     return CKPT_ERR_ALIGNMENT;
-  hipError_t e = ckpt::launch_scatter(dst_plan->dev, d_manifest, nentries, d_staging, staging_bytes,
-                                      d_rejected, static_cast<hipStream_t>(stream));
+  hipError_t e = ckpt::launch_scatter(dst_plan->dev, d_manifest, nentries, nullptr, d_staging,
+                                      staging_bytes, d_rejected, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,
+                         const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                         const ckpt_counts_t *d_counts, uint64_t *d_rejected, void *stream) {
+  if (dst_plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (staging_bytes != 0 && d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap > (1ull << 40)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_staging, 16) || !aligned(d_manifest, 8) || !aligned(d_rejected, 8) ||
+      !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_scatter(dst_plan->dev, d_manifest, manifest_cap, d_counts, d_staging,
+                                      staging_bytes, d_rejected, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

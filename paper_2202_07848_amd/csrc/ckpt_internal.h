@@ -103,9 +103,10 @@ hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8
                                hipStream_t s);
 hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint8_t *d_hint_copy,
                              uint64_t *d_misses, hipStream_t s);
+// Applies min(nentries, d_counts->ndirty) entries when d_counts is not null, else nentries.
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
-                          const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
-                          hipStream_t s);
+                          const ckpt_counts_t *d_counts, const void *d_staging,
+                          uint64_t staging_bytes, uint64_t *d_rejected, hipStream_t s);
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);

@@ -154,15 +154,15 @@ hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint6
 }
 
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
-                          const void *d_staging, uint64_t staging_bytes, uint64_t *d_rejected,
-                          hipStream_t s) {
+                          const ckpt_counts_t *d_counts, const void *d_staging,
+                          uint64_t staging_bytes, uint64_t *d_rejected, hipStream_t s) {
   if (d_rejected)
     hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(1), 0, s,
                        reinterpret_cast<unsigned long long *>(d_rejected));
   const uint32_t groups = move_groups(p, nentries);
   if (groups == 0) return hipGetLastError();
   hipLaunchKernelGGL(k_move<false>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, nentries,
-                     (const ckpt_counts_t *)nullptr,
+                     d_counts,
                      const_cast<uint8_t *>(reinterpret_cast<const uint8_t *>(d_staging)),
                      staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected),
                      (const unsigned long long *)nullptr);
