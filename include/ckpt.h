@@ -186,6 +186,14 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
  * staging beyond the final staged_bytes (never beyond staging_cap).
  * Errors: INVALID_ARG, GEOMETRY, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
 uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks);
+/* Tuning of ckpt_snapshot with a hint, process-wide: a plan of at least this
+ * many bytes runs the pass as two launches (the chunks that are staged, then
+ * the rest: read/write traffic and pure reads do not mix, which is faster from
+ * a few hundred MB of state), a smaller one as a single launch (fewer
+ * kernels).  Results are identical either way.  Default 256 MiB; 0 = always
+ * two launches, UINT64_MAX = never. */
+uint64_t ckpt_snapshot_split_threshold(void);
+void ckpt_snapshot_set_split_threshold(uint64_t nbytes);
 int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
                   const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
                   uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,

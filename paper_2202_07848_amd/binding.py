@@ -26,7 +26,8 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
+    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot",
+    "ckpt_snapshot_split_threshold", "ckpt_snapshot_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
@@ -83,6 +84,10 @@ def _lib():
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore_counted.restype = ci
         lib.ckpt_restore_counted.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
+        lib.ckpt_snapshot_split_threshold.restype = u64
+        lib.ckpt_snapshot_split_threshold.argtypes = []
+        lib.ckpt_snapshot_set_split_threshold.restype = None
+        lib.ckpt_snapshot_set_split_threshold.argtypes = [u64]
         lib.ckpt_snapshot_workspace_bytes.restype = u64
         lib.ckpt_snapshot_workspace_bytes.argtypes = [u64]
         lib.ckpt_snapshot.restype = ci
@@ -220,6 +225,14 @@ def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,
     _check(_lib().ckpt_compact(plan._h, _ptr(mask), _ptr(digests), _ptr(staging), staging_cap,
                                _ptr(manifest), manifest_cap, _ptr(counts), _stream(stream)),
            "ckpt_compact")
+
+
+def snapshot_split_threshold() -> int:
+    return int(_lib().ckpt_snapshot_split_threshold())
+
+
+def snapshot_set_split_threshold(nbytes: int) -> None:
+    _lib().ckpt_snapshot_set_split_threshold(nbytes)
 
 
 def snapshot_workspace_bytes(nchunks: int) -> int:

@@ -94,15 +94,28 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
                          const uint64_t *d_only_if_nonzero, hipStream_t s);
+// d_list: one uint32 per fingerprint group; d_list_counts: two uint64, zero on entry; split:
+// staging groups and the rest in two launches (pays off from a few hundred MB of state).
 hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
                                       const uint64_t *d_hint_off, void *d_staging,
-                                      uint64_t staging_cap, hipStream_t s);
+                                      uint64_t staging_cap, uint32_t *d_list,
+                                      uint64_t *d_list_counts, bool split, hipStream_t s);
+uint64_t fingerprint_groups(const PlanDev &p);
+// 64-bit words at the head of the fused snapshot's counter block, cleared by
+// launch_hint_offsets: [0] hint misses, [1..3] scratch counts, [4..5] group list lengths.
+constexpr int SNAPSHOT_COUNTERS = 6;
 hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8_t *d_hint_copy,
                                uint64_t *d_blocksums, ckpt_counts_t *d_tmp_counts,
                                uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
                                hipStream_t s);
-hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint8_t *d_hint_copy,
-                             uint64_t *d_misses, hipStream_t s);
+// k_diff + scan + manifest in three kernels; with d_hint_copy the chunks where mask and hint
+// differ are added to *d_misses (cleared by launch_hint_offsets), and *d_misses_out (may be null)
+// receives that count, or 0 without a hint.
+hipError_t launch_diff_compact_scan(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
+                                    uint8_t *d_mask, const uint8_t *d_hint_copy, uint64_t *d_misses,
+                                    uint64_t *d_misses_out, uint64_t staging_cap,
+                                    ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                                    uint64_t *d_blocksums, ckpt_counts_t *d_counts, hipStream_t s);
 // Applies min(nentries, d_counts->ndirty) entries when d_counts is not null, else nentries.
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const ckpt_counts_t *d_counts, const void *d_staging,
@@ -126,7 +139,6 @@ hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_man
                         uint64_t nentries, void *d_ring, uint64_t b0, uint64_t b1,
                         uint64_t *d_rejected, hipStream_t s);
 hipError_t launch_zero_u64(uint64_t *d_value, hipStream_t s);
-hipError_t launch_copy_u64(uint64_t *d_dst, const uint64_t *d_src, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
 

@@ -76,20 +76,32 @@ __device__ __forceinline__ Pair sum_marked(const PlanDev &p, uint64_t k0, const 
 
 // mask[k] = (ref == nullptr || dig[k] != ref[k]); per-workgroup sums of the
 // marked chunks go to blocksums[2*b], [2*b+1].
+//
+// Fused snapshot: with `hint` (a private copy of the caller's hint, so that hint
+// and mask may be one buffer) the chunks whose mask differs from the hint are
+// counted into *misses.
 __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t *__restrict__ dig,
                                                        const uint64_t *__restrict__ ref,
                                                        uint8_t *__restrict__ mask,
-                                                       uint64_t *__restrict__ blocksums) {
+                                                       uint64_t *__restrict__ blocksums,
+                                                       const uint8_t *__restrict__ hint,
+                                                       unsigned long long *misses) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
+  uint32_t bad = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
       m[i] = (ref == nullptr || dig[k] != ref[k]) ? 1 : 0;
+      if (hint != nullptr) bad += (hint[k] != 0) != (m[i] != 0);
       mask[k] = m[i];
       n = i + 1;
     }
+  }
+  if (hint != nullptr) {
+    for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
   }
   Pair mine = sum_marked(p, k0, m, n, nullptr), total;
   block_exclusive_scan(mine, &total);
@@ -133,19 +145,28 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
 }
 
 // Same sums for a caller-supplied mask (any non-zero byte marks a chunk).
+// Fused snapshot: the mask (there: the hint) is also copied to `keep`, and the
+// snapshot's counters zero_me[0 .. SNAPSHOT_COUNTERS) are cleared (hint misses,
+// which k_diff adds to later; scratch counts; the lengths of the group lists).
 __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(PlanDev p,
                                                              const uint8_t *__restrict__ mask,
-                                                             uint64_t *__restrict__ blocksums) {
+                                                             uint64_t *__restrict__ blocksums,
+                                                             uint8_t *__restrict__ keep,
+                                                             unsigned long long *zero_me) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
-      m[i] = mask[k] != 0;
+      const uint8_t v = mask[k];
+      if (keep != nullptr) keep[k] = v;
+      m[i] = v != 0;
       n = i + 1;
     }
   }
+  if (zero_me != nullptr && blockIdx.x == 0 && threadIdx.x < SNAPSHOT_COUNTERS)
+    zero_me[threadIdx.x] = 0;
   Pair mine = sum_marked(p, k0, m, n, nullptr), total;
   block_exclusive_scan(mine, &total);
   if (threadIdx.x == 0) {
@@ -156,9 +177,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(PlanDev p,
 
 // One workgroup: turns blocksums[0..nblocks) into their exclusive prefix sums
 // (when `rewrite`) and writes the grand totals to counts, overflow = 0.
-__global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(uint64_t *__restrict__ blocksums,
-                                                              uint64_t nblocks, int rewrite,
-                                                              ckpt_counts_t *__restrict__ counts) {
+// Fused snapshot: *publish_dst (when not null) receives *publish_src, or 0
+// when there is no source -- the hint-miss count, complete once k_diff is.
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(
+    uint64_t *__restrict__ blocksums, uint64_t nblocks, int rewrite,
+    ckpt_counts_t *__restrict__ counts, const unsigned long long *publish_src,
+    unsigned long long *publish_dst) {
   Pair carry = {0, 0};
   for (uint64_t base = 0; base < nblocks; base += SCAN_THREADS) {
     const uint64_t b = base + threadIdx.x;
@@ -176,6 +200,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(uint64_t *__restri
     counts->ndirty = carry.cnt;
     counts->staged_bytes = carry.bytes;
     counts->overflow = 0;
+    if (publish_dst != nullptr) *publish_dst = publish_src != nullptr ? *publish_src : 0ull;
   }
 }
 
@@ -257,27 +282,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(PlanDev p,
   }
 }
 
-// Fused snapshot, after the pass: in how many chunks does the mask differ from the hint?
-// (also keeps a private copy of the hint, so that hint and mask may be one buffer)
-__global__ __launch_bounds__(256) void k_copy_bytes(uint8_t *__restrict__ dst,
-                                                    const uint8_t *__restrict__ src, uint64_t n,
-                                                    unsigned long long *zero_me) {
-  const uint64_t stride = (uint64_t)gridDim.x * 256;
-  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
-  if (blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;
-}
-
-__global__ __launch_bounds__(256) void k_hint_check(const uint8_t *__restrict__ mask,
-                                                    const uint8_t *__restrict__ hint, uint64_t n,
-                                                    unsigned long long *misses) {
-  uint32_t bad = 0;
-  const uint64_t stride = (uint64_t)gridDim.x * 256;
-  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
-    bad += (mask[i] != 0) != (hint[i] != 0);
-  for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
-  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
-}
-
 // Squashing validation (paper sec. 5.2.3): per chunk, did rank a and rank b
 // change it alike?  Counters are zeroed by k_validate_init on the same stream.
 __global__ void k_validate_init(ckpt_validation_t *r) {
@@ -334,9 +338,31 @@ hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
-                       d_blocksums);
+                       d_blocksums, (const uint8_t *)nullptr, (unsigned long long *)nullptr);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 0, d_counts);
+                     (uint64_t)nblocks, 0, d_counts, (const unsigned long long *)nullptr,
+                     (unsigned long long *)nullptr);
+  return hipGetLastError();
+}
+
+// diff and the metadata half of compact as one sequence of three kernels (the
+// workgroup sums k_diff leaves behind are the ones the compaction scan needs).
+hipError_t launch_diff_compact_scan(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
+                                    uint8_t *d_mask, const uint8_t *d_hint_copy, uint64_t *d_misses,
+                                    uint64_t *d_misses_out, uint64_t staging_cap,
+                                    ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                                    uint64_t *d_blocksums, ckpt_counts_t *d_counts, hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  unsigned long long *misses = reinterpret_cast<unsigned long long *>(d_misses);
+  if (nblocks)
+    hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
+                       d_blocksums, d_hint_copy, misses);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
+                     (uint64_t)nblocks, 1, d_counts, (const unsigned long long *)misses,
+                     reinterpret_cast<unsigned long long *>(d_misses_out));
+  if (nblocks)
+    hipLaunchKernelGGL(k_emit_manifest, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dig,
+                       d_blocksums, d_manifest, manifest_cap, staging_cap, d_counts);
   return hipGetLastError();
 }
 
@@ -348,7 +374,8 @@ hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, ui
     hipLaunchKernelGGL(k_upload_owners, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_gathered,
                        world, rank, d_mask, d_blocksums);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 0, d_counts);
+                     (uint64_t)nblocks, 0, d_counts, (const unsigned long long *)nullptr,
+                     (unsigned long long *)nullptr);
   return hipGetLastError();
 }
 
@@ -357,29 +384,17 @@ hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8
                                uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
                                hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
-  uint32_t groups = (uint32_t)((p.nchunks + 255) / 256);
-  if (groups > 4096) groups = 4096;
-  if (groups == 0) groups = 1;
-  hipLaunchKernelGGL(k_copy_bytes, dim3(groups), dim3(256), 0, s, d_hint_copy, d_hint_in, p.nchunks,
-                     reinterpret_cast<unsigned long long *>(d_misses));
   if (nblocks)
-    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_copy,
-                       d_blocksums);
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in,
+                       d_blocksums, d_hint_copy, reinterpret_cast<unsigned long long *>(d_misses));
+  // with no chunks the scan kernel clears the miss counter instead
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 1, d_tmp_counts);
+                     (uint64_t)nblocks, 1, d_tmp_counts, (const unsigned long long *)nullptr,
+                     nblocks ? (unsigned long long *)nullptr
+                             : reinterpret_cast<unsigned long long *>(d_misses));
   if (nblocks)
     hipLaunchKernelGGL(k_hint_offsets, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_copy,
                        d_blocksums, manifest_cap, d_hoff);
-  return hipGetLastError();
-}
-
-hipError_t launch_hint_check(const PlanDev &p, const uint8_t *d_mask, const uint8_t *d_hint_copy,
-                             uint64_t *d_misses, hipStream_t s) {
-  if (p.nchunks == 0) return hipSuccess;
-  uint32_t groups = (uint32_t)((p.nchunks + 255) / 256);
-  if (groups > 4096) groups = 4096;
-  hipLaunchKernelGGL(k_hint_check, dim3(groups), dim3(256), 0, s, d_mask, d_hint_copy, p.nchunks,
-                     reinterpret_cast<unsigned long long *>(d_misses));
   return hipGetLastError();
 }
 
@@ -402,9 +417,10 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
-                       d_blocksums);
+                       d_blocksums, (uint8_t *)nullptr, (unsigned long long *)nullptr);
   hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 1, d_counts);
+                     (uint64_t)nblocks, 1, d_counts, (const unsigned long long *)nullptr,
+                     (unsigned long long *)nullptr);
   if (nblocks)
     hipLaunchKernelGGL(k_emit_manifest, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dig,
                        d_blocksums, d_manifest, manifest_cap, staging_cap, d_counts);

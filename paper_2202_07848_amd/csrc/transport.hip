@@ -75,7 +75,6 @@ __global__ __launch_bounds__(COPY_THREADS) void k_slice(PlanDev p,
 }
 
 __global__ void k_zero_one(unsigned long long *p) { *p = 0; }
-__global__ void k_copy_one(unsigned long long *dst, const unsigned long long *src) { *dst = *src; }
 
 }  // namespace
 
@@ -92,13 +91,6 @@ hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_man
   else
     hipLaunchKernelGGL(k_slice<false>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest,
                        nentries, reinterpret_cast<uint8_t *>(d_ring), b0, b1, rej);
-  return hipGetLastError();
-}
-
-hipError_t launch_copy_u64(uint64_t *d_dst, const uint64_t *d_src, hipStream_t s) {
-  hipLaunchKernelGGL(k_copy_one, dim3(1), dim3(1), 0, s,
-                     reinterpret_cast<unsigned long long *>(d_dst),
-                     reinterpret_cast<const unsigned long long *>(d_src));
   return hipGetLastError();
 }
 

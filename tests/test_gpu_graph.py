@@ -14,6 +14,16 @@ from gpu_util import DeviceBuffers, counts_dict, u64
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["two_launches", "one_launch"])
+def fused_pass_shape(request):
+    """Every test here runs with the hinted pass forced into each of its two launch shapes (the
+    library picks by state size, and these inputs are all on the small side)."""
+    before = ck.snapshot_split_threshold()
+    ck.snapshot_set_split_threshold(0 if request.param == "two_launches" else 2**64 - 1)
+    yield request.param
+    ck.snapshot_set_split_threshold(before)
+
+
 def test_snapshot_and_restore_replay_from_a_hip_graph():
     chunk = 4096
     rng = np.random.default_rng(1)

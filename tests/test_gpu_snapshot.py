@@ -14,6 +14,16 @@ from gpu_util import DeviceBuffers, counts_dict, u64
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, params=["two_launches", "one_launch"])
+def fused_pass_shape(request):
+    """Every test here runs with the hinted pass forced into each of its two launch shapes (the
+    library picks by state size, and these inputs are all on the small side)."""
+    before = ck.snapshot_split_threshold()
+    ck.snapshot_set_split_threshold(0 if request.param == "two_launches" else 2**64 - 1)
+    yield request.param
+    ck.snapshot_set_split_threshold(before)
+
 ODD_SIZES = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 288, 511, 512, 1000, 4095, 4096, 4097,
              8191, 8192, 12289, 0, 31, 100000, 7, 65536, 65537, 3, 262144 + 40, 5000]
 
