@@ -64,9 +64,30 @@ def pins_hold() -> bool:
         for a, d, b in zip(arenas, dst, bufs):
             assert np.array_equal(d, b) and np.all(a[:32] == 0xEE) and np.all(a[32 + b.size:] == 0xEE)
         owner_pins()
+        widened_pins()
         return True
     except AssertionError:
         return False
+
+
+def widened_pins():
+    """The pins of the content-addressed match, of the moves it drives and of the squashing
+    validation, as their own test files state them (called here so that the mutation test can
+    run them against a deliberately broken build)."""
+    import test_oracle_match as tm
+    import test_validate_mutations as tv
+    for chunk in (256, 1024):
+        for seed in (1, 2, 3):
+            tm.test_match_equals_pairwise_definition(chunk, seed)
+    tm.test_match_hand_case()
+    tm.test_match_prefers_same_position_and_lowest_reference_position()
+    tm.test_match_with_empty_reference_marks_first_occurrences()
+    for seed in (4, 5):
+        tm.test_snapshot_is_rebuilt_from_staging_reference_and_duplicates(seed)
+    tm.test_apply_matches_skips_impossible_sources()
+    for kind in tv.KINDS:
+        tv.test_oracle_verdict_matches_construction(kind)
+    tv.test_oracle_no_mutation_at_all_and_empty()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -139,7 +160,8 @@ def use_library(path):
     good = oracle._load()
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
-               "ora_compact", "ora_restore", "ora_upload_owners"):
+               "ora_compact", "ora_restore", "ora_upload_owners", "ora_match", "ora_apply_matches",
+               "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     oracle._lib = other

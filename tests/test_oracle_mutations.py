@@ -52,6 +52,21 @@ MUTATIONS = [
     ("restore to wrong offset", "(uint8_t *)dst[m->buf].ptr + m->buf_off, in", "(uint8_t *)dst[m->buf].ptr + m->stage_off, in"),
     ("thread split loses the boundary chunk", "if (k < job->k_lo || k >= job->k_hi) continue;",
      "if (k <= job->k_lo || k >= job->k_hi) continue;"),
+    ("match: same position not preferred", "if (k < n_ref && ref[k] == dig[k]) {", "if (0) {"),
+    ("match: highest reference position taken", "if (pairs[mid].dig < d) lo = mid + 1; else hi = mid;",
+     "if (pairs[mid].dig <= d && !(pairs[mid].dig == d && mid + 1 < n && pairs[mid + 1].dig != d) && !(pairs[mid].dig == d && mid + 1 == n)) lo = mid + 1; else hi = mid;"),
+    ("match: first occurrence taken for its own duplicate", "if ((uint64_t)k0 < k) {",
+     "if ((uint64_t)k0 <= k) {"),
+    ("match: duplicate encoding off by one", "s = -2 - k0;", "s = -1 - k0;"),
+    ("match: moved chunks also staged", "counts->nmoved += 1;", "counts->nmoved += 1; counts->staged_bytes += 16;"),
+    ("match: mask set for duplicates", "mask[k] = (s == -1) ? 1 : 0;", "mask[k] = (s < 0) ? 1 : 0;"),
+    ("apply: duplicates before reference copies", "if (s == -1 || (pass == 0) != (s >= 0)) continue;",
+     "if (s == -1 || (pass == 1) != (s >= 0)) continue;"),
+    ("apply: length mismatch accepted", "if (!ok || flen != tlen) {", "if (!ok) {"),
+    ("validate: new checksums not compared", "if (ca != cb || (ca && after_a[k] != after_b[k])) {",
+     "if (ca != cb) {"),
+    ("validate: change of b read from a", "int cb = before_b[k] != after_b[k];", "int cb = before_a[k] != after_b[k];"),
+    ("validate: last mismatch reported", "if (first == ~(uint64_t)0) first = k;", "first = k;"),
     ("owner: lowest rank always uploads", "(k % size == my_place) ? 1 : 0", "(0 == my_place) ? 1 : 0"),
     ("owner: group taken against rank 0", "uint64_t mine = gathered[(uint64_t)rank * N + k];",
      "uint64_t mine = gathered[k];"),

@@ -43,6 +43,8 @@ def scenario(kind):
     """Two ranks with identical P/O state before the optimizer step (the squashing
     window); returns (before_a, after_a, before_b, after_b, expected verdict)."""
     a0, b0 = state(1), state(1)
+    if kind == "untouched_state_differs":                # e.g. a per-rank buffer nobody writes
+        write(b0, 14, 200)
     a1, b1 = [x.copy() for x in a0], [x.copy() for x in b0]
     for k, v in ((0, 11), (9, 12), (27, 13)):          # the update every rank performs
         write(a1, k, v)
@@ -65,7 +67,8 @@ def scenario(kind):
     return a0, a1, b0, b1, exp
 
 
-KINDS = ["identical", "b_extra_write", "different_value", "a_skips_one", "both_wrong_twice"]
+KINDS = ["identical", "b_extra_write", "different_value", "a_skips_one", "both_wrong_twice",
+         "untouched_state_differs"]
 
 
 @pytest.mark.parametrize("kind", KINDS)
