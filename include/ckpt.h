@@ -91,6 +91,11 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  *   bufs        host array of nbufs descriptors (may be NULL when nbufs == 0)
  *   chunk_bytes C: power of two, 256 <= C <= 2^30
  *   out         receives the plan; destroy it with ckpt_plan_destroy
+ * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
+ * ckpt_snapshot, ckpt_upload_owners, ckpt_swap_out and ckpt_apply_moves_inplace
+ * write: calls of these on ONE plan must be ordered (one stream, or events);
+ * issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
+ * the other calls only read the plan and may overlap freely.
  * Errors: INVALID_ARG, CHUNK, ALIGNMENT (ptr not 16-byte aligned),
  * NOMEM, DEVICE. */
 int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,
