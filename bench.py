@@ -60,7 +60,8 @@ def parse_args():
     ap.add_argument("--swap-slice-mib", type=int, default=256)
     ap.add_argument("--calibrate", action="store_true",
                     help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
-                         "the known-size dispatches that scale the rocprofv3 byte counters)")
+                         "the known-size dispatches that scale the rocprofv3 byte counters) and "
+                         "the XXH64 arithmetic alone (integer ceiling)")
     return ap.parse_args()
 
 
@@ -411,6 +412,9 @@ def main():
         },
         "hbm_frac_fp_diff_compact": round(moved / t_fdc / 1e9 / HBM_PEAK_GBPS, 4),
         "bytes_moved_algorithmic": moved,
+        # XXH64 costs two 64-bit multiplies per 8 input bytes; the rate the pass achieves, to set
+        # beside the arithmetic-only ceiling that --calibrate measures
+        "xxh64_u64_mul_per_s": round(bytes_fp / 4 / t_fdc, 0),
         "phases_ms_mean": phase_names({k: round(v, 3) for k, v in mean.items()}, fused),
         "phases_ms_median": phase_names({k: round(v, 3) for k, v in med.items()}, fused),
         "restore_GBps_read_plus_write": round(2 * dirty_bytes / (mean["restore"] / 1e3) / 1e9, 1)
@@ -445,6 +449,18 @@ def main():
             ms = e0.elapsed_time(e1) / 5
             cal[name] = {"bytes": nb, "ms": round(ms, 3),
                          "GBps": round((2 if name == "copy" else 1) * nb / ms / 1e6, 1)}
+        # the hash arithmetic alone (no memory traffic): the integer units' ceiling for the pass
+        hashed = ck.alu_xxh64(1 << 14, sink)
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            ck.alu_xxh64(1 << 14, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        cal["xxh64_alu_only"] = {"bytes_stood_for": hashed, "ms": round(ms, 3),
+                                 "GBps": round(hashed / ms / 1e6, 1),
+                                 "u64_mul_per_s": round(hashed / 4 / (ms / 1e3), 0)}
         out["calibration"] = cal
 
     if args.swap:

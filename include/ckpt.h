@@ -374,6 +374,14 @@ int ckpt_validate_mutations(const ckpt_plan_t *plan, const uint64_t *d_before_a,
 int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream);
 int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *stream);
 
+/* The other yardstick: the XXH64 accumulator arithmetic alone, on words made
+ * up in registers, no memory traffic -- what the integer units allow the
+ * fingerprint kernel.  Every lane of a fixed grid runs rounds_per_lane steps
+ * (rounded up to a multiple of 8, at most 2^32); d_sink receives one word per
+ * workgroup (at least 16 KiB).  Returns the number of input bytes those steps
+ * stand for (8 per step), or 0 on an argument or launch error. */
+uint64_t ckpt_alu_xxh64(uint64_t rounds_per_lane, uint64_t *d_sink, void *stream);
+
 const char *ckpt_strerror(int status);
 /* hipError_t of the last failed HIP call on this thread (0 if none). */
 int ckpt_last_device_error(void);

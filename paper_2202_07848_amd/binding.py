@@ -30,7 +30,7 @@ EXPORTS = (
     "ckpt_snapshot_split_threshold", "ckpt_snapshot_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
-    "ckpt_bw_copy", "ckpt_bw_read", "ckpt_strerror", "ckpt_last_device_error",
+    "ckpt_bw_copy", "ckpt_bw_read", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
 )
 
@@ -116,6 +116,8 @@ def _lib():
         lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
         lib.ckpt_bw_read.restype = ci
         lib.ckpt_bw_read.argtypes = [vp, u64, vp, vp]
+        lib.ckpt_alu_xxh64.restype = u64
+        lib.ckpt_alu_xxh64.argtypes = [u64, vp, vp]
         lib.ckpt_strerror.restype = ctypes.c_char_p
         lib.ckpt_strerror.argtypes = [ci]
         lib.ckpt_last_device_error.restype = ci
@@ -381,6 +383,14 @@ def bw_copy(dst, src, nbytes: int, stream=None) -> None:
 
 def bw_read(src, nbytes: int, sink, stream=None) -> None:
     _check(_lib().ckpt_bw_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "ckpt_bw_read")
+
+
+def alu_xxh64(rounds_per_lane: int, sink, stream=None) -> int:
+    """``ckpt_alu_xxh64``: hash arithmetic only; returns the bytes the steps stand for."""
+    n = int(_lib().ckpt_alu_xxh64(rounds_per_lane, _ptr(sink), _stream(stream)))
+    if n == 0:
+        raise CkptError(-1, "ckpt_alu_xxh64")
+    return n
 
 
 def version() -> int:

@@ -482,6 +482,19 @@ int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *str
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+uint64_t ckpt_alu_xxh64(uint64_t rounds_per_lane, uint64_t *d_sink, void *stream) {
+  if (d_sink == nullptr || !aligned(d_sink, 8) || rounds_per_lane == 0 ||
+      rounds_per_lane > (1ull << 32))
+    return 0;
+  rounds_per_lane = (rounds_per_lane + 7) & ~7ull;
+  hipError_t e = ckpt::launch_alu_xxh64(rounds_per_lane, d_sink, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    (void)device_error(e);
+    return 0;
+  }
+  return 8ull * rounds_per_lane * 256 * ckpt::ALU_PROBE_GROUPS;
+}
+
 const char *ckpt_strerror(int status) {
   switch (status) {
     case CKPT_OK: return "ok";

@@ -14,6 +14,7 @@
 // the exit, nothing waits on another wave.
 #include "ckpt_internal.h"
 #include "stream_copy.h"
+#include "xxh64_device.h"
 
 namespace ckpt {
 
@@ -129,6 +130,30 @@ __global__ __launch_bounds__(256) void k_bw_read(const uint4 *__restrict__ src, 
   if (threadIdx.x == 0) sink[blockIdx.x] = s_x[0];
 }
 
+// The hash arithmetic alone: every lane runs `rounds` XXH64 accumulator steps on words it
+// makes up in registers (one 64-bit add per word), no memory traffic.  Its rate, times 8 bytes
+// per step, is the ceiling the integer units set for the fingerprint kernel.
+__global__ __launch_bounds__(256) void k_alu_xxh64(uint64_t rounds, uint64_t *__restrict__ sink) {
+  uint64_t acc = xxh::acc_init(threadIdx.x & 3) + blockIdx.x;
+  uint64_t w = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  for (uint64_t i = 0; i < rounds; i += 8) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      acc = xxh::round(acc, w);
+      w += 0x9E3779B97F4A7C15ull;
+    }
+  }
+  // keeps the loop alive; one word per workgroup, as k_bw_read
+  __shared__ uint64_t s_x[256];
+  s_x[threadIdx.x] = acc;
+  __syncthreads();
+  for (int d = 128; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) s_x[threadIdx.x] ^= s_x[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) sink[blockIdx.x] = s_x[0];
+}
+
 inline uint32_t move_groups(const PlanDev &p, uint64_t max_entries) {
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
   const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
@@ -176,6 +201,11 @@ hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipSt
   if (groups > 2048) groups = 2048;
   hipLaunchKernelGGL(k_bw_copy, dim3((uint32_t)groups), dim3(256), 0, s,
                      reinterpret_cast<uint4 *>(d_dst), reinterpret_cast<const uint4 *>(d_src), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_alu_xxh64(uint64_t rounds_per_lane, uint64_t *d_sink, hipStream_t s) {
+  hipLaunchKernelGGL(k_alu_xxh64, dim3(ALU_PROBE_GROUPS), dim3(256), 0, s, rounds_per_lane, d_sink);
   return hipGetLastError();
 }
 
