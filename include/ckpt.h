@@ -156,8 +156,12 @@ int ckpt_upload_owners(const ckpt_plan_t *plan, const uint64_t *d_gathered, uint
  *   stage_off[0] = 0, stage_off[e+1] = stage_off[e] + pad16(len[e]).
  * d_counts receives ndirty, staged_bytes (both the full need, whatever the
  * capacities) and overflow.
- *   d_staging    device buffer of staging_cap bytes, 16-byte aligned, not
- *                overlapping any plan buffer
+ *   d_staging    buffer of staging_cap bytes the device can address, 16-byte
+ *                aligned, not overlapping any plan buffer: device memory, or
+ *                pinned host memory (hipHostMalloc) -- then the kernel writes
+ *                the bytes over the host link itself and the call is the
+ *                paper's swap-out to host memory, still asynchronous.  The
+ *                same holds for ckpt_snapshot and, reading, for ckpt_restore
  *   d_manifest   device array of manifest_cap entries, 8-byte aligned
  * Capacity: entry e is written only if e < manifest_cap; its bytes are written
  * only if also stage_off + pad16(len) <= staging_cap.  Every dirty chunk that

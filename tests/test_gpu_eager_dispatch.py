@@ -79,8 +79,10 @@ def test_restore_counted_argument_errors():
     torch.cuda.synchronize()
 
 
-def test_switch_is_enqueued_without_host_reads_and_next_rank_waits_on_an_event():
-    """Two ranks share one set of device buffers.  Rank A is resident; the switch saves A's delta
+@pytest.mark.parametrize("where", ["device", "pinned_host"])
+def test_switch_is_enqueued_without_host_reads_and_next_rank_waits_on_an_event(where):
+    """Two ranks share one set of device buffers; the deltas that are swapped out and in live in
+    device memory or in pinned host memory (then the kernels move them over the host link).  Rank A is resident; the switch saves A's delta
     against the common reference and brings in B's delta, on the switch stream.  Rank B's first
     device operation (here: a checksum pass over its state and a mutation of one buffer) is
     dispatched immediately on its own stream behind an event.  Nothing is synchronised until the
@@ -99,14 +101,21 @@ def test_switch_is_enqueued_without_host_reads_and_next_rank_waits_on_an_event()
     # B's delta against the reference, as an earlier switch left it (device-resident here)
     mb, cb = oracle.diff(b_host, CHUNK, o_b, n_ref)
     st_b, man_b, _ = oracle.compact(b_host, CHUNK, mb, o_b)
-    b_staging = torch.from_numpy(st_b).cuda()
+    def place(t):
+        if where == "device":
+            return t.cuda()
+        p = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+        p.copy_(t)
+        return p
+
+    b_staging = place(torch.from_numpy(st_b))
     b_manifest = torch.from_numpy(man_b.view(np.uint8).reshape(-1).copy()).cuda()
     b_counts = torch.tensor([cb["ndirty"], cb["staged_bytes"], 0], dtype=torch.int64, device="cuda")
 
     dig = torch.zeros(n, dtype=torch.int64, device="cuda")
     mask = torch.zeros(n, dtype=torch.uint8, device="cuda")
     counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
-    a_staging = torch.full((n * CHUNK,), 0xEE, dtype=torch.uint8, device="cuda")
+    a_staging = place(torch.full((n * CHUNK,), 0xEE, dtype=torch.uint8))
     a_manifest = torch.full((n * 32,), 0xEE, dtype=torch.uint8, device="cuda")
     rejected = torch.full((2,), -1, dtype=torch.int64, device="cuda")
     b_dig = torch.zeros(n, dtype=torch.int64, device="cuda")

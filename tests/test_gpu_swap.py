@@ -114,3 +114,67 @@ def test_swap_out_capacity_error_leaves_host_buffer_untouched():
     assert bool((h == 0x5A).all())
     with pytest.raises(ck.CkptError):
         ck.Swapper(1000)
+
+
+# ---- the same swap with no ring and no DMA: staging in pinned host memory -----------------
+# ckpt_compact, ckpt_snapshot and ckpt_restore take a staging pointer the device can reach; pinned
+# host memory is such a pointer, and then the kernels move the bytes over the host link
+# themselves.  The calls stay asynchronous, which the ring cannot be.
+
+def pinned(nbytes, fill):
+    t = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    t.fill_(fill)
+    assert t.is_pinned()
+    return t
+
+
+@pytest.mark.parametrize("chunk", [256, 4096, 65536, 1 << 20])
+@pytest.mark.parametrize("fused", [False, True], ids=["compact", "snapshot"])
+def test_staging_in_pinned_host_memory(chunk, fused):
+    ref_bufs = host_bufs(5, ODD_SIZES)
+    snap = [b.copy() for b in ref_bufs]
+    rng = np.random.default_rng(6)
+    for i in (6, 8, 12, 15, 19):
+        off = int(rng.integers(0, snap[i].size))
+        snap[i][off:off + 3000] ^= 0x3C
+    dev = DeviceBuffers(snap, chunk)
+    n = dev.plan.nchunks
+    o_ref, o_dig = oracle.fingerprint(ref_bufs, chunk, 8), oracle.fingerprint(snap, chunk, 8)
+    o_mask, _ = oracle.diff(snap, chunk, o_dig, o_ref)
+    want_st, want_man, want_cnt = oracle.compact(snap, chunk, o_mask, o_dig)
+    ref = torch.from_numpy(o_ref.view(np.int64)).cuda()
+    slack = 4096
+    h_staging = pinned(want_st.size + slack, 0xA5)
+    manifest = torch.full((max(1, want_man.size) * 32,), 0xA5, dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    dig = torch.zeros(n, dtype=torch.int64, device="cuda")
+    mask = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    if fused:
+        hint = torch.from_numpy(o_mask).cuda()
+        misses = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        ck.snapshot(dev.plan, ref, hint, dig, mask, h_staging, manifest, counts, misses, ws,
+                    staging_cap=want_st.size, manifest_cap=want_man.size)
+        torch.cuda.synchronize()
+        assert int(misses.item()) == 0
+    else:
+        ck.fingerprint(dev.plan, dig)
+        ck.diff(dev.plan, dig, ref, mask, counts)
+        ck.compact(dev.plan, mask, dig, h_staging, manifest, counts, staging_cap=want_st.size,
+                   manifest_cap=want_man.size)
+        torch.cuda.synchronize()
+    c = counts.cpu().numpy().view(np.uint64)
+    assert {"ndirty": int(c[0]), "staged_bytes": int(c[1]), "overflow": int(c[2])} == want_cnt
+    img = h_staging.numpy()
+    assert np.array_equal(img[:want_st.size], want_st)
+    assert np.all(img[want_st.size:] == 0xA5)
+    assert np.array_equal(ck.manifest_to_numpy(manifest, want_man.size), want_man)
+
+    dst = DeviceBuffers(ref_bufs, chunk)
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ck.restore_counted(dst.plan, h_staging, want_st.size, manifest, want_man.size, counts, rejected)
+    torch.cuda.synchronize()
+    assert int(rejected.item()) == 0
+    got, image = dst.host()
+    assert all(np.array_equal(g, s) for g, s in zip(got, snap))
+    assert dst.canaries_intact(image)
