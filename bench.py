@@ -58,6 +58,9 @@ def parse_args():
                     help="also swap the last replica's delta out to pinned host memory and back in "
                          "(ckpt_swap_out / ckpt_swap_in through a small device ring)")
     ap.add_argument("--swap-slice-mib", type=int, default=256)
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step in HIP graphs (snapshot part, restore part) and "
+                         "time their replays: what a launch-bound small state gains")
     ap.add_argument("--calibrate", action="store_true",
                     help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
                          "the known-size dispatches that scale the rocprofv3 byte counters) and "
@@ -186,6 +189,37 @@ def host_swap_leg(w, rep, dig, mask, manifest, d_staging, staged, ndirty, ck, to
             "swap_in_GBps": round(staged / t["timed_zc_in"] / 1e9, 1)},
         "host_image_equals_device_staging": same,
     }
+
+
+def graph_leg(step_calls, restore_calls, bytes_fp, args, torch):
+    """The same calls captured in two HIP graphs and replayed: the library only enqueues kernels,
+    so a whole snapshot is one graph launch.  Times are per replay, from events around it."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = []
+    with torch.cuda.stream(side):
+        for calls in (step_calls, restore_calls):
+            calls()                                   # eager once on the capture stream
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                calls()
+            graphs.append(g)
+    torch.cuda.synchronize()
+    times = {"snapshot": [], "restore": []}
+    for it in range(args.warmup + args.steps):
+        for name, g in zip(("snapshot", "restore"), graphs):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                times[name].append(e0.elapsed_time(e1))
+    snap = sum(times["snapshot"]) / len(times["snapshot"])
+    return {"snapshot_ms": round(snap, 4),
+            "restore_ms": round(sum(times["restore"]) / len(times["restore"]), 4),
+            "value_GBps": round(bytes_fp / snap / 1e6, 1)}
 
 
 def content_addressed_leg(w, t0, t1, ref, ck, torch, np, steps):
@@ -354,6 +388,24 @@ def main():
             marks.append(ev(enable_timing=True)); marks[-1].record()
         return marks
 
+    def step_calls():          # the measured part of a step, no events: for graph capture
+        if w.nreplicas >= 2:
+            ck.fingerprint(pairs[0][0].plan, ref)
+        for i, (a, b) in enumerate(pairs):
+            if fused:
+                ck.snapshot(b.plan, ref, masks[i], digs[i], masks[i], stagings[i], manifests[i],
+                            counts[i], misses[i], spaces[i], staging_cap=staged[i],
+                            manifest_cap=ndirty[i])
+            else:
+                ck.fingerprint(b.plan, digs[i])
+                ck.diff(b.plan, digs[i], ref, masks[i], counts[i])
+                ck.compact(b.plan, masks[i], digs[i], stagings[i], manifests[i], counts[i],
+                           staging_cap=staged[i], manifest_cap=ndirty[i])
+
+    def restore_calls():
+        for i, (a, b) in enumerate(pairs):
+            ck.restore(b.plan, stagings[i], staged[i], manifests[i], ndirty[i])
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -457,6 +509,9 @@ def main():
             "achieved_on_moved_bytes": round(moved_bytes / (fp_launch_ms / 1e3) / 1e9, 1),
         },
     }
+
+    if args.graph:
+        out["hip_graph"] = graph_leg(step_calls, restore_calls, bytes_fp, args, torch)
 
     if args.calibrate:
         nb = min(8 * 2**30, pairs[0][1].arena.numel() // 16 * 16, stagings[0].numel() // 16 * 16)
