@@ -201,3 +201,60 @@ def test_moves_inside_one_memory_image(chunk):
         assert np.array_equal(g, w) and np.array_equal(g, s)
     assert image.canaries_intact(img)
 
+
+
+def random_permuted_case(seed):
+    """A memory image whose full chunks are shuffled by a random permutation (any cycle
+    structure), with a few chunks replaced by new content, some of it repeated."""
+    rng = np.random.default_rng(500 + seed)
+    chunk = int(rng.choice([256, 1024, 4096]))
+    sizes = [int(rng.integers(1, 12)) * chunk + int(rng.choice([0, 0, 1, 40, chunk // 2]))
+             for _ in range(int(rng.integers(2, 9)))]
+    ref = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+    snap = [b.copy() for b in ref]
+    slots = [(i, j * chunk) for i, n in enumerate(sizes) for j in range(n // chunk)]
+    perm = rng.permutation(len(slots))
+    moved = rng.random(len(slots)) < 0.7
+    for t, s in enumerate(perm):
+        if moved[t]:
+            (di, do), (si, so) = slots[t], slots[int(s)]
+            snap[di][do:do + chunk] = ref[si][so:so + chunk]
+    fresh = rng.integers(0, 256, size=chunk, dtype=np.uint8)
+    for t in rng.choice(len(slots), size=min(3, len(slots)), replace=False):
+        di, do = slots[int(t)]
+        snap[di][do:do + chunk] = fresh if rng.random() < 0.7 else \
+            rng.integers(0, 256, size=chunk, dtype=np.uint8)
+    return chunk, ref, snap
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_permutation_inside_one_memory_image(seed):
+    chunk, ref, snap = random_permuted_case(seed)
+    d_snap = DeviceBuffers(snap, chunk)
+    image = DeviceBuffers(ref, chunk)
+    n = image.plan.nchunks
+    rdig, sdig = run_fingerprint(image.plan), run_fingerprint(d_snap.plan)
+    o_rdig, o_sdig = oracle.fingerprint(ref, chunk), oracle.fingerprint(snap, chunk)
+    want_src, want_mask, want_cnt = oracle.match(snap, chunk, o_sdig, o_rdig)
+    src, mask, cnt = run_match(d_snap.plan, sdig, rdig, n)
+    assert np.array_equal(src[:n].cpu().numpy(), want_src) and cnt == want_cnt
+    assert np.array_equal(mask[:n].cpu().numpy(), want_mask)
+    want_st, want_man, _ = oracle.compact(snap, chunk, want_mask, o_sdig)
+    staging, manifest, _ = run_compact(d_snap.plan, mask, sdig, want_st.size, want_man.size)
+    moved = (want_src >= 0) & (want_src != np.arange(n))
+    lens = oracle.chunk_lens(snap, chunk).astype(np.int64)
+    need = int(((lens + 15) // 16 * 16)[moved].sum())
+    temp = torch.full((need + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ck.moves_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ck.apply_moves_inplace(image.plan, src, temp, ws, counts, rejected, temp_cap=need)
+    ck.restore(image.plan, staging, want_st.size, manifest, want_man.size)
+    ck.apply_matches(image.plan, None, src)
+    torch.cuda.synchronize()
+    assert counts_dict(counts) == {"ndirty": int(moved.sum()), "staged_bytes": need, "overflow": 0}
+    assert int(rejected.item()) == 0
+    assert bool((temp[need:] == 0xA5).all())
+    got, img = image.host()
+    assert all(np.array_equal(g, s) for g, s in zip(got, snap))
+    assert image.canaries_intact(img)
