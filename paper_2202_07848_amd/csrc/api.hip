@@ -312,9 +312,9 @@ uint64_t ckpt_snapshot_split_threshold(void) { return g_split_pass_bytes.load();
 void ckpt_snapshot_set_split_threshold(uint64_t nbytes) { g_split_pass_bytes.store(nbytes); }
 
 uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) {
-  // hint offsets, counter block, private copy of the hint, one uint32 per group of 16 chunks
-  // (full and short chunks are grouped separately, hence at most N/16 + 2 groups)
-  return 8 * nchunks + 64 + ((nchunks + 15) & ~15ull) + 4 * (nchunks / 16 + 2);
+  // hint offsets, counter block, private copy of the hint, one uint32 and one byte per group of
+  // 16 chunks (full and short chunks are grouped separately, hence at most N/16 + 2 groups)
+  return 8 * nchunks + 64 + ((nchunks + 15) & ~15ull) + 5 * (nchunks / 16 + 2);
 }
 
 int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
@@ -342,24 +342,25 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
   const uint8_t *hint_copy = nullptr;
   if (d_hint != nullptr) {
     // workspace: [hint offsets: N x u64][counter block: 8 x u64][hint copy: N bytes, padded to
-    // 16][group list: uint32 per group]
+    // 16][group list: uint32 per group][group flags: byte per group]
     uint64_t *hoff = static_cast<uint64_t *>(d_workspace);
     misses = hoff + n;
     ckpt_counts_t *tmp = reinterpret_cast<ckpt_counts_t *>(misses + 1);
     uint64_t *list_counts = misses + 4;
     uint8_t *copy = reinterpret_cast<uint8_t *>(misses + 8);
     uint32_t *list = reinterpret_cast<uint32_t *>(copy + ((n + 15) & ~15ull));
+    uint8_t *flags = reinterpret_cast<uint8_t *>(list + (n / 16 + 2));
     hint_copy = copy;
     e = ckpt::launch_hint_offsets(p, d_hint, copy, plan->d_blocksums, tmp, manifest_cap, hoff,
                                   misses, s);
     if (e == hipSuccess)
       e = ckpt::launch_fingerprint_staging(p, d_digests, copy, hoff, d_staging, staging_cap, list,
-                                           list_counts, plan->nbytes >= g_split_pass_bytes.load(), s);
+                                           flags, list_counts, plan->nbytes >= g_split_pass_bytes.load(), s);
   } else {
     e = ckpt::launch_fingerprint(p, d_digests, s);
   }
-  // with a hint: 3 kernels for its offsets, the pass (1 launch, or the group lists and 2), 3
-  // here, the conditional gather; 5 kernels without
+  // with a hint: 3 kernels for its offsets, the pass (1 launch, or 2 for the group lists and 2),
+  // 3 here, the conditional gather; 5 kernels without
   if (e == hipSuccess)
     e = ckpt::launch_diff_compact_scan(p, d_digests, d_ref, d_mask, hint_copy, misses, d_hint_misses,
                                        staging_cap, d_manifest, manifest_cap, plan->d_blocksums,

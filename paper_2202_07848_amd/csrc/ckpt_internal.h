@@ -94,11 +94,12 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
                          const uint64_t *d_only_if_nonzero, hipStream_t s);
-// d_list: one uint32 per fingerprint group; d_list_counts: two uint64, zero on entry; split:
+// d_list: one uint32, d_flags: one byte per fingerprint group; d_list_counts: two uint64, zero
+// on entry; split:
 // staging groups and the rest in two launches (pays off from a few hundred MB of state).
 hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
                                       const uint64_t *d_hint_off, void *d_staging,
-                                      uint64_t staging_cap, uint32_t *d_list,
+                                      uint64_t staging_cap, uint32_t *d_list, uint8_t *d_flags,
                                       uint64_t *d_list_counts, bool split, hipStream_t s);
 uint64_t fingerprint_groups(const PlanDev &p);
 // 64-bit words at the head of the fused snapshot's counter block, cleared by

@@ -213,36 +213,69 @@ __device__ __forceinline__ uint64_t stage_address(const StageArgs &st, uint64_t 
   return 0;
 }
 
-// Sorts the groups into those that stage something and the rest (see StageArgs).  The order
-// inside each list is whatever the atomics give; it only decides which workgroup runs which
-// group, never a result.  counts[0..1] are zero on entry.
-__global__ __launch_bounds__(256) void k_group_lists(PlanDev p, StageArgs st, uint32_t *list,
-                                                     unsigned long long *counts) {
-  const uint64_t g = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  const bool valid = g < st.ngroups;
-  bool any = false;
-  if (valid) {
-    for (int lane = 0; lane < GROUP; ++lane) {
-      uint64_t ptr, k;
-      uint32_t len;
-      group_slot(p, g, lane, &ptr, &k, &len);
-      if (len != 0 && stage_address(st, k, len) != 0) any = true;
+// Sorting the groups into those that stage something and the rest (see StageArgs), in two
+// kernels.  k_group_flags: does group g stage a chunk?  GROUP lanes per group, one per slot,
+// because each lookup is a chain of dependent loads.
+__global__ __launch_bounds__(256) void k_group_flags(PlanDev p, StageArgs st,
+                                                     uint8_t *__restrict__ flags) {
+  const uint64_t gid = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  const uint64_t g = gid / GROUP;
+  const int lane = threadIdx.x & 63;
+  bool staged = false;
+  if (g < st.ngroups) {
+    uint64_t ptr, k;
+    uint32_t len;
+    group_slot(p, g, (int)(gid % GROUP), &ptr, &k, &len);
+    staged = len != 0 && stage_address(st, k, len) != 0;
+  }
+  const uint64_t staged_lanes = __ballot(staged);
+  if (g < st.ngroups && gid % GROUP == 0)
+    flags[g] = ((staged_lanes >> (lane & ~(GROUP - 1))) & ((1ull << GROUP) - 1)) != 0;
+}
+
+// k_group_lists: a workgroup takes LIST_RUN consecutive groups and appends its share to each
+// list as one run, in group order, with one atomic per list.  The lists stay sorted in long
+// runs, which keeps the pass a forward sweep through memory: with 4 KiB chunks a list
+// shuffled in runs of 4 costs 30 %; runs of 64, 256 and 1024 measure alike within 3 %.
+// Which run lands where only decides which workgroup runs which group, never a result.
+// counts[0..1] are zero on entry.
+template <int LIST_RUN>
+__global__ __launch_bounds__(LIST_RUN) void k_group_lists(const uint8_t *__restrict__ flags,
+                                                          uint32_t ngroups, uint32_t *list,
+                                                          unsigned long long *counts) {
+  __shared__ uint32_t s_wave_stage[LIST_RUN / 64], s_wave_rest[LIST_RUN / 64];
+  __shared__ unsigned long long s_base[2];
+  const uint64_t g = (uint64_t)blockIdx.x * LIST_RUN + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool valid = g < ngroups;
+  const bool any = valid && flags[valid ? g : 0] != 0;
+  // rank of this group among the workgroup's groups of the same kind
+  const uint64_t lanes_below = (1ull << lane) - 1;
+  const uint64_t m_stage = __ballot(any), m_rest = __ballot(valid && !any);
+  if (lane == 0) {
+    s_wave_stage[wave] = (uint32_t)__popcll(m_stage);
+    s_wave_rest[wave] = (uint32_t)__popcll(m_rest);
+  }
+  __syncthreads();
+  uint32_t before_stage = 0, before_rest = 0, all_stage = 0, all_rest = 0;
+#pragma unroll
+  for (int v = 0; v < LIST_RUN / 64; ++v) {
+    if (v < wave) {
+      before_stage += s_wave_stage[v];
+      before_rest += s_wave_rest[v];
     }
+    all_stage += s_wave_stage[v];
+    all_rest += s_wave_rest[v];
   }
-  // one atomic per wavefront and list: the first lane reserves a run, each lane takes its rank
-  const uint64_t lanes_below = (1ull << (threadIdx.x & 63)) - 1;
-  const uint64_t m_stage = __ballot(valid && any), m_rest = __ballot(valid && !any);
-  unsigned long long base_stage = 0, base_rest = 0;
-  if ((threadIdx.x & 63) == 0) {
-    if (m_stage) base_stage = atomicAdd(&counts[0], (unsigned long long)__popcll(m_stage));
-    if (m_rest) base_rest = atomicAdd(&counts[1], (unsigned long long)__popcll(m_rest));
+  if (threadIdx.x == 0) {
+    s_base[0] = all_stage ? atomicAdd(&counts[0], (unsigned long long)all_stage) : 0;
+    s_base[1] = all_rest ? atomicAdd(&counts[1], (unsigned long long)all_rest) : 0;
   }
-  base_stage = __shfl(base_stage, 0, 64);
-  base_rest = __shfl(base_rest, 0, 64);
-  if (valid && any)
-    list[base_stage + __popcll(m_stage & lanes_below)] = (uint32_t)g;
+  __syncthreads();
+  if (any)
+    list[s_base[0] + before_stage + __popcll(m_stage & lanes_below)] = (uint32_t)g;
   else if (valid)
-    list[st.ngroups - 1 - (base_rest + __popcll(m_rest & lanes_below))] = (uint32_t)g;
+    list[ngroups - 1 - (s_base[1] + before_rest + __popcll(m_rest & lanes_below))] = (uint32_t)g;
 }
 
 // MODE_PLAIN: ckpt_fingerprint, workgroup b takes group b.  The fused snapshot runs
@@ -380,6 +413,8 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
 
 }  // namespace
 
+constexpr int LIST_RUN = 1024;   // groups per run of the fused pass's group lists
+
 uint64_t fingerprint_groups(const PlanDev &p) {
   return (p.nfull + GROUP - 1) / GROUP + (p.nshort + GROUP - 1) / GROUP;
 }
@@ -394,11 +429,11 @@ hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t
 }
 
 // split: the group lists, then two launches: first the groups that stage at least one chunk,
-// then the others.  d_list holds one uint32 per group; d_list_counts two uint64 that are zero
-// when the first kernel here starts.  !split: one launch over all groups.
+// then the others.  d_list holds one uint32 and d_flags one byte per group; d_list_counts two
+// uint64 that are zero when the first kernel here starts.  !split: one launch over all groups.
 hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
                                       const uint64_t *d_hint_off, void *d_staging,
-                                      uint64_t staging_cap, uint32_t *d_list,
+                                      uint64_t staging_cap, uint32_t *d_list, uint8_t *d_flags,
                                       uint64_t *d_list_counts, bool split, hipStream_t s) {
   if (p.nchunks == 0) return hipSuccess;
   const uint64_t groups = fingerprint_groups(p);
@@ -411,8 +446,10 @@ hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, con
                        d_digests, st);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(k_group_lists, dim3((uint32_t)((groups + 255) / 256)), dim3(256), 0, s, p, st,
-                     d_list, counts);
+  hipLaunchKernelGGL(k_group_flags, dim3((uint32_t)((groups * GROUP + 255) / 256)), dim3(256), 0, s,
+                     p, st, d_flags);
+  hipLaunchKernelGGL(k_group_lists<LIST_RUN>, dim3((uint32_t)((groups + LIST_RUN - 1) / LIST_RUN)),
+                     dim3(LIST_RUN), 0, s, d_flags, (uint32_t)groups, d_list, counts);
   hipLaunchKernelGGL(k_fingerprint<MODE_STAGING>, dim3((uint32_t)groups), dim3(64), 0, s, p,
                      d_digests, st);
   hipLaunchKernelGGL(k_fingerprint<MODE_REST>, dim3((uint32_t)groups), dim3(64), 0, s, p, d_digests,
