@@ -89,7 +89,11 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  * every live buffer because it owns the allocator, sec. 3.2.1 / 5.2.1) and
  * uploads the descriptor tables to the current device.  Synchronous.
  *   bufs        host array of nbufs descriptors (may be NULL when nbufs == 0)
- *   chunk_bytes C: power of two, 256 <= C <= 2^30
+ *   chunk_bytes C: power of two, 256 <= C <= 2^30.  A chunk is hashed by four
+ *               lanes (XXH64 has four independent accumulators), so speed needs
+ *               many chunks: keep at least about 10 000 of them (1 KiB..2 MiB
+ *               chunks for states of 100 MB..100 GB); with a few hundred the
+ *               fingerprint runs at a fraction of the memory bandwidth
  *   out         receives the plan; destroy it with ckpt_plan_destroy
  * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
  * ckpt_snapshot, ckpt_upload_owners, ckpt_swap_out and ckpt_apply_moves_inplace
