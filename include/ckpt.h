@@ -213,6 +213,30 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
                   ckpt_counts_t *d_counts, uint64_t *d_hint_misses, void *d_workspace,
                   uint64_t workspace_bytes, void *stream);
 
+/* ckpt_snapshot for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * ckpt_snapshot minus the workspace: the hint offsets, counters, group lists
+ * and the scan scratch (which ckpt_snapshot takes from d_workspace and from
+ * the plan) live in one static device array inside the library, about 2.4 MiB,
+ * which every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine);
+ * its only set-up is one symbol-address lookup per device on the first call
+ * there.
+ *   Limit: plans of at most ckpt_snapshot_static_max_chunks() = 262 144 chunks;
+ *   larger ones are refused with CKPT_ERR_CAPACITY and nothing is enqueued.
+ *   The current device must be the plan's (INVALID_ARG otherwise).
+ * All calls on one GPU share that array, which keeps the last call's contents
+ * (every word a call reads it has written first): calls must be ordered on the
+ * GPU -- one stream, or events -- also across plans; two that overlap race.
+ * Errors: as ckpt_snapshot, plus CAPACITY for a plan above the limit. */
+uint64_t ckpt_snapshot_static_max_chunks(void);
+int ckpt_snapshot_static(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                         const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask,
+                         void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                         uint64_t manifest_cap, ckpt_counts_t *d_counts, uint64_t *d_hint_misses,
+                         void *stream);
+
 /* Swap-in / restore (sec. 4.5, sec. 5.2.1): for each of the first nentries
  * manifest entries, copy len bytes from d_staging + stage_off to buffer
  * entry.buf of dst_plan at offset buf_off.  Chunks without an entry are not

@@ -27,6 +27,7 @@ EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
     "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot",
+    "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_snapshot_split_threshold", "ckpt_snapshot_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
@@ -92,6 +93,10 @@ def _lib():
         lib.ckpt_snapshot_workspace_bytes.argtypes = [u64]
         lib.ckpt_snapshot.restype = ci
         lib.ckpt_snapshot.argtypes = [vp, vp, u64, vp, vp, vp, vp, u64, vp, u64, vp, vp, vp, u64, vp]
+        lib.ckpt_snapshot_static_max_chunks.restype = u64
+        lib.ckpt_snapshot_static_max_chunks.argtypes = []
+        lib.ckpt_snapshot_static.restype = ci
+        lib.ckpt_snapshot_static.argtypes = [vp, vp, u64, vp, vp, vp, vp, u64, vp, u64, vp, vp, vp]
         lib.ckpt_match_workspace_bytes.restype = u64
         lib.ckpt_match_workspace_bytes.argtypes = [u64, u64]
         lib.ckpt_match.restype = ci
@@ -258,6 +263,28 @@ def snapshot(plan: Plan, ref, hint, digests, mask, staging, manifest, counts, hi
                                 _ptr(staging), staging_cap, _ptr(manifest), manifest_cap,
                                 _ptr(counts), _ptr(hint_misses), _ptr(workspace), ws_bytes,
                                 _stream(stream)), "ckpt_snapshot")
+
+
+def snapshot_static_max_chunks() -> int:
+    return int(_lib().ckpt_snapshot_static_max_chunks())
+
+
+def snapshot_static(plan: Plan, ref, hint, digests, mask, staging, manifest, counts,
+                    hint_misses=None, stream=None, staging_cap: Optional[int] = None,
+                    manifest_cap: Optional[int] = None, n_ref: Optional[int] = None) -> None:
+    """``ckpt_snapshot_static``: ``snapshot`` without a workspace argument (the library's static
+    device scratch serves; plans up to ``snapshot_static_max_chunks()`` chunks)."""
+    if n_ref is None:
+        n_ref = 0 if ref is None else ref.numel()
+    if staging_cap is None:
+        staging_cap = 0 if staging is None else staging.numel() * staging.element_size()
+    if manifest_cap is None:
+        manifest_cap = 0 if manifest is None else \
+            manifest.numel() * manifest.element_size() // ENTRY_BYTES
+    _check(_lib().ckpt_snapshot_static(plan._h, _ptr(ref), n_ref, _ptr(hint), _ptr(digests),
+                                       _ptr(mask), _ptr(staging), staging_cap, _ptr(manifest),
+                                       manifest_cap, _ptr(counts), _ptr(hint_misses),
+                                       _stream(stream)), "ckpt_snapshot_static")
 
 
 def restore(dst_plan: Plan, staging, staging_bytes: int, manifest, nentries: int,

@@ -41,6 +41,30 @@ void set_last_device_error(hipError_t e) {
 }
 }  // namespace ckpt
 
+namespace {
+
+constexpr uint64_t snapshot_ws_bytes(uint64_t nchunks) {
+  // hint offsets, counter block, private copy of the hint, one uint32 and one byte per group of
+  // 16 chunks (full and short chunks are grouped separately, hence at most N/16 + 2 groups)
+  return 8 * nchunks + 64 + ((nchunks + 15) & ~15ull) + 5 * (nchunks / 16 + 2);
+}
+
+// ckpt_snapshot_static: the scan scratch (as a plan owns it) followed by the snapshot workspace
+// (as ckpt_snapshot takes it), for plans of at most STATIC_MAX_CHUNKS chunks.
+constexpr uint64_t STATIC_MAX_CHUNKS = 1ull << 18;
+constexpr uint64_t STATIC_SCAN_BYTES =
+    (16 * (STATIC_MAX_CHUNKS / ckpt::SCAN_BLOCK + 1) + 255) & ~255ull;
+constexpr uint64_t STATIC_BYTES =
+    STATIC_SCAN_BYTES + ((snapshot_ws_bytes(STATIC_MAX_CHUNKS) + 255) & ~255ull);
+constexpr int STATIC_MAX_DEVICES = 64;
+
+}  // namespace
+
+// Scratch of ckpt_snapshot_static.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+static std::atomic<void *> g_static_scratch[STATIC_MAX_DEVICES];
+
 extern "C" {
 
 int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,
@@ -311,17 +335,16 @@ static std::atomic<uint64_t> g_split_pass_bytes{256ull << 20};
 uint64_t ckpt_snapshot_split_threshold(void) { return g_split_pass_bytes.load(); }
 void ckpt_snapshot_set_split_threshold(uint64_t nbytes) { g_split_pass_bytes.store(nbytes); }
 
-uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) {
-  // hint offsets, counter block, private copy of the hint, one uint32 and one byte per group of
-  // 16 chunks (full and short chunks are grouped separately, hence at most N/16 + 2 groups)
-  return 8 * nchunks + 64 + ((nchunks + 15) & ~15ull) + 5 * (nchunks / 16 + 2);
-}
+uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) { return snapshot_ws_bytes(nchunks); }
 
-int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
-                  const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
-                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
-                  ckpt_counts_t *d_counts, uint64_t *d_hint_misses, void *d_workspace,
-                  uint64_t workspace_bytes, void *stream) {
+// Argument checks and launches of ckpt_snapshot; d_blocksums is the scan scratch to use (the
+// plan's own, or the library's static block).
+static int snapshot_impl(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                         const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask,
+                         void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                         uint64_t manifest_cap, ckpt_counts_t *d_counts, uint64_t *d_hint_misses,
+                         void *d_workspace, uint64_t workspace_bytes, uint64_t *d_blocksums,
+                         void *stream) {
   if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
   const uint64_t n = plan->dev.nchunks;
   if (d_ref != nullptr && n_ref != n) return CKPT_ERR_GEOMETRY;
@@ -333,8 +356,7 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
       !aligned(d_ref, 8) || !aligned(d_counts, 8) || !aligned(d_workspace, 16) ||
       !aligned(d_hint_misses, 8))
     return CKPT_ERR_ALIGNMENT;
-  if (d_hint != nullptr && workspace_bytes < ckpt_snapshot_workspace_bytes(n))
-    return CKPT_ERR_CAPACITY;
+  if (d_hint != nullptr && workspace_bytes < snapshot_ws_bytes(n)) return CKPT_ERR_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const ckpt::PlanDev &p = plan->dev;
   hipError_t e = hipSuccess;
@@ -351,8 +373,7 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
     uint32_t *list = reinterpret_cast<uint32_t *>(copy + ((n + 15) & ~15ull));
     uint8_t *flags = reinterpret_cast<uint8_t *>(list + (n / 16 + 2));
     hint_copy = copy;
-    e = ckpt::launch_hint_offsets(p, d_hint, copy, plan->d_blocksums, tmp, manifest_cap, hoff,
-                                  misses, s);
+    e = ckpt::launch_hint_offsets(p, d_hint, copy, d_blocksums, tmp, manifest_cap, hoff, misses, s);
     if (e == hipSuccess)
       e = ckpt::launch_fingerprint_staging(p, d_digests, copy, hoff, d_staging, staging_cap, list,
                                            flags, list_counts, plan->nbytes >= g_split_pass_bytes.load(), s);
@@ -363,11 +384,49 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
   // 3 here, the conditional gather; 5 kernels without
   if (e == hipSuccess)
     e = ckpt::launch_diff_compact_scan(p, d_digests, d_ref, d_mask, hint_copy, misses, d_hint_misses,
-                                       staging_cap, d_manifest, manifest_cap, plan->d_blocksums,
-                                       d_counts, s);
+                                       staging_cap, d_manifest, manifest_cap, d_blocksums, d_counts,
+                                       s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, misses, s);
   return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                  const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
+                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                  ckpt_counts_t *d_counts, uint64_t *d_hint_misses, void *d_workspace,
+                  uint64_t workspace_bytes, void *stream) {
+  return snapshot_impl(plan, d_ref, n_ref, d_hint, d_digests, d_mask, d_staging, staging_cap,
+                       d_manifest, manifest_cap, d_counts, d_hint_misses, d_workspace,
+                       workspace_bytes, plan ? plan->d_blocksums : nullptr, stream);
+}
+
+uint64_t ckpt_snapshot_static_max_chunks(void) { return STATIC_MAX_CHUNKS; }
+
+int ckpt_snapshot_static(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
+                         const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask,
+                         void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                         uint64_t manifest_cap, ckpt_counts_t *d_counts, uint64_t *d_hint_misses,
+                         void *stream) {
+  if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nchunks > STATIC_MAX_CHUNKS) return CKPT_ERR_CAPACITY;
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return device_error(e);
+  if (device != plan->device || device < 0 || device >= STATIC_MAX_DEVICES)
+    return CKPT_ERR_INVALID_ARG;
+  // each GPU holds its own copy of the array at its own address: looked up once per device,
+  // with that device current (two threads racing here store the same value)
+  void *block = g_static_scratch[device].load(std::memory_order_acquire);
+  if (block == nullptr) {
+    e = hipGetSymbolAddress(&block, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || block == nullptr) return device_error(e);
+    g_static_scratch[device].store(block, std::memory_order_release);
+  }
+  uint8_t *base = static_cast<uint8_t *>(block);
+  return snapshot_impl(plan, d_ref, n_ref, d_hint, d_digests, d_mask, d_staging, staging_cap,
+                       d_manifest, manifest_cap, d_counts, d_hint_misses, base + STATIC_SCAN_BYTES,
+                       STATIC_BYTES - STATIC_SCAN_BYTES, reinterpret_cast<uint64_t *>(base), stream);
 }
 
 int ckpt_restore(const ckpt_plan_t *dst_plan, const void *d_staging, uint64_t staging_bytes,

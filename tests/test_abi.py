@@ -58,6 +58,32 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.ckpt_plan_nchunks(None) == 0
 
 
+def test_static_scratch_symbol_is_visible_to_the_runtime():
+    """hipGetSymbolAddress finds a device variable by name among the code object's global
+    symbols.  The static scratch array of ckpt_snapshot_static is made global by the compiler
+    because host code names it; an attribute that pins its internal linkage (such as `used`)
+    would leave it a local symbol, which the runtime cannot look up."""
+    import subprocess
+    import tempfile
+    from paper_2202_07848_amd import build as hip_build
+    readelf = "/opt/rocm/llvm/bin/llvm-readelf"
+    if not (os.path.exists(hip_build.HIPCC) and os.path.exists(readelf)):
+        pytest.skip("no ROCm toolchain")
+    with tempfile.TemporaryDirectory() as tmp:
+        obj = os.path.join(tmp, "api_device.o")
+        flags = [f for f in hip_build.FLAGS if f != "-shared"]
+        subprocess.run([hip_build.HIPCC] + flags + ["--offload-device-only", "--no-gpu-bundle-output",
+                        "-c", os.path.join(hip_build.CSRC, "api.hip"), "-o", obj],
+                       check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        table = subprocess.run([readelf, "-s", obj], check=True, stdout=subprocess.PIPE,
+                               text=True).stdout
+    rows = [ln.split() for ln in table.splitlines() if ln.rstrip().endswith("scratch")
+            and "OBJECT" in ln]
+    assert rows, "the scratch array is not in the device code object"
+    assert all(r[4] == "GLOBAL" for r in rows), rows
+    assert all(int(r[2]) >= 2_400_000 for r in rows), rows
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(ck, "_handle", None)
     monkeypatch.setattr(ck, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libckpt.so"))
