@@ -58,8 +58,7 @@ typedef enum ckpt_status {
 } ckpt_status;
 
 /* One live buffer.  ptr: device address, 16-byte aligned (unless nbytes == 0,
- * then it is ignored).  Buffers may not overlap if the plan is used as the
- * destination of ckpt_restore. */
+ * then it is ignored).  The buffers of one list may not overlap. */
 typedef struct ckpt_buf {
   void *ptr;
   uint64_t nbytes;
@@ -100,6 +99,9 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  * write: calls of these on ONE plan must be ordered (one stream, or events);
  * issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
  * the other calls only read the plan and may overlap freely.
+ * Two non-empty buffers that share a byte are refused (INVALID_ARG): restoring
+ * into such a list has no defined result, and an allocator never hands out
+ * overlapping live buffers.
  * Errors: INVALID_ARG, CHUNK, ALIGNMENT (ptr not 16-byte aligned),
  * NOMEM, DEVICE. */
 int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_bytes,
@@ -114,9 +116,19 @@ uint64_t ckpt_plan_nbytes(const ckpt_plan_t *plan);      /* S = sum nbytes_i */
 uint64_t ckpt_plan_nbufs(const ckpt_plan_t *plan);       /* B */
 uint64_t ckpt_plan_chunk_bytes(const ckpt_plan_t *plan); /* C */
 
+/* Tuning of ckpt_snapshot with a hint, per plan: a plan of at least this many
+ * bytes runs the pass as two launches (the chunks that are staged, then the
+ * rest: read/write traffic and pure reads do not mix, which is faster from a
+ * few hundred MB of state), a smaller one as a single launch (fewer kernels).
+ * Results are identical either way.  Default 256 MiB; 0 = always two launches,
+ * UINT64_MAX = never.  Set it while no call on the plan is being issued. */
+uint64_t ckpt_plan_split_threshold(const ckpt_plan_t *plan);
+int ckpt_plan_set_split_threshold(ckpt_plan_t *plan, uint64_t nbytes);
+
 /* ---- the four data calls ------------------------------------------------- */
 
-/* Content checksum of every chunk (sec. 5.2.1, sec. 6):
+/* Content checksum of every chunk (sec. 5.2.1, sec. 6: checksums of all live
+ * buffers are computed at every context switch):
  *   d_digests[k] = XXH64(bytes of chunk k, length len_k, seed 0), k in [0, N).
  * A short last chunk is hashed at its true length.  Reads every buffer byte
  * once and nothing else; writes N native-endian uint64.
@@ -125,7 +137,8 @@ uint64_t ckpt_plan_chunk_bytes(const ckpt_plan_t *plan); /* C */
 int ckpt_fingerprint(const ckpt_plan_t *plan, uint64_t *d_digests, void *stream);
 
 /* Positional comparison with a reference replica's or an earlier snapshot's
- * checksums (sec. 5.2.1 "same content checksum"; sec. 4.6; sec. 5.2.3):
+ * checksums (sec. 5.2.1: a buffer whose checksum is already known is not
+ * swapped; sec. 4.6; sec. 5.2.3):
  *   d_mask[k] = 1 if d_ref == NULL or d_digests[k] != d_ref[k], else 0.
  *   d_counts->ndirty = number of ones, ->staged_bytes = staging size
  *   ckpt_compact will need for them, ->overflow = 0.
@@ -171,6 +184,10 @@ int ckpt_upload_owners(const ckpt_plan_t *plan, const uint64_t *d_gathered, uint
  * only if also stage_off + pad16(len) <= staging_cap.  Every dirty chunk that
  * is not fully staged adds 1 to d_counts->overflow; nothing is written past
  * either capacity.  (The prefix that fits is complete and usable.)
+ * The call is stream-ordered and reads nothing back, so it cannot know on the
+ * host whether the capacities sufficed and never returns CKPT_ERR_CAPACITY
+ * itself: the caller reads d_counts->overflow after synchronising (non-zero =
+ * incomplete) and may map that to CKPT_ERR_CAPACITY.
  * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
 int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
                  void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
@@ -184,8 +201,10 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
  * offsets of the predicted chunks are computed first and the fingerprint pass
  * writes each predicted chunk to its staging place while hashing it, so no byte
  * is read twice.  Afterwards the real mask is compared with the hint: if they are
- * equal staging is complete; if not, the ordinary gather runs and overwrites
- * staging, so a wrong hint costs time, never correctness.  (Measured on MI355X the
+ * equal staging is complete; if not, a gather copies the chunks that are not yet
+ * at their final staging offset -- those behind the first chunk the hint got
+ * wrong; the ones before it stay as the pass wrote them -- so a wrong hint costs
+ * time, never correctness, and a late miss costs little.  (Measured on MI355X the
  * single pass wins once the hint marks more than about a fifth of the bytes; below
  * that, mixing the staging writes into the read stream costs more than the second
  * read it saves -- pass NULL then.)
@@ -199,14 +218,12 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
  * staging beyond the final staged_bytes (never beyond staging_cap).
  * Errors: INVALID_ARG, GEOMETRY, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
 uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks);
-/* Tuning of ckpt_snapshot with a hint, process-wide: a plan of at least this
- * many bytes runs the pass as two launches (the chunks that are staged, then
- * the rest: read/write traffic and pure reads do not mix, which is faster from
- * a few hundred MB of state), a smaller one as a single launch (fewer
- * kernels).  Results are identical either way.  Default 256 MiB; 0 = always
- * two launches, UINT64_MAX = never. */
-uint64_t ckpt_snapshot_split_threshold(void);
-void ckpt_snapshot_set_split_threshold(uint64_t nbytes);
+/* Diagnostics of a hinted ckpt_snapshot, readable once the stream is synchronised:
+ * at this byte offset of d_workspace sit four uint64 -- [0] the hint misses (as
+ * *d_hint_misses), [1] and [2] unspecified, [3] the number of chunks the
+ * corrective gather copied after the pass (0 with an exact hint; with one wrong
+ * chunk, the staged chunks behind it). */
+uint64_t ckpt_snapshot_stats_offset(uint64_t nchunks);
 int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,
                   const uint8_t *d_hint, uint64_t *d_digests, uint8_t *d_mask, void *d_staging,
                   uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
@@ -218,7 +235,7 @@ int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref
  * harnesses that forbid hipMalloc.  Same arguments, results and errors as
  * ckpt_snapshot minus the workspace: the hint offsets, counters, group lists
  * and the scan scratch (which ckpt_snapshot takes from d_workspace and from
- * the plan) live in one static device array inside the library, about 2.4 MiB,
+ * the plan) live in one static device array inside the library, about 2.6 MiB,
  * which every GPU the library runs on holds until the process ends.  The call
  * allocates nothing (no hipMalloc / hipFree, no allocating library routine);
  * its only set-up is one symbol-address lookup per device on the first call
@@ -242,7 +259,11 @@ int ckpt_snapshot_static(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_
  * entry.buf of dst_plan at offset buf_off.  Chunks without an entry are not
  * touched (the caller guarantees they already hold the reference's bytes).
  * An entry that names a buffer outside dst_plan, a range outside that buffer,
- * or a range outside [0, staging_bytes) is skipped, never partially applied.
+ * a range outside [0, staging_bytes), offsets that are not multiples of 16, or
+ * a length above the chunk size is skipped, never partially applied.  Whether
+ * an entry fits is only known when the kernel reads it, so a bad manifest is
+ * not a host-side CKPT_ERR_GEOMETRY: the count of skipped entries is the
+ * report, and a caller that must fail hard checks it after synchronising.
  *   d_rejected  optional device uint64 that receives the number of skipped
  *               entries (0 = all applied); may be NULL
  * dst_plan may be the snapshot's own plan or another one with compatible
@@ -317,8 +338,8 @@ int ckpt_apply_matches(const ckpt_plan_t *dst_plan, const ckpt_plan_t *ref_plan,
 
 /* The moves when the destination IS the reference's memory (sec. 5.2.1: the
  * buffers of the rank that ran before are turned into those of the rank that runs
- * next; "cyclic dependencies between source and destination buffers force the
- * copy to happen in phases").  plan's buffers hold the reference image, chunk for
+ * next; moves may depend on each other in cycles, which is why the paper copies
+ * in phases).  plan's buffers hold the reference image, chunk for
  * chunk (n_ref == N); afterwards every chunk k with d_src[k] = j >= 0, j != k holds
  * what chunk j held BEFORE the call.  Two phases through d_temp break every cycle:
  * all sources are gathered, then all destinations written.  Chunks with

@@ -26,9 +26,9 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
-    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot",
+    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
-    "ckpt_snapshot_split_threshold", "ckpt_snapshot_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
+    "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
@@ -85,12 +85,14 @@ def _lib():
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore_counted.restype = ci
         lib.ckpt_restore_counted.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
-        lib.ckpt_snapshot_split_threshold.restype = u64
-        lib.ckpt_snapshot_split_threshold.argtypes = []
-        lib.ckpt_snapshot_set_split_threshold.restype = None
-        lib.ckpt_snapshot_set_split_threshold.argtypes = [u64]
+        lib.ckpt_plan_split_threshold.restype = u64
+        lib.ckpt_plan_split_threshold.argtypes = [vp]
+        lib.ckpt_plan_set_split_threshold.restype = ci
+        lib.ckpt_plan_set_split_threshold.argtypes = [vp, u64]
         lib.ckpt_snapshot_workspace_bytes.restype = u64
         lib.ckpt_snapshot_workspace_bytes.argtypes = [u64]
+        lib.ckpt_snapshot_stats_offset.restype = u64
+        lib.ckpt_snapshot_stats_offset.argtypes = [u64]
         lib.ckpt_snapshot.restype = ci
         lib.ckpt_snapshot.argtypes = [vp, vp, u64, vp, vp, vp, vp, u64, vp, u64, vp, vp, vp, u64, vp]
         lib.ckpt_snapshot_static_max_chunks.restype = u64
@@ -200,6 +202,15 @@ class Plan:
     def chunk_bytes(self) -> int:
         return int(_lib().ckpt_plan_chunk_bytes(self._h))
 
+    @property
+    def split_threshold(self) -> int:
+        """``ckpt_plan_split_threshold``: state size from which the hinted pass runs as two launches."""
+        return int(_lib().ckpt_plan_split_threshold(self._h))
+
+    @split_threshold.setter
+    def split_threshold(self, nbytes: int) -> None:
+        _check(_lib().ckpt_plan_set_split_threshold(self._h, nbytes), "ckpt_plan_set_split_threshold")
+
 
 def fingerprint(plan: Plan, digests, stream=None) -> None:
     """``ckpt_fingerprint``: digests (int64/uint64 CUDA tensor, N elements) <- XXH64 per chunk."""
@@ -234,16 +245,15 @@ def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,
            "ckpt_compact")
 
 
-def snapshot_split_threshold() -> int:
-    return int(_lib().ckpt_snapshot_split_threshold())
-
-
-def snapshot_set_split_threshold(nbytes: int) -> None:
-    _lib().ckpt_snapshot_set_split_threshold(nbytes)
-
-
 def snapshot_workspace_bytes(nchunks: int) -> int:
     return int(_lib().ckpt_snapshot_workspace_bytes(nchunks))
+
+
+def snapshot_stats(workspace, nchunks: int) -> dict:
+    """Diagnostics a hinted ``snapshot`` left in its workspace (synchronise first)."""
+    off = int(_lib().ckpt_snapshot_stats_offset(nchunks))
+    words = workspace.view(-1)[off:off + 32].cpu().numpy().view(np.uint64)
+    return {"hint_misses": int(words[0]), "regathered_chunks": int(words[3])}
 
 
 def snapshot(plan: Plan, ref, hint, digests, mask, staging, manifest, counts, hint_misses=None,

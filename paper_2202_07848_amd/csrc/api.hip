@@ -30,6 +30,9 @@ struct ckpt_plan {
   void *d_tables = nullptr;        // one allocation holding every table
   uint64_t *d_blocksums = nullptr; // scan scratch: 2 x uint64 per SCAN_BLOCK chunks (+2)
   int device = -1;
+  // Below this much state the fused pass stays one launch (measured: at 64 MiB two more launches
+  // cost 20 us of 58; at 3 GB the split saves 7 %).
+  uint64_t split_pass_bytes = 256ull << 20;
 };
 
 namespace ckpt {
@@ -44,9 +47,10 @@ void set_last_device_error(hipError_t e) {
 namespace {
 
 constexpr uint64_t snapshot_ws_bytes(uint64_t nchunks) {
-  // hint offsets, counter block, private copy of the hint, one uint32 and one byte per group of
-  // 16 chunks (full and short chunks are grouped separately, hence at most N/16 + 2 groups)
-  return 8 * nchunks + 64 + ((nchunks + 15) & ~15ull) + 5 * (nchunks / 16 + 2);
+  // hint offsets, counter block, private copy of the hint, one byte per manifest entry (already
+  // staged or not), one uint32 and one byte per group of 16 chunks (full and short chunks are
+  // grouped separately, hence at most N/16 + 2 groups)
+  return 8 * nchunks + 64 + 2 * ((nchunks + 15) & ~15ull) + 5 * (nchunks / 16 + 2);
 }
 
 // ckpt_snapshot_static: the scan scratch (as a plan owns it) followed by the snapshot workspace
@@ -154,6 +158,16 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
       while (k >= dense_base[row + 1]) ++row;
       group_first[g] = row;
     }
+    // two buffers of one list may not share a byte: a restore into such a list has no defined
+    // result.  Sorted by address, each non-empty buffer must end before the next one starts.
+    std::vector<uint32_t> by_addr(dense_ptr.size());
+    std::iota(by_addr.begin(), by_addr.end(), 0u);
+    std::sort(by_addr.begin(), by_addr.end(),
+              [&](uint32_t a, uint32_t b) { return dense_ptr[a] < dense_ptr[b]; });
+    for (size_t j = 1; j < by_addr.size(); ++j) {
+      const uint32_t a = by_addr[j - 1], b = by_addr[j];
+      if (dense_ptr[a] + dense_nbytes[a] > dense_ptr[b]) return CKPT_ERR_INVALID_ARG;
+    }
   } catch (const std::bad_alloc &) {
     return CKPT_ERR_NOMEM;
   }
@@ -197,6 +211,10 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   }
   const uint64_t nscan = (nchunks + ckpt::SCAN_BLOCK - 1) / ckpt::SCAN_BLOCK;
   e = hipMalloc(reinterpret_cast<void **>(&plan->d_blocksums), 16 * (nscan + 1));
+  if (e == hipSuccess) {
+    e = hipMemset(plan->d_blocksums, 0, 16);   // the scan's ticket counter starts at zero
+    if (e != hipSuccess) (void)hipFree(plan->d_blocksums);
+  }
   if (e != hipSuccess) {
     (void)hipFree(plan->d_tables);
     delete plan;
@@ -273,6 +291,15 @@ uint64_t ckpt_plan_nbytes(const ckpt_plan_t *plan) { return plan ? plan->nbytes 
 uint64_t ckpt_plan_nbufs(const ckpt_plan_t *plan) { return plan ? plan->dev.nbufs : 0; }
 uint64_t ckpt_plan_chunk_bytes(const ckpt_plan_t *plan) { return plan ? plan->chunk : 0; }
 
+uint64_t ckpt_plan_split_threshold(const ckpt_plan_t *plan) {
+  return plan ? plan->split_pass_bytes : 0;
+}
+int ckpt_plan_set_split_threshold(ckpt_plan_t *plan, uint64_t nbytes) {
+  if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  plan->split_pass_bytes = nbytes;
+  return CKPT_OK;
+}
+
 int ckpt_fingerprint(const ckpt_plan_t *plan, uint64_t *d_digests, void *stream) {
   if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
   if (plan->dev.nchunks == 0) return CKPT_OK;
@@ -321,21 +348,16 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
     return CKPT_ERR_ALIGNMENT;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = ckpt::launch_compact_scan(plan->dev, d_mask, d_digests, staging_cap, d_manifest,
-                                           manifest_cap, plan->d_blocksums, d_counts, s);
+                                           manifest_cap, plan->d_blocksums, d_counts, nullptr,
+                                           nullptr, s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
-                            nullptr, s);
+                            nullptr, nullptr, nullptr, s);
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
-// Below this much state the fused pass stays one launch (measured: at 64 MiB two more launches
-// cost 20 us of 58; at 3 GB the split saves 7 %).
-static std::atomic<uint64_t> g_split_pass_bytes{256ull << 20};
-
-uint64_t ckpt_snapshot_split_threshold(void) { return g_split_pass_bytes.load(); }
-void ckpt_snapshot_set_split_threshold(uint64_t nbytes) { g_split_pass_bytes.store(nbytes); }
-
 uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) { return snapshot_ws_bytes(nchunks); }
+uint64_t ckpt_snapshot_stats_offset(uint64_t nchunks) { return 8 * nchunks; }
 
 // Argument checks and launches of ckpt_snapshot; d_blocksums is the scan scratch to use (the
 // plan's own, or the library's static block).
@@ -360,34 +382,38 @@ static int snapshot_impl(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_
   hipStream_t s = static_cast<hipStream_t>(stream);
   const ckpt::PlanDev &p = plan->dev;
   hipError_t e = hipSuccess;
-  uint64_t *misses = nullptr;
-  const uint8_t *hint_copy = nullptr;
+  ckpt::HintState h{};
   if (d_hint != nullptr) {
     // workspace: [hint offsets: N x u64][counter block: 8 x u64][hint copy: N bytes, padded to
-    // 16][group list: uint32 per group][group flags: byte per group]
-    uint64_t *hoff = static_cast<uint64_t *>(d_workspace);
-    misses = hoff + n;
-    ckpt_counts_t *tmp = reinterpret_cast<ckpt_counts_t *>(misses + 1);
-    uint64_t *list_counts = misses + 4;
-    uint8_t *copy = reinterpret_cast<uint8_t *>(misses + 8);
-    uint32_t *list = reinterpret_cast<uint32_t *>(copy + ((n + 15) & ~15ull));
+    // 16][already-staged flags: N bytes, padded to 16][group list: uint32 per group][group
+    // flags: byte per group]
+    const uint64_t npad = (n + 15) & ~15ull;
+    h.hoff = static_cast<uint64_t *>(d_workspace);
+    h.misses = h.hoff + n;
+    ckpt_counts_t *tmp = reinterpret_cast<ckpt_counts_t *>(h.misses + 1);
+    uint64_t *list_counts = h.misses + 4;
+    h.copy = reinterpret_cast<uint8_t *>(h.misses + 8);
+    h.need = h.copy + npad;
+    uint32_t *list = reinterpret_cast<uint32_t *>(h.need + npad);
     uint8_t *flags = reinterpret_cast<uint8_t *>(list + (n / 16 + 2));
-    hint_copy = copy;
-    e = ckpt::launch_hint_offsets(p, d_hint, copy, d_blocksums, tmp, manifest_cap, hoff, misses, s);
+    e = ckpt::launch_hint_offsets(p, d_hint, h, d_blocksums, tmp, manifest_cap, s);
     if (e == hipSuccess)
-      e = ckpt::launch_fingerprint_staging(p, d_digests, copy, hoff, d_staging, staging_cap, list,
-                                           flags, list_counts, plan->nbytes >= g_split_pass_bytes.load(), s);
+      e = ckpt::launch_fingerprint_staging(p, d_digests, d_ref, d_mask, h.copy, h.hoff, d_staging,
+                                           staging_cap, list, flags, list_counts,
+                                           plan->nbytes >= plan->split_pass_bytes, s);
   } else {
-    e = ckpt::launch_fingerprint(p, d_digests, s);
+    e = ckpt::launch_fingerprint_diff(p, d_digests, d_ref, d_mask, s);
   }
-  // with a hint: 3 kernels for its offsets, the pass (1 launch, or 2 for the group lists and 2),
-  // 3 here, the conditional gather; 5 kernels without
+  // Kernels up to SMALL_SCAN_CHUNKS chunks: with a hint 4 (its offsets, the pass, the manifest,
+  // the conditional gather; 7 when the pass is split), 3 without.  Above: 6 (9) and 4.
+  const ckpt::HintState *hp = d_hint != nullptr ? &h : nullptr;
   if (e == hipSuccess)
-    e = ckpt::launch_diff_compact_scan(p, d_digests, d_ref, d_mask, hint_copy, misses, d_hint_misses,
-                                       staging_cap, d_manifest, manifest_cap, d_blocksums, d_counts,
-                                       s);
+    e = ckpt::launch_compact_scan(p, d_mask, d_digests, staging_cap, d_manifest, manifest_cap,
+                                  d_blocksums, d_counts, hp, d_hint_misses, s);
   if (e == hipSuccess)
-    e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap, misses, s);
+    e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
+                            hp ? h.misses : nullptr, hp ? h.need : nullptr,
+                            hp ? h.misses + 3 : nullptr, s);
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

@@ -75,6 +75,20 @@ __device__ __forceinline__ uint64_t pad16(uint64_t x) { return (x + 15) & ~15ull
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_PER_THREAD = 4;
 constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
+// Scan scratch (owned by a plan, 2 + 2 * ceil(N / SCAN_BLOCK) words): word 0 is a ticket counter
+// that is zero whenever no scan kernel is running, word 1 is spare, then one pair per block.
+constexpr int SCRATCH_HEAD = 2;
+// Up to this many chunks a workgroup finds its own scan offset by counting the mask bytes in
+// front of its block (at most 256 KiB per workgroup), which makes the scan a single kernel.
+constexpr uint64_t SMALL_SCAN_CHUNKS = 1ull << 18;
+
+// Fused snapshot: where the hint's derived state lives in the caller's workspace.
+struct HintState {
+  uint64_t *hoff;     // [N] staging offset every chunk would get if the hint were the mask
+  uint64_t *misses;   // counter block, SNAPSHOT_COUNTERS words: [0] chunks where hint != mask
+  uint8_t *copy;      // [N] private copy of the hint
+  uint8_t *need;      // [entries] 1 = the gather after a wrong hint must copy this entry
+};
 
 // Copy geometry: one wavefront moves one piece of one staged chunk per
 // iteration; a piece is min(C, COPY_PIECE) bytes.
@@ -84,39 +98,43 @@ constexpr int COPY_MAX_GROUPS = 65536;
 
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s);
+// The same pass, also writing d_mask[k] = (d_ref == null || digest != d_ref[k]).
+hipError_t launch_fingerprint_diff(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
+                                   uint8_t *d_mask, hipStream_t s);
 hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                       uint8_t *d_mask, uint64_t *d_blocksums, ckpt_counts_t *d_counts,
+                       uint8_t *d_mask, uint64_t *d_scratch, ckpt_counts_t *d_counts,
                        hipStream_t s);
+// Manifest and counts for a mask.  h (fused snapshot, may be null): hint misses are counted into
+// h->misses[0] and entries the pass has already staged in place are marked in h->need;
+// *d_misses_out (may be null) receives the miss count, 0 without h.
 hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
                                uint64_t staging_cap, ckpt_entry_t *d_manifest,
-                               uint64_t manifest_cap, uint64_t *d_blocksums,
-                               ckpt_counts_t *d_counts, hipStream_t s);
+                               uint64_t manifest_cap, uint64_t *d_scratch,
+                               ckpt_counts_t *d_counts, const HintState *h, uint64_t *d_misses_out,
+                               hipStream_t s);
+// d_only_if_nonzero (may be null): the kernel does nothing when it points to 0;  d_need (may be
+// null): entries e with d_need[e] == 0 are skipped;  d_copied (may be null): incremented once
+// per entry copied.
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
-                         const uint64_t *d_only_if_nonzero, hipStream_t s);
-// d_list: one uint32, d_flags: one byte per fingerprint group; d_list_counts: two uint64, zero
-// on entry; split:
-// staging groups and the rest in two launches (pays off from a few hundred MB of state).
-hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
+                         const uint64_t *d_only_if_nonzero, const uint8_t *d_need,
+                         uint64_t *d_copied, hipStream_t s);
+// The fused pass: fingerprint + mask + staging of the hinted chunks.  d_list: one uint32, d_flags:
+// one byte per fingerprint group; d_list_counts: two uint64, zero on entry; split: staging groups
+// and the rest in two launches (pays off from a few hundred MB of state).
+hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
+                                      uint8_t *d_mask, const uint8_t *d_hint,
                                       const uint64_t *d_hint_off, void *d_staging,
                                       uint64_t staging_cap, uint32_t *d_list, uint8_t *d_flags,
                                       uint64_t *d_list_counts, bool split, hipStream_t s);
 uint64_t fingerprint_groups(const PlanDev &p);
 // 64-bit words at the head of the fused snapshot's counter block, cleared by
-// launch_hint_offsets: [0] hint misses, [1..3] scratch counts, [4..5] group list lengths.
+// launch_hint_offsets: [0] hint misses, [1..3] scratch counts of the hint (word 3 ends up zero and
+// then counts the chunks the corrective gather copies), [4..5] group list lengths.
 constexpr int SNAPSHOT_COUNTERS = 6;
-hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8_t *d_hint_copy,
-                               uint64_t *d_blocksums, ckpt_counts_t *d_tmp_counts,
-                               uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
-                               hipStream_t s);
-// k_diff + scan + manifest in three kernels; with d_hint_copy the chunks where mask and hint
-// differ are added to *d_misses (cleared by launch_hint_offsets), and *d_misses_out (may be null)
-// receives that count, or 0 without a hint.
-hipError_t launch_diff_compact_scan(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                                    uint8_t *d_mask, const uint8_t *d_hint_copy, uint64_t *d_misses,
-                                    uint64_t *d_misses_out, uint64_t staging_cap,
-                                    ckpt_entry_t *d_manifest, uint64_t manifest_cap,
-                                    uint64_t *d_blocksums, ckpt_counts_t *d_counts, hipStream_t s);
+hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, const HintState &h,
+                               uint64_t *d_scratch, ckpt_counts_t *d_tmp_counts,
+                               uint64_t manifest_cap, hipStream_t s);
 // Applies min(nentries, d_counts->ndirty) entries when d_counts is not null, else nentries.
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const ckpt_counts_t *d_counts, const void *d_staging,

@@ -1,14 +1,20 @@
 // Checksum comparison and the prefix scan that orders the swap-out.
 //
-// diff: the comparison of a rank's checksums "with the other rank's copy" that
+// diff: the comparison of a rank's checksums with the other rank's copy that
 // the Singularity paper does on the host (sec. 6; sec. 5.2.1, 5.2.3) -- here a
 // device kernel, one thread per four chunks.
 //
 // compact, metadata half: stable compaction.  Staging order must be ascending
 // chunk id, so offsets come from an exclusive prefix sum over
-// (mask, mask * pad16(len)) pairs, done in three deterministic steps with no
-// inter-workgroup waiting: per-workgroup sums, a single-workgroup scan of
-// those sums, then a per-workgroup rescan that writes the manifest.
+// (mask, mask * pad16(len)) pairs.  No workgroup ever waits for another one:
+//   * every workgroup stores the pair of its SCAN_BLOCK chunks and takes a
+//     ticket; the one that draws the last ticket knows all pairs are stored
+//     and scans them (a single kernel where there used to be two);
+//   * a second kernel rescans each block from its offset and writes the
+//     manifest;
+//   * up to SMALL_SCAN_CHUNKS chunks even that is one kernel: a workgroup
+//     gets its offset by counting the mask bytes in front of its block
+//     itself (at most 256 KiB, out of L2), so nothing has to be handed over.
 #include "ckpt_internal.h"
 
 namespace ckpt {
@@ -74,41 +80,97 @@ __device__ __forceinline__ Pair sum_marked(const PlanDev &p, uint64_t k0, const 
   return s;
 }
 
-// mask[k] = (ref == nullptr || dig[k] != ref[k]); per-workgroup sums of the
-// marked chunks go to blocksums[2*b], [2*b+1].
-//
-// Fused snapshot: with `hint` (a private copy of the caller's hint, so that hint
-// and mask may be one buffer) the chunks whose mask differs from the hint are
-// counted into *misses.
+// Scan scratch: word 0 is the ticket counter (zero between kernels), word 1 is
+// spare, block b's pair sits in words SCRATCH_HEAD + 2b, + 2b + 1.
+__device__ __forceinline__ uint64_t *block_pairs(uint64_t *scratch) { return scratch + SCRATCH_HEAD; }
+
+// Every workgroup calls this after storing what it hands on.  True in exactly
+// one workgroup: the one that arrives last, by which time every other
+// workgroup's stores are visible to it.  Nobody waits.  That workgroup must put
+// the ticket back to zero before it ends (reset_ticket).
+__device__ bool arrived_last(uint64_t *scratch) {
+  __shared__ bool s_last;
+  __threadfence();                 // this workgroup's stores, device-wide
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned long long t = atomicAdd(reinterpret_cast<unsigned long long *>(scratch), 1ull);
+    s_last = t == (unsigned long long)gridDim.x - 1;
+  }
+  __syncthreads();
+  const bool last = s_last;
+  if (last) __threadfence();       // the other workgroups' stores
+  return last;
+}
+
+__device__ __forceinline__ void reset_ticket(uint64_t *scratch) {
+  if (threadIdx.x == 0) *reinterpret_cast<volatile uint64_t *>(scratch) = 0;
+}
+
+// One workgroup: turns pairs[0..nblocks) into their exclusive prefix sums
+// (when `rewrite`) and writes the grand totals to counts, overflow = 0.
+// Fused snapshot: *publish_dst (when not null) receives *publish_src, or 0
+// when there is no source -- the hint-miss count.
+__device__ void scan_pairs(uint64_t *pairs, uint64_t nblocks, bool rewrite, ckpt_counts_t *counts,
+                           const unsigned long long *publish_src, unsigned long long *publish_dst) {
+  Pair carry = {0, 0};
+  for (uint64_t base = 0; base < nblocks; base += SCAN_THREADS) {
+    const uint64_t b = base + threadIdx.x;
+    Pair v = {0, 0};
+    if (b < nblocks) v = {pairs[2 * b], pairs[2 * b + 1]};
+    Pair total;
+    Pair excl = block_exclusive_scan(v, &total);
+    if (rewrite && b < nblocks) {
+      pairs[2 * b] = carry.cnt + excl.cnt;
+      pairs[2 * b + 1] = carry.bytes + excl.bytes;
+    }
+    carry = carry + total;
+  }
+  if (threadIdx.x == 0) {
+    counts->ndirty = carry.cnt;
+    counts->staged_bytes = carry.bytes;
+    counts->overflow = 0;
+    if (publish_dst != nullptr)
+      *publish_dst = publish_src != nullptr ? *reinterpret_cast<const volatile unsigned long long *>(publish_src)
+                                            : 0ull;
+  }
+}
+
+// Tail of every kernel that produces block pairs: store, ticket, and in the
+// last workgroup the scan over all of them.
+__device__ void finish_pairs(uint64_t *scratch, Pair total, bool rewrite, ckpt_counts_t *counts,
+                             const unsigned long long *publish_src,
+                             unsigned long long *publish_dst) {
+  uint64_t *pairs = block_pairs(scratch);
+  if (threadIdx.x == 0) {
+    pairs[2 * (uint64_t)blockIdx.x] = total.cnt;
+    pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  }
+  if (arrived_last(scratch)) {
+    scan_pairs(pairs, gridDim.x, rewrite, counts, publish_src, publish_dst);
+    reset_ticket(scratch);
+  }
+}
+
+// mask[k] = (ref == nullptr || dig[k] != ref[k]); counts = totals over the mask.
 __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t *__restrict__ dig,
                                                        const uint64_t *__restrict__ ref,
                                                        uint8_t *__restrict__ mask,
-                                                       uint64_t *__restrict__ blocksums,
-                                                       const uint8_t *__restrict__ hint,
-                                                       unsigned long long *misses) {
+                                                       uint64_t *__restrict__ scratch,
+                                                       ckpt_counts_t *__restrict__ counts) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
-  uint32_t bad = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
       m[i] = (ref == nullptr || dig[k] != ref[k]) ? 1 : 0;
-      if (hint != nullptr) bad += (hint[k] != 0) != (m[i] != 0);
       mask[k] = m[i];
       n = i + 1;
     }
   }
-  if (hint != nullptr) {
-    for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
-    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
-  }
   Pair mine = sum_marked(p, k0, m, n, nullptr), total;
   block_exclusive_scan(mine, &total);
-  if (threadIdx.x == 0) {
-    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
-    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
-  }
+  finish_pairs(scratch, total, false, counts, nullptr, nullptr);
 }
 
 // Cross-worker upload ownership (sec. 4.6): gathered holds `world` rows of N
@@ -117,7 +179,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t
 // A thread reads `world` values per chunk, each row access coalesced over k.
 __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
     PlanDev p, const uint64_t *__restrict__ gathered, uint32_t world, uint32_t rank,
-    uint8_t *__restrict__ mask, uint64_t *__restrict__ blocksums) {
+    uint8_t *__restrict__ mask, uint64_t *__restrict__ scratch, ckpt_counts_t *__restrict__ counts) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
@@ -138,94 +200,166 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
   }
   Pair mine = sum_marked(p, k0, m, n, nullptr), total;
   block_exclusive_scan(mine, &total);
-  if (threadIdx.x == 0) {
-    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
-    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
-  }
+  finish_pairs(scratch, total, false, counts, nullptr, nullptr);
 }
 
-// Same sums for a caller-supplied mask (any non-zero byte marks a chunk).
-// Fused snapshot: the mask (there: the hint) is also copied to `keep`, and the
-// snapshot's counters zero_me[0 .. SNAPSHOT_COUNTERS) are cleared (hint misses,
-// which k_diff adds to later; scratch counts; the lengths of the group lists).
-__global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(PlanDev p,
-                                                             const uint8_t *__restrict__ mask,
-                                                             uint64_t *__restrict__ blocksums,
-                                                             uint8_t *__restrict__ keep,
-                                                             unsigned long long *zero_me) {
+// Block pairs of a caller-supplied mask (any non-zero byte marks a chunk), then
+// their exclusive prefix sums and the totals.
+// Fused snapshot, first use (the hint): the mask is also copied to `keep`, and
+// the snapshot's counters zero_me[0 .. SNAPSHOT_COUNTERS) are cleared.  Second
+// use (the real mask): chunks whose mask differs from `hint` are added to
+// *misses, and *misses_out receives the sum once every workgroup has added.
+__global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(
+    PlanDev p, const uint8_t *__restrict__ mask, uint64_t *__restrict__ scratch,
+    ckpt_counts_t *__restrict__ counts, uint8_t *__restrict__ keep, unsigned long long *zero_me,
+    const uint8_t *__restrict__ hint, unsigned long long *misses, unsigned long long *misses_out) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
+  uint32_t bad = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
       const uint8_t v = mask[k];
       if (keep != nullptr) keep[k] = v;
       m[i] = v != 0;
+      if (hint != nullptr) bad += (hint[k] != 0) != (m[i] != 0);
       n = i + 1;
     }
   }
   if (zero_me != nullptr && blockIdx.x == 0 && threadIdx.x < SNAPSHOT_COUNTERS)
     zero_me[threadIdx.x] = 0;
+  if (hint != nullptr) {
+    for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
+  }
   Pair mine = sum_marked(p, k0, m, n, nullptr), total;
   block_exclusive_scan(mine, &total);
-  if (threadIdx.x == 0) {
-    blocksums[2 * (uint64_t)blockIdx.x] = total.cnt;
-    blocksums[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
-  }
+  finish_pairs(scratch, total, true, counts, misses, misses_out);
 }
 
-// One workgroup: turns blocksums[0..nblocks) into their exclusive prefix sums
-// (when `rewrite`) and writes the grand totals to counts, overflow = 0.
-// Fused snapshot: *publish_dst (when not null) receives *publish_src, or 0
-// when there is no source -- the hint-miss count, complete once k_diff is.
-__global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(
-    uint64_t *__restrict__ blocksums, uint64_t nblocks, int rewrite,
-    ckpt_counts_t *__restrict__ counts, const unsigned long long *publish_src,
-    unsigned long long *publish_dst) {
-  Pair carry = {0, 0};
-  for (uint64_t base = 0; base < nblocks; base += SCAN_THREADS) {
-    const uint64_t b = base + threadIdx.x;
-    Pair v = {0, 0};
-    if (b < nblocks) v = {blocksums[2 * b], blocksums[2 * b + 1]};
-    Pair total;
-    Pair excl = block_exclusive_scan(v, &total);
-    if (rewrite && b < nblocks) {
-      blocksums[2 * b] = carry.cnt + excl.cnt;
-      blocksums[2 * b + 1] = carry.bytes + excl.bytes;
-    }
-    carry = carry + total;
+// Sum over the workgroup of one value per thread, returned in every thread.
+__device__ uint64_t block_sum(uint64_t v) {
+  __shared__ uint64_t s_part[SCAN_THREADS / 64];
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint64_t all = 0;
+#pragma unroll
+  for (int w = 0; w < SCAN_THREADS / 64; ++w) all += s_part[w];
+  return all;
+}
+
+// Non-zero bytes among the four of a word.
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w) {
+  return __popc((((w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | w) & 0x80808080u);
+}
+
+// The pair of all marked chunks with id < k0, computed by the calling workgroup
+// from the mask bytes themselves: their number by counting non-zero bytes, and
+// their padded bytes as number * C minus what the marked short last chunks fall
+// short of C (the plan lists those: at most one per buffer).
+__device__ Pair pair_before(const PlanDev &p, const uint8_t *__restrict__ mask, uint64_t k0) {
+  uint64_t cnt = 0, lost = 0;
+  uint64_t head = (16 - (reinterpret_cast<uintptr_t>(mask) & 15)) & 15;   // bytes before 16-byte alignment
+  if (head > k0) head = k0;
+  if (threadIdx.x < head) cnt += mask[threadIdx.x] != 0;
+  const uint64_t nvec = (k0 - head) / 16;
+  const uint4 *v = reinterpret_cast<const uint4 *>(mask + head);
+  for (uint64_t i = threadIdx.x; i < nvec; i += SCAN_THREADS) {
+    const uint4 w = v[i];
+    cnt += nonzero_bytes(w.x) + nonzero_bytes(w.y) + nonzero_bytes(w.z) + nonzero_bytes(w.w);
   }
+  const uint64_t tail = head + 16 * nvec;
+  if (tail + threadIdx.x < k0) cnt += mask[tail + threadIdx.x] != 0;     // fewer than 16 left
+  const uint64_t c = 1ull << p.chunk_log2;
+  for (uint64_t s = threadIdx.x; s < p.nshort; s += SCAN_THREADS) {
+    const uint64_t k = p.short_chunk[s];
+    if (k < k0 && mask[k] != 0) lost += c - pad16(p.short_len[s]);
+  }
+  Pair r;
+  r.cnt = block_sum(cnt);
+  r.bytes = r.cnt * c - block_sum(lost);
+  return r;
+}
+
+// What one workgroup of the one-kernel paths hands to the last one: marked
+// chunks, entries that missed a capacity and hint misses of its block (each at
+// most SCAN_BLOCK, 20 bits apiece) in one word, padded bytes in the other.
+__device__ void finish_small(uint64_t *scratch, Pair total, uint32_t missed, uint32_t bad,
+                             ckpt_counts_t *counts, unsigned long long *misses,
+                             unsigned long long *misses_out) {
+  uint64_t *pairs = block_pairs(scratch);
+  const uint64_t all_missed = block_sum(missed), all_bad = block_sum(bad);
   if (threadIdx.x == 0) {
-    counts->ndirty = carry.cnt;
-    counts->staged_bytes = carry.bytes;
-    counts->overflow = 0;
-    if (publish_dst != nullptr) *publish_dst = publish_src != nullptr ? *publish_src : 0ull;
+    pairs[2 * (uint64_t)blockIdx.x] = total.cnt | (all_missed << 20) | (all_bad << 40);
+    pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  }
+  if (arrived_last(scratch)) {
+    uint64_t cnt = 0, bytes = 0, over = 0, wrong = 0;
+    for (uint64_t b = threadIdx.x; b < gridDim.x; b += SCAN_THREADS) {
+      const uint64_t w = pairs[2 * b];
+      cnt += w & 0xFFFFF;
+      over += (w >> 20) & 0xFFFFF;
+      wrong += w >> 40;
+      bytes += pairs[2 * b + 1];
+    }
+    cnt = block_sum(cnt);
+    bytes = block_sum(bytes);
+    over = block_sum(over);
+    wrong = block_sum(wrong);
+    if (threadIdx.x == 0) {
+      counts->ndirty = cnt;
+      counts->staged_bytes = bytes;
+      counts->overflow = over;
+      if (misses != nullptr) *misses = wrong;
+      if (misses_out != nullptr) *misses_out = wrong;
+    }
+    reset_ticket(scratch);
   }
 }
 
 // Final pass: every marked chunk learns its entry index and staging offset and
-// writes its manifest entry.  blockoff holds the exclusive sums from
-// k_scan_blocks.  Entries that miss a capacity are counted in counts->overflow.
+// writes its manifest entry.  !SMALL: scratch holds the exclusive block sums,
+// counts the totals; entries that miss a capacity are added to
+// counts->overflow.  SMALL: the workgroup computes its own offset
+// (pair_before), and the last workgroup writes the counts.
+// Fused snapshot (hint, hoff, need not null): entry e gets need[e] = 0 if the
+// fingerprint pass has already staged the chunk at this very offset (it was
+// hinted, its hinted offset equals the real one, and it fitted), else 1 -- the
+// gather that follows a wrong hint copies only those.  SMALL also counts the
+// chunks where hint and mask differ.
+template <bool SMALL>
 __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
     PlanDev p, const uint8_t *__restrict__ mask, const uint64_t *__restrict__ dig,
-    const uint64_t *__restrict__ blockoff, ckpt_entry_t *__restrict__ manifest,
-    uint64_t manifest_cap, uint64_t staging_cap, ckpt_counts_t *__restrict__ counts) {
+    uint64_t *__restrict__ scratch, ckpt_entry_t *__restrict__ manifest, uint64_t manifest_cap,
+    uint64_t staging_cap, ckpt_counts_t *__restrict__ counts, const uint8_t *__restrict__ hint,
+    const uint64_t *__restrict__ hoff, uint8_t *__restrict__ need, unsigned long long *misses,
+    unsigned long long *misses_out) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   ChunkRef refs[SCAN_PER_THREAD];
   int n = 0;
+  uint32_t bad = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
       m[i] = mask[k] != 0;
+      if (SMALL && hint != nullptr) bad += (hint[k] != 0) != (m[i] != 0);
       n = i + 1;
     }
   }
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   Pair pos = block_exclusive_scan(mine, &total);
-  pos.cnt += blockoff[2 * (uint64_t)blockIdx.x];
-  pos.bytes += blockoff[2 * (uint64_t)blockIdx.x + 1];
+  Pair before;
+  if (SMALL) {
+    before = pair_before(p, mask, (uint64_t)blockIdx.x * SCAN_BLOCK);
+  } else {
+    const uint64_t *blockoff = block_pairs(scratch);
+    before = {blockoff[2 * (uint64_t)blockIdx.x], blockoff[2 * (uint64_t)blockIdx.x + 1]};
+  }
+  pos = pos + before;
   uint32_t missed = 0;
   for (int i = 0; i < n; ++i) {
     if (!m[i]) continue;
@@ -241,22 +375,30 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
       e.stage_off = pos.bytes;
       e.digest = dig[k0 + i];
       manifest[pos.cnt] = e;
+      if (need != nullptr)
+        need[pos.cnt] = !(fits_staging && hint[k0 + i] != 0 && hoff[k0 + i] == pos.bytes);
     }
     if (!fits_staging) ++missed;
     pos.cnt += 1;
     pos.bytes += padded;
   }
-  if (missed) atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow),
-                        (unsigned long long)missed);
+  if (SMALL) {
+    finish_small(scratch, total, missed, bad, counts, misses, misses_out);
+  } else if (missed) {
+    atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow), (unsigned long long)missed);
+  }
 }
 
 // Fused snapshot, before the pass: staging offset of every hinted chunk (the
-// exclusive prefix sum over the hint, as k_emit_manifest computes it for a mask).
-__global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(PlanDev p,
-                                                               const uint8_t *__restrict__ hint,
-                                                               const uint64_t *__restrict__ blockoff,
-                                                               uint64_t manifest_cap,
-                                                               uint64_t *__restrict__ hoff) {
+// exclusive prefix sum over the hint, as k_emit_manifest computes it for a
+// mask).  SMALL: one kernel does it all -- reads the caller's hint, keeps a
+// private copy (hint and mask may be one buffer), clears the snapshot's
+// counters; otherwise k_block_sums has done those and left the block offsets.
+template <bool SMALL>
+__global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(
+    PlanDev p, const uint8_t *__restrict__ hint, const uint64_t *__restrict__ scratch,
+    uint64_t manifest_cap, uint64_t *__restrict__ hoff, uint8_t *__restrict__ keep,
+    unsigned long long *zero_me) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   ChunkRef refs[SCAN_PER_THREAD];
@@ -264,14 +406,23 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(PlanDev p,
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
     if (k < p.nchunks) {
-      m[i] = hint[k] != 0;
+      const uint8_t v = hint[k];
+      if (SMALL) keep[k] = v;
+      m[i] = v != 0;
       n = i + 1;
     }
   }
+  if (SMALL && blockIdx.x == 0 && threadIdx.x < SNAPSHOT_COUNTERS) zero_me[threadIdx.x] = 0;
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   Pair pos = block_exclusive_scan(mine, &total);
-  pos.cnt += blockoff[2 * (uint64_t)blockIdx.x];
-  pos.bytes += blockoff[2 * (uint64_t)blockIdx.x + 1];
+  Pair before;
+  if (SMALL) {
+    before = pair_before(p, hint, (uint64_t)blockIdx.x * SCAN_BLOCK);
+  } else {
+    const uint64_t *blockoff = scratch + SCRATCH_HEAD;
+    before = {blockoff[2 * (uint64_t)blockIdx.x], blockoff[2 * (uint64_t)blockIdx.x + 1]};
+  }
+  pos = pos + before;
   for (int i = 0; i < n; ++i) {
     // a chunk whose entry would not fit the manifest is not staged either (all-ones = never fits)
     hoff[k0 + i] = pos.cnt < manifest_cap ? pos.bytes : ~0ull;
@@ -280,6 +431,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(PlanDev p,
       pos.bytes += pad16(refs[i].len);
     }
   }
+}
+
+// No chunks at all: the counts (and the miss counters) are still written.
+__global__ void k_empty_counts(ckpt_counts_t *counts, unsigned long long *misses,
+                               unsigned long long *misses_out) {
+  counts->ndirty = counts->staged_bytes = counts->overflow = 0;
+  if (misses != nullptr) *misses = 0;
+  if (misses_out != nullptr) *misses_out = 0;
 }
 
 // Squashing validation (paper sec. 5.2.3): per chunk, did rank a and rank b
@@ -330,71 +489,85 @@ inline uint32_t scan_blocks(uint64_t nchunks) {
   return (uint32_t)((nchunks + SCAN_BLOCK - 1) / SCAN_BLOCK);
 }
 
+typedef unsigned long long ull;
+
 }  // namespace
 
 hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                       uint8_t *d_mask, uint64_t *d_blocksums, ckpt_counts_t *d_counts,
+                       uint8_t *d_mask, uint64_t *d_scratch, ckpt_counts_t *d_counts,
                        hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
-                       d_blocksums, (const uint8_t *)nullptr, (unsigned long long *)nullptr);
-  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 0, d_counts, (const unsigned long long *)nullptr,
-                     (unsigned long long *)nullptr);
-  return hipGetLastError();
-}
-
-// diff and the metadata half of compact as one sequence of three kernels (the
-// workgroup sums k_diff leaves behind are the ones the compaction scan needs).
-hipError_t launch_diff_compact_scan(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                                    uint8_t *d_mask, const uint8_t *d_hint_copy, uint64_t *d_misses,
-                                    uint64_t *d_misses_out, uint64_t staging_cap,
-                                    ckpt_entry_t *d_manifest, uint64_t manifest_cap,
-                                    uint64_t *d_blocksums, ckpt_counts_t *d_counts, hipStream_t s) {
-  const uint32_t nblocks = scan_blocks(p.nchunks);
-  unsigned long long *misses = reinterpret_cast<unsigned long long *>(d_misses);
-  if (nblocks)
-    hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
-                       d_blocksums, d_hint_copy, misses);
-  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 1, d_counts, (const unsigned long long *)misses,
-                     reinterpret_cast<unsigned long long *>(d_misses_out));
-  if (nblocks)
-    hipLaunchKernelGGL(k_emit_manifest, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dig,
-                       d_blocksums, d_manifest, manifest_cap, staging_cap, d_counts);
+                       d_scratch, d_counts);
+  else
+    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, (ull *)nullptr,
+                       (ull *)nullptr);
   return hipGetLastError();
 }
 
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
-                                uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
+                                uint32_t rank, uint8_t *d_mask, uint64_t *d_scratch,
                                 ckpt_counts_t *d_counts, hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_upload_owners, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_gathered,
-                       world, rank, d_mask, d_blocksums);
-  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 0, d_counts, (const unsigned long long *)nullptr,
-                     (unsigned long long *)nullptr);
+                       world, rank, d_mask, d_scratch, d_counts);
+  else
+    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, (ull *)nullptr,
+                       (ull *)nullptr);
   return hipGetLastError();
 }
 
-hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, uint8_t *d_hint_copy,
-                               uint64_t *d_blocksums, ckpt_counts_t *d_tmp_counts,
-                               uint64_t manifest_cap, uint64_t *d_hoff, uint64_t *d_misses,
+// The metadata half of compact for a given mask: one kernel up to SMALL_SCAN_CHUNKS chunks,
+// two above.  With h (fused snapshot) the hint misses are counted and the entries the pass has
+// already staged are marked in h->need.
+hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
+                               uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                               uint64_t manifest_cap, uint64_t *d_scratch,
+                               ckpt_counts_t *d_counts, const HintState *h, uint64_t *d_misses_out,
                                hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
-  if (nblocks)
+  const uint8_t *hint = h ? h->copy : nullptr;
+  const uint64_t *hoff = h ? h->hoff : nullptr;
+  uint8_t *need = h ? h->need : nullptr;
+  ull *misses = h ? reinterpret_cast<ull *>(h->misses) : nullptr;
+  ull *misses_out = reinterpret_cast<ull *>(d_misses_out);
+  if (nblocks == 0) {
+    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, misses, misses_out);
+  } else if (p.nchunks <= SMALL_SCAN_CHUNKS) {
+    hipLaunchKernelGGL(k_emit_manifest<true>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
+                       d_dig, d_scratch, d_manifest, manifest_cap, staging_cap, d_counts, hint, hoff,
+                       need, misses, misses_out);
+  } else {
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_scratch,
+                       d_counts, (uint8_t *)nullptr, (ull *)nullptr, hint, misses, misses_out);
+    hipLaunchKernelGGL(k_emit_manifest<false>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
+                       d_dig, d_scratch, d_manifest, manifest_cap, staging_cap, d_counts, hint, hoff,
+                       need, (ull *)nullptr, (ull *)nullptr);
+  }
+  return hipGetLastError();
+}
+
+// Staging offsets of the hinted chunks, the private copy of the hint, cleared counters.
+hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, const HintState &h,
+                               uint64_t *d_scratch, ckpt_counts_t *d_tmp_counts,
+                               uint64_t manifest_cap, hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  ull *zero_me = reinterpret_cast<ull *>(h.misses);
+  if (nblocks == 0) {
+    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_tmp_counts, zero_me, (ull *)nullptr);
+  } else if (p.nchunks <= SMALL_SCAN_CHUNKS) {
+    hipLaunchKernelGGL(k_hint_offsets<true>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in,
+                       (const uint64_t *)nullptr, manifest_cap, h.hoff, h.copy, zero_me);
+  } else {
     hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in,
-                       d_blocksums, d_hint_copy, reinterpret_cast<unsigned long long *>(d_misses));
-  // with no chunks the scan kernel clears the miss counter instead
-  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 1, d_tmp_counts, (const unsigned long long *)nullptr,
-                     nblocks ? (unsigned long long *)nullptr
-                             : reinterpret_cast<unsigned long long *>(d_misses));
-  if (nblocks)
-    hipLaunchKernelGGL(k_hint_offsets, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_copy,
-                       d_blocksums, manifest_cap, d_hoff);
+                       d_scratch, d_tmp_counts, h.copy, zero_me, (const uint8_t *)nullptr,
+                       (ull *)nullptr, (ull *)nullptr);
+    hipLaunchKernelGGL(k_hint_offsets<false>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p,
+                       (const uint8_t *)h.copy, (const uint64_t *)d_scratch, manifest_cap, h.hoff,
+                       (uint8_t *)nullptr, (ull *)nullptr);
+  }
   return hipGetLastError();
 }
 
@@ -407,23 +580,6 @@ hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a,
     hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
                        b_b, a_b, d_result);
   }
-  return hipGetLastError();
-}
-
-hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
-                               uint64_t staging_cap, ckpt_entry_t *d_manifest,
-                               uint64_t manifest_cap, uint64_t *d_blocksums,
-                               ckpt_counts_t *d_counts, hipStream_t s) {
-  const uint32_t nblocks = scan_blocks(p.nchunks);
-  if (nblocks)
-    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
-                       d_blocksums, (uint8_t *)nullptr, (unsigned long long *)nullptr);
-  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_blocksums,
-                     (uint64_t)nblocks, 1, d_counts, (const unsigned long long *)nullptr,
-                     (unsigned long long *)nullptr);
-  if (nblocks)
-    hipLaunchKernelGGL(k_emit_manifest, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dig,
-                       d_blocksums, d_manifest, manifest_cap, staging_cap, d_counts);
   return hipGetLastError();
 }
 

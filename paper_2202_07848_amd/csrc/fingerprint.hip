@@ -172,6 +172,10 @@ struct StageArgs {
   const uint32_t *list;
   const unsigned long long *counts;
   uint32_t ngroups;
+  // the comparison of ckpt_diff done on the spot: mask[k] = (ref == null || digest != ref[k]),
+  // written by the lane that finishes the digest (mask null: not wanted)
+  const uint64_t *ref;
+  uint8_t *mask;
 };
 
 // Slot `lane` of group `group`: the chunk's address, global id and length (0: empty slot).
@@ -407,7 +411,10 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
       tp += 1;
       left -= 1;
     }
-    dig[s_chunk[c]] = xxh::avalanche(h);
+    h = xxh::avalanche(h);
+    const uint64_t k = s_chunk[c];
+    dig[k] = h;
+    if (st.mask != nullptr) st.mask[k] = (st.ref == nullptr || h != st.ref[k]) ? 1 : 0;
   }
 }
 
@@ -424,14 +431,27 @@ hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t
   const uint64_t groups = fingerprint_groups(p);
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_fingerprint<MODE_PLAIN>, dim3((uint32_t)groups), dim3(64), 0, s, p,
-                     d_digests, StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0});
+                     d_digests,
+                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr});
+  return hipGetLastError();
+}
+
+hipError_t launch_fingerprint_diff(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
+                                   uint8_t *d_mask, hipStream_t s) {
+  if (p.nchunks == 0) return hipSuccess;
+  const uint64_t groups = fingerprint_groups(p);
+  if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_fingerprint<MODE_PLAIN>, dim3((uint32_t)groups), dim3(64), 0, s, p,
+                     d_digests,
+                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, d_ref, d_mask});
   return hipGetLastError();
 }
 
 // split: the group lists, then two launches: first the groups that stage at least one chunk,
 // then the others.  d_list holds one uint32 and d_flags one byte per group; d_list_counts two
 // uint64 that are zero when the first kernel here starts.  !split: one launch over all groups.
-hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint8_t *d_hint,
+hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
+                                      uint8_t *d_mask, const uint8_t *d_hint,
                                       const uint64_t *d_hint_off, void *d_staging,
                                       uint64_t staging_cap, uint32_t *d_list, uint8_t *d_flags,
                                       uint64_t *d_list_counts, bool split, hipStream_t s) {
@@ -440,7 +460,7 @@ hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, con
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   unsigned long long *counts = reinterpret_cast<unsigned long long *>(d_list_counts);
   const StageArgs st{d_hint, d_hint_off, reinterpret_cast<uint8_t *>(d_staging), staging_cap,
-                     d_list,  counts,    (uint32_t)groups};
+                     d_list,  counts,    (uint32_t)groups, d_ref, d_mask};
   if (!split) {
     hipLaunchKernelGGL(k_fingerprint<MODE_MIXED>, dim3((uint32_t)groups), dim3(64), 0, s, p,
                        d_digests, st);

@@ -237,21 +237,23 @@ __global__ __launch_bounds__(COPY_THREADS) void k_moves(PlanDev p,
     const uint32_t padded = (uint32_t)pad16(ent.len);
     if (hi > padded) hi = padded;
     uint8_t *slot = temp + ent.stage_off;
+    // a move whose source is no chunk of the plan, or a chunk of another length, is rejected in
+    // both phases alike: its temp slot is never filled and its destination never written
+    const uint64_t j = ent.digest;                        // source chunk id
+    bool ok = j < p.nchunks;
+    ChunkRef from = {0, 0, 0};
+    if (ok) {
+      from = locate_chunk(p, j);
+      ok = from.len == ent.len;
+    }
+    if (!ok) {
+      if (!SCATTER && rejected != nullptr && piece == 0 && lane == 0) atomicAdd(rejected, 1ull);
+      continue;
+    }
     if (SCATTER) {
       uint8_t *to = reinterpret_cast<uint8_t *>(p.list_ptr[ent.buf]) + ent.buf_off;
       move_piece<false>(slot, to, lo, hi, ent.len, lane);
     } else {
-      const uint64_t j = ent.digest;                      // source chunk id
-      bool ok = j < p.nchunks;
-      ChunkRef from = {0, 0, 0};
-      if (ok) {
-        from = locate_chunk(p, j);
-        ok = from.len == ent.len;
-      }
-      if (!ok) {          // leaves the slot's old bytes; counted so that the caller can tell
-        if (rejected != nullptr && piece == 0 && lane == 0) atomicAdd(rejected, 1ull);
-        continue;
-      }
       const uint8_t *sp = reinterpret_cast<const uint8_t *>(p.dense_ptr[from.row]) + from.off;
       move_piece<true>(sp, slot, lo, hi, ent.len, lane);
     }
@@ -320,7 +322,7 @@ hipError_t launch_moves_inplace(const PlanDev &p, const int64_t *d_src, void *d_
   if (groups) hipLaunchKernelGGL(k_mark_moves, dim3(groups), dim3(256), 0, s, d_src, n, moved);
   // the manifest scan, with src[k] travelling in the digest field of each entry
   hipError_t e = launch_compact_scan(p, moved, reinterpret_cast<const uint64_t *>(d_src), temp_cap,
-                                     moves, n, d_blocksums, d_counts, s);
+                                     moves, n, d_blocksums, d_counts, nullptr, nullptr, s);
   if (e != hipSuccess || n == 0) return e;
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
   const uint64_t items = n << (p.chunk_log2 - piece_log2);

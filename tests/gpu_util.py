@@ -9,6 +9,9 @@ from paper_2202_07848_amd import binding as ck
 
 CANARY = 0xC7
 GAP = 64          # canary bytes between buffers (keeps 16-byte alignment)
+# When not None, every plan DeviceBuffers creates gets this split threshold (the state size from
+# which the hinted snapshot pass runs as two launches): tests force both launch shapes with it.
+SPLIT_THRESHOLD = None
 
 
 class DeviceBuffers:
@@ -28,6 +31,8 @@ class DeviceBuffers:
         base = self.arena.data_ptr()
         assert base % 16 == 0
         self.plan = ck.Plan([(base + o, n) for o, n in zip(offs, self.sizes)], chunk)
+        if SPLIT_THRESHOLD is not None:
+            self.plan.split_threshold = SPLIT_THRESHOLD
 
     def host(self):
         """Current device bytes of every buffer plus the whole arena image."""

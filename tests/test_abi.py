@@ -50,6 +50,17 @@ def test_host_side_argument_checks_need_no_device():
     one[0].ptr = None
     assert lib.ckpt_plan_create(one, 1, 4096, ctypes.byref(out)) == -1        # NULL with bytes
     assert out.value is None
+    # two buffers of one list that share a byte (checked before anything touches a device)
+    two = (ck._Buf * 3)()
+    two[0].ptr, two[0].nbytes = 0x20000, 8192
+    two[1].ptr, two[1].nbytes = 0x10000, 4096
+    two[2].ptr, two[2].nbytes = 0x21FF0, 64            # starts 16 bytes before buffer 0 ends
+    assert lib.ckpt_plan_create(two, 3, 4096, ctypes.byref(out)) == -1
+    two[2].ptr = 0x20000                                # the same buffer twice
+    assert lib.ckpt_plan_create(two, 3, 4096, ctypes.byref(out)) == -1
+    assert out.value is None
+    assert lib.ckpt_plan_set_split_threshold(None, 0) == -1
+    assert lib.ckpt_plan_split_threshold(None) == 0
     assert lib.ckpt_fingerprint(None, None, None) == -1
     assert lib.ckpt_diff(None, None, None, 0, None, None, None) == -1
     assert lib.ckpt_compact(None, None, None, None, 0, None, 0, None, None) == -1

@@ -18,10 +18,10 @@ pytestmark = pytest.mark.gpu
 def fused_pass_shape(request):
     """Every test here runs with the hinted pass forced into each of its two launch shapes (the
     library picks by state size, and these inputs are all on the small side)."""
-    before = ck.snapshot_split_threshold()
-    ck.snapshot_set_split_threshold(0 if request.param == "two_launches" else 2**64 - 1)
+    import gpu_util
+    gpu_util.SPLIT_THRESHOLD = 0 if request.param == "two_launches" else 2**64 - 1
     yield request.param
-    ck.snapshot_set_split_threshold(before)
+    gpu_util.SPLIT_THRESHOLD = None
 
 
 def test_snapshot_and_restore_replay_from_a_hip_graph():

@@ -97,6 +97,38 @@ def test_odd_sizes_against_reference(chunk):
     assert 0 < cnt["ndirty"] < oracle.nchunks(snap, chunk)
 
 
+def sizes_with_chunks(total_chunks, chunk):
+    """A ragged buffer list (odd sizes, empty buffers, short last chunks) with exactly
+    total_chunks chunks."""
+    sizes = [1, 255, 257, 1000, 70001, 0, 4097, 300, 123457, 31, 5 * chunk, 0, 999999, chunk + 1]
+    have = sum(-(-n // chunk) for n in sizes)
+    left = total_chunks - have
+    assert left > 2
+    half = left // 2
+    return sizes[:7] + [half * chunk] + sizes[7:] + [(left - half) * chunk - 17]
+
+
+@pytest.mark.parametrize("nchunks", [1 << 18, (1 << 18) + 1],
+                         ids=["scan_in_one_kernel_at_its_limit", "scan_in_two_kernels"])
+def test_both_scan_shapes_at_the_switch_over(nchunks):
+    """Up to 2**18 chunks every workgroup of the manifest kernel counts the marked chunks in
+    front of its block itself; above, block sums are scanned by the workgroup that finishes
+    last and a second kernel writes the manifest.  One case on each side of the boundary."""
+    chunk = 256
+    sizes = sizes_with_chunks(nchunks, chunk)
+    ref = host_bufs(21, sizes)
+    assert oracle.nchunks(ref, chunk) == nchunks
+    snap = [b.copy() for b in ref]
+    rng = np.random.default_rng(22)
+    for b in snap:                          # about 1 byte in 700 differs, everywhere
+        if b.size:
+            b[rng.integers(0, b.size, size=max(1, b.size // 700))] ^= 0x3C
+    cnt = full_pipeline_check(snap, ref, chunk)
+    assert nchunks // 8 < cnt["ndirty"] < nchunks
+    cnt = full_pipeline_check(snap, None, chunk)
+    assert cnt["ndirty"] == nchunks
+
+
 def test_identical_replica_stages_nothing():
     ref = host_bufs(4, ODD_SIZES)
     cnt = full_pipeline_check([b.copy() for b in ref], ref, 1024)

@@ -19,10 +19,10 @@ pytestmark = pytest.mark.gpu
 def fused_pass_shape(request):
     """Every test here runs with the hinted pass forced into each of its two launch shapes (the
     library picks by state size, and these inputs are all on the small side)."""
-    before = ck.snapshot_split_threshold()
-    ck.snapshot_set_split_threshold(0 if request.param == "two_launches" else 2**64 - 1)
+    import gpu_util
+    gpu_util.SPLIT_THRESHOLD = 0 if request.param == "two_launches" else 2**64 - 1
     yield request.param
-    ck.snapshot_set_split_threshold(before)
+    gpu_util.SPLIT_THRESHOLD = None
 
 ODD_SIZES = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 288, 511, 512, 1000, 4095, 4096, 4097,
              8191, 8192, 12289, 0, 31, 100000, 7, 65536, 65537, 3, 262144 + 40, 5000]
@@ -49,7 +49,26 @@ def run_snapshot(dev, ref, hint, staging_cap, manifest_cap, alias_hint_and_mask=
                 staging_cap=staging_cap, manifest_cap=manifest_cap,
                 n_ref=None if ref is None else n)
     torch.cuda.synchronize()
-    return dig, mask, staging, manifest, counts_dict(counts), int(misses.item())
+    stats = ck.snapshot_stats(ws, n) if hint is not None else None
+    return dig, mask, staging, manifest, counts_dict(counts), int(misses.item()), stats
+
+
+def expected_regather(lens, h, o_mask, staging_cap, manifest_cap):
+    """Entries the corrective gather has to copy after a pass guided by hint h: those the pass
+    did not already put at their final offset.  Host arithmetic on the definition: a chunk is in
+    place iff it was hinted, its entry would have fitted the manifest in the hint's numbering,
+    the hint's prefix sum gives it the offset the real mask's prefix sum gives it, and it fits."""
+    pad = (lens.astype(np.int64) + 15) // 16 * 16
+    hm, m = (h != 0), (o_mask != 0)
+    if not np.any(hm != m):
+        return 0
+    hoff = np.cumsum(pad * hm) - pad * hm
+    hcnt = np.cumsum(hm) - hm
+    off = np.cumsum(pad * m) - pad * m
+    cnt = np.cumsum(m) - m
+    fits = m & (cnt < manifest_cap) & (off + pad <= staging_cap)
+    in_place = fits & hm & (hcnt < manifest_cap) & (hoff == off)
+    return int((fits & ~in_place).sum())
 
 
 def check_against_oracle(snap, ref_bufs, chunk, hint_kind, staging_cap=None, manifest_cap=None,
@@ -77,13 +96,18 @@ def check_against_oracle(snap, ref_bufs, chunk, hint_kind, staging_cap=None, man
         h = (rng.random(n) < 0.5).astype(np.uint8) * 7          # any non-zero byte marks
     hint = None if h is None else torch.from_numpy(h if h.size else np.zeros(1, np.uint8)).cuda()
     ref = None if o_ref is None else torch.from_numpy(o_ref.view(np.int64)).cuda()
-    dig, mask, staging, manifest, cnt, misses = run_snapshot(
+    dig, mask, staging, manifest, cnt, misses, stats = run_snapshot(
         dev, ref, hint, o_st.size, o_man.size, alias_hint_and_mask=alias)
     assert np.array_equal(u64(dig, n), o_dig)
     assert np.array_equal(mask[:n].cpu().numpy(), o_mask)
     assert cnt == o_cnt2
     want_misses = 0 if h is None else int(((h != 0) != (o_mask != 0)).sum())
     assert misses == want_misses
+    if h is not None:
+        # the gather after a wrong hint copies exactly the chunks that are not yet in place
+        assert stats["hint_misses"] == want_misses
+        assert stats["regathered_chunks"] == expected_regather(
+            oracle.chunk_lens(snap, chunk), h, o_mask, o_st.size, o_man.size)
     man_raw = manifest.cpu().numpy()
     assert np.array_equal(man_raw[:32 * o_man.size].view(oracle.ENTRY_DTYPE), o_man)
     assert np.all(man_raw[32 * o_man.size:] == 0xA5)
@@ -116,6 +140,48 @@ def test_snapshot_against_reference(chunk, hint_kind):
     cnt, misses = check_against_oracle(snap, ref, chunk, hint_kind)
     assert 0 < cnt["ndirty"] < oracle.nchunks(snap, chunk)
     assert (misses == 0) == (hint_kind in ("exact", "none"))
+
+
+@pytest.mark.parametrize("hint_kind", ["exact", "none", "one_flip", "random"])
+@pytest.mark.parametrize("nchunks", [1 << 18, (1 << 18) + 1],
+                         ids=["scan_in_one_kernel_at_its_limit", "scan_in_two_kernels"])
+def test_snapshot_both_scan_shapes_at_the_switch_over(nchunks, hint_kind):
+    from test_gpu_parity import sizes_with_chunks
+    chunk = 256
+    ref = host_bufs(31, sizes_with_chunks(nchunks, chunk))
+    snap = [b.copy() for b in ref]
+    rng = np.random.default_rng(32)
+    for b in snap:
+        if b.size:
+            b[rng.integers(0, b.size, size=max(1, b.size // 900))] ^= 0x11
+    cnt, misses = check_against_oracle(snap, ref, chunk, hint_kind)
+    assert nchunks // 8 < cnt["ndirty"] < nchunks
+    assert (misses == 0) == (hint_kind in ("exact", "none"))
+
+
+def test_one_wrong_hint_chunk_regathers_only_what_lies_behind_it():
+    """A hint that is wrong in one chunk in the middle: the chunks staged before it stay as the
+    pass wrote them, the gather copies the ones behind it (about half), and the result is exact."""
+    chunk = 4096
+    ref = host_bufs(41, [1 << 20, 3 << 20, 4096 * 9 + 5, 2 << 20])
+    snap = [b.copy() for b in ref]
+    for b in snap:
+        b[::8192] ^= 0x7E                      # every second chunk differs
+    dev = DeviceBuffers(snap, chunk)
+    n = dev.plan.nchunks
+    o_dig, o_ref = oracle.fingerprint(snap, chunk, 8), oracle.fingerprint(ref, chunk, 8)
+    o_mask, _ = oracle.diff(snap, chunk, o_dig, o_ref)
+    o_st, o_man, o_cnt = oracle.compact(snap, chunk, o_mask, o_dig)
+    ref_t = torch.from_numpy(o_ref.view(np.int64)).cuda()
+    for flip, lo, hi in ((n // 2, 0.4, 0.6), (n - 1, 0.0, 0.01), (0, 0.99, 1.01)):
+        h = o_mask.copy()
+        h[flip] ^= 1
+        out = run_snapshot(dev, ref_t, torch.from_numpy(h).cuda(), o_st.size, o_man.size)
+        dig, mask, staging, manifest, cnt, misses, stats = out
+        assert misses == 1 and cnt == o_cnt
+        assert np.array_equal(staging.cpu().numpy()[:o_st.size], o_st)
+        assert np.array_equal(ck.manifest_to_numpy(manifest, o_man.size), o_man)
+        assert lo * o_man.size <= stats["regathered_chunks"] <= hi * o_man.size, (flip, stats)
 
 
 @pytest.mark.parametrize("hint_kind", ["exact", "ones", "zeros"])

@@ -12,7 +12,7 @@ from paper_2202_07848_amd import binding as ck
 pytestmark = pytest.mark.gpu
 
 
-def make_state(seed, sizes, chunk, flip_every):
+def make_state(seed, sizes, chunk, flip_every, split):
     """Reference digests, a snapshot state that differs from the reference in some chunks, and
     an exact hint -- all produced by the existing entry points."""
     g = torch.Generator(device="cuda")
@@ -24,6 +24,7 @@ def make_state(seed, sizes, chunk, flip_every):
         if b.numel() and i % 2 == 0:
             b[::flip_every] ^= 0x5A
     p_ref, plan = ck.Plan(ref_bufs, chunk), ck.Plan(bufs, chunk)
+    plan.split_threshold = split
     n = plan.nchunks
     ref = torch.zeros(n, dtype=torch.int64, device="cuda")
     dig = torch.zeros(n, dtype=torch.int64, device="cuda")
@@ -61,32 +62,27 @@ def both_ways(plan, ref, hint, ndirty, staged):
 
 @pytest.mark.parametrize("split", [0, 2**64 - 1], ids=["two_launches", "one_launch"])
 def test_static_snapshot_equals_snapshot_twice_in_a_row(split):
-    before = ck.snapshot_split_threshold()
-    ck.snapshot_set_split_threshold(split)
-    try:
-        big = [3 << 20, 1 << 20, 4096 * 37 + 123, 0, 65536, 17, 2 << 20, 700_001]
-        small = [4096 * 5 + 1, 300_000, 31]
-        plan1, bufs1, ref1, hint1, nd1, st1 = make_state(11, big, 4096, 40_009)
-        plan2, bufs2, ref2, hint2, nd2, st2 = make_state(12, small, 4096, 9_001)
-        assert nd1 > nd2 > 0 and plan1.nchunks > plan2.nchunks
-        r1 = both_ways(plan1, ref1, hint1, nd1, st1)        # first call: exact hint
-        c = r1["counts"].cpu().numpy().view(np.uint64)
-        assert (int(c[0]), int(c[1]), int(c[2])) == (nd1, st1, 0) and int(r1["misses"]) == 0
-        r2 = both_ways(plan2, ref2, hint2, nd2, st2)        # second call: smaller input
-        c = r2["counts"].cpu().numpy().view(np.uint64)
-        assert (int(c[0]), int(c[1]), int(c[2])) == (nd2, st2, 0) and int(r2["misses"]) == 0
-        # a wrong hint (gather path), no hint, and no reference, each after the other
-        wrong = hint2.clone()
-        wrong[plan2.nchunks // 2] ^= 1
-        r3 = both_ways(plan2, ref2, wrong, nd2, st2)
-        assert int(r3["misses"]) == 1
-        assert torch.equal(r3["staging"][:st2], r2["staging"][:st2])
-        both_ways(plan2, ref2, None, nd2, st2)
-        both_ways(plan2, None, None, plan2.nchunks, plan2.nbytes + 16 * plan2.nchunks)
-        # capacity limits are honoured the same way
-        both_ways(plan1, ref1, hint1, nd1 // 2, st1 // 3)
-    finally:
-        ck.snapshot_set_split_threshold(before)
+    big = [3 << 20, 1 << 20, 4096 * 37 + 123, 0, 65536, 17, 2 << 20, 700_001]
+    small = [4096 * 5 + 1, 300_000, 31]
+    plan1, bufs1, ref1, hint1, nd1, st1 = make_state(11, big, 4096, 40_009, split)
+    plan2, bufs2, ref2, hint2, nd2, st2 = make_state(12, small, 4096, 9_001, split)
+    assert nd1 > nd2 > 0 and plan1.nchunks > plan2.nchunks
+    r1 = both_ways(plan1, ref1, hint1, nd1, st1)        # first call: exact hint
+    c = r1["counts"].cpu().numpy().view(np.uint64)
+    assert (int(c[0]), int(c[1]), int(c[2])) == (nd1, st1, 0) and int(r1["misses"]) == 0
+    r2 = both_ways(plan2, ref2, hint2, nd2, st2)        # second call: smaller input
+    c = r2["counts"].cpu().numpy().view(np.uint64)
+    assert (int(c[0]), int(c[1]), int(c[2])) == (nd2, st2, 0) and int(r2["misses"]) == 0
+    # a wrong hint (gather path), no hint, and no reference, each after the other
+    wrong = hint2.clone()
+    wrong[plan2.nchunks // 2] ^= 1
+    r3 = both_ways(plan2, ref2, wrong, nd2, st2)
+    assert int(r3["misses"]) == 1
+    assert torch.equal(r3["staging"][:st2], r2["staging"][:st2])
+    both_ways(plan2, ref2, None, nd2, st2)
+    both_ways(plan2, None, None, plan2.nchunks, plan2.nbytes + 16 * plan2.nchunks)
+    # capacity limits are honoured the same way
+    both_ways(plan1, ref1, hint1, nd1 // 2, st1 // 3)
 
 
 def test_static_snapshot_refuses_plans_above_its_limit():
