@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--separate", action="store_true",
                     help="time ckpt_fingerprint, ckpt_diff and ckpt_compact as three calls instead "
                          "of the fused ckpt_snapshot (hint = the previous step's mask)")
+    ap.add_argument("--hint-cases", action="store_true",
+                    help="time ckpt_snapshot with an exact hint, no hint and a hint with one wrong "
+                         "chunk also when the main path is the three calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=8.0)
     ap.add_argument("--match", action="store_true",
@@ -69,12 +72,16 @@ def parse_args():
 
 
 class Replica:
+    plan_create_ms = []        # one entry per plan built (host geometry + table upload)
+
     def __init__(self, w, arena, offs, ck):
         self.arena = arena
         base = arena.data_ptr()
         self.desc = [(base + int(o), b.nbytes) for o, b in zip(offs, w.bufs)]
         self.offs = offs
+        t0 = time.perf_counter()
         self.plan = ck.Plan(self.desc, w.chunk)
+        Replica.plan_create_ms.append((time.perf_counter() - t0) * 1e3)
 
 
 def read_traffic_note(kernel: str, workload: str):
@@ -84,10 +91,10 @@ def read_traffic_note(kernel: str, workload: str):
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                return float(line.split(":", 1)[1]), os.path.relpath(path, ROOT)
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def cpu_baseline(w, rep_ref, rep_new, sample_bytes, torch):
@@ -121,7 +128,8 @@ def cpu_baseline(w, rep_ref, rep_new, sample_bytes, torch):
     dt = time.perf_counter() - t0
     hashed = sum(b.size for b in h_ref) + nbytes
     return {
-        "value": hashed / dt / 1e9, "unit": "GB/s of device state (fingerprint+diff+compact)",
+        "value": hashed / dt / 1e9,
+        "unit": "GB/s of device state (fingerprint on all threads + diff + compact on one thread)",
         "cores": threads, "kind": "oracle",
         "sample": f"every {stride}th buffer of both replicas: {len(idx)} buffers, "
                   f"{hashed / 2**30:.2f} GiB fingerprinted, {cnt2['staged_bytes'] / 2**30:.2f} GiB "
@@ -281,6 +289,57 @@ def content_addressed_leg(w, t0, t1, ref, ck, torch, np, steps):
     }
 
 
+def hint_cases_leg(w, rep, ref, staged, ndirty, ck, torch, np, args):
+    """ckpt_snapshot of one replica under the three hints a caller can have, each timed on its
+    own with events around the call: (i) the exact hint (the steady state of a context switch),
+    (ii) no hint (the first snapshot: plain pass + gather), (iii) the exact hint with one wrong
+    chunk in the middle (the pass, then a gather of the staged chunks behind the miss).
+    Fractions: `of_peak_on_moved_bytes` counts the bytes each case really moves,
+    `of_peak_vs_two_pass` the (1 + 2d) S a fingerprint followed by a gather has to move."""
+    dev = rep.arena.device
+    n, S = w.nchunks, w.nbytes
+    dig = torch.zeros(n, dtype=torch.int64, device=dev)
+    mask = torch.zeros(n, dtype=torch.uint8, device=dev)
+    cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+    miss = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws = torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    staging = torch.empty(max(16, staged), dtype=torch.uint8, device=dev)
+    manifest = torch.empty(max(1, ndirty) * 32, dtype=torch.uint8, device=dev)
+    ck.fingerprint(rep.plan, dig)
+    ck.diff(rep.plan, dig, ref, mask, cnt)
+    exact = mask.clone()
+    wrong = exact.clone()
+    wrong[n // 2] ^= 1
+    ev = torch.cuda.Event
+    out = {}
+    for name, hint in (("exact_hint", exact), ("no_hint", None), ("one_wrong_chunk_mid", wrong)):
+        ms = []
+        for it in range(args.warmup + args.steps):
+            e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+            e0.record()
+            ck.snapshot(rep.plan, ref, hint, dig, mask, staging, manifest, cnt, miss,
+                        ws if hint is not None else None, staging_cap=staged, manifest_cap=ndirty)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                ms.append(e0.elapsed_time(e1))
+        c = cnt.cpu().numpy().view(np.uint64)
+        assert (int(c[0]), int(c[1]), int(c[2])) == (ndirty, staged, 0), (name, c)
+        stats = ck.snapshot_stats(ws, n) if hint is not None else \
+            {"hint_misses": 0, "regathered_chunks": ndirty}
+        regathered_bytes = staged * stats["regathered_chunks"] / max(1, ndirty)
+        moved = S + (staged if hint is not None else 0) + 2 * regathered_bytes
+        mean = float(np.mean(ms))
+        out[name] = {
+            "snapshot_ms_mean": round(mean, 4), "snapshot_ms_min": round(min(ms), 4),
+            "hint_misses": stats["hint_misses"], "regathered_chunks": stats["regathered_chunks"],
+            "bytes_moved": int(moved),
+            "of_peak_on_moved_bytes": round(moved / mean / 1e6 / HBM_PEAK_GBPS, 4),
+            "of_peak_vs_two_pass": round((S + 2 * staged) / mean / 1e6 / HBM_PEAK_GBPS, 4),
+        }
+    return out
+
+
 def phase_names(d, fused):
     """With the fused call there is one snapshot phase instead of three."""
     if not fused:
@@ -308,6 +367,7 @@ def main():
     w = wl.config(args.config, args.shrink)
     t_gen = time.perf_counter()
 
+    Replica.plan_create_ms.clear()
     replicas = []
     if w.nreplicas >= 2:
         for r in range(w.nreplicas):
@@ -362,30 +422,33 @@ def main():
     spaces = [torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device=dev)
               for _ in pairs] if fused else None
 
-    def step(timed):
-        marks = [ev(enable_timing=True)]
-        marks[0].record()
+    nmarks = 2 + 4 * len(pairs)
+
+    def step(marks):
+        """One step; marks: pre-created events, recorded in order (a phase boundary each)."""
+        it = iter(marks)
+        next(it).record()
         if w.nreplicas >= 2:
             ck.fingerprint(pairs[0][0].plan, ref)
-        marks.append(ev(enable_timing=True)); marks[-1].record()
+        next(it).record()
         for i, (a, b) in enumerate(pairs):
             if fused:
                 # one call; the mask of the previous step (same buffer) is the hint
                 ck.snapshot(b.plan, ref, masks[i], digs[i], masks[i], stagings[i], manifests[i],
                             counts[i], misses[i], spaces[i], staging_cap=staged[i],
                             manifest_cap=ndirty[i])
-                marks.append(ev(enable_timing=True)); marks[-1].record()
-                marks.append(marks[-1])
+                next(it).record()
+                next(it).record()
             else:
                 ck.fingerprint(b.plan, digs[i])
-                marks.append(ev(enable_timing=True)); marks[-1].record()
+                next(it).record()
                 ck.diff(b.plan, digs[i], ref, masks[i], counts[i])
-                marks.append(ev(enable_timing=True)); marks[-1].record()
+                next(it).record()
                 ck.compact(b.plan, masks[i], digs[i], stagings[i], manifests[i], counts[i],
                            staging_cap=staged[i], manifest_cap=ndirty[i])
-            marks.append(ev(enable_timing=True)); marks[-1].record()
+            next(it).record()
             ck.restore(b.plan, stagings[i], staged[i], manifests[i], ndirty[i])
-            marks.append(ev(enable_timing=True)); marks[-1].record()
+            next(it).record()
         return marks
 
     def step_calls():          # the measured part of a step, no events: for graph capture
@@ -406,22 +469,31 @@ def main():
         for i, (a, b) in enumerate(pairs):
             ck.restore(b.plan, stagings[i], staged[i], manifests[i], ndirty[i])
 
-    for _ in range(args.warmup):
-        step(False)
+    # events exist (and have been recorded once, in the warm-up) before the timed region, and the
+    # collector stays out of it: a host hiccup between two enqueues would be timed as GPU work
+    import gc
+    all_marks = [[ev(enable_timing=True) for _ in range(nmarks)] for _ in range(args.steps)]
+    for i in range(max(args.warmup, 1)):
+        step(all_marks[i % args.steps])
+    for marks in all_marks[max(args.warmup, 1):]:
+        for e in marks:
+            e.record()
     torch.cuda.synchronize()
-    all_marks = []
+    gc.collect()
+    gc.disable()
     wall0 = time.perf_counter()
-    for _ in range(args.steps):
-        all_marks.append(step(True))
+    for marks in all_marks:
+        step(marks)
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
+    gc.enable()
 
     ph = {"fingerprint_ref": [], "fingerprint": [], "diff": [], "compact": [], "restore": []}
     for marks in all_marks:
         ph["fingerprint_ref"].append(marks[0].elapsed_time(marks[1]))
         fp = df = cp = rs = 0.0
         for i in range(len(pairs)):
-            m = marks[1 + 4 * i: 6 + 4 * i]
+            m = marks[1 + 4 * i: 6 + 4 * i]      # end of the previous phase + this pair's four
             fp += m[0].elapsed_time(m[1]); df += m[1].elapsed_time(m[2])
             cp += m[2].elapsed_time(m[3]); rs += m[3].elapsed_time(m[4])
         ph["fingerprint"].append(fp); ph["diff"].append(df)
@@ -432,6 +504,7 @@ def main():
         ph["compact"] = [0.0] * len(ph["compact"])
     mean = {k: float(np.mean(v)) for k, v in ph.items()}
     med = {k: float(np.median(v)) for k, v in ph.items()}
+    low = {k: float(np.min(v)) for k, v in ph.items()}
 
     for cnt, k, s in zip(counts, ndirty, staged):
         c = cnt.cpu().numpy().view(np.uint64)
@@ -443,28 +516,33 @@ def main():
     dirty_bytes = sum(staged)
     t_fdc = (mean["fingerprint_ref"] + mean["fingerprint"] + mean["diff"] + mean["compact"]) / 1e3
     value = bytes_fp / t_fdc / 1e9
-    moved = bytes_fp + 2 * dirty_bytes
+    # what a fingerprint followed by a gather has to move, (1 + 2d) S per snapshot, and what the
+    # path really moves: the fused pass reads S and writes d S, nothing twice
+    two_pass_bytes = bytes_fp + 2 * dirty_bytes
+    moved_path = bytes_fp + (dirty_bytes if fused else 2 * dirty_bytes)
     workload = f"config{w.config}_{w.name}"
     if fused:
         # dominant kernel: the fused fingerprint + stage pass, which the library runs as two
-        # launches (k_fingerprint<1>: the groups that stage chunks, k_fingerprint<2>: the rest);
-        # together they must read S and write d*S.  Their time is the snapshot phase minus the
-        # small diff / scan / manifest kernels, which are not separable by events inside one
-        # call; they are microseconds (see profiles/).
-        kernel = "k_fingerprint<1>+k_fingerprint<2>"
+        # launches from 256 MiB of state (k_fingerprint<1>: the groups that stage chunks,
+        # k_fingerprint<2>: the rest) and as one below (k_fingerprint<3>).  Its time is the
+        # snapshot phase, which also holds the hint-offset, manifest and (idle) gather kernels:
+        # events cannot separate kernels inside one call, and those are microseconds (profiles/).
+        split = S >= pairs[0][1].plan.split_threshold
+        kernel = "k_fingerprint<1>+k_fingerprint<2>" if split else "k_fingerprint<3>"
         launches = len(pairs)
-        kernel_bytes = S + 2 * dirty_bytes / launches     # what fingerprint + compact must move
-        moved_bytes = S + dirty_bytes / launches          # what the single pass really moves
+        kernel_bytes = S + dirty_bytes / launches             # read S, write d S
+        two_pass_kernel_bytes = S + 2 * dirty_bytes / launches
         fp_launch_ms = mean["fingerprint"] / launches
     else:
         kernel = "k_fingerprint<0>"
         launches = fingerprinted if w.nreplicas >= 2 else 1
-        kernel_bytes = moved_bytes = S
+        kernel_bytes = two_pass_kernel_bytes = S
         fp_launch_ms = (mean["fingerprint_ref"] + mean["fingerprint"]) / launches
     achieved = kernel_bytes / (fp_launch_ms / 1e3) / 1e9
     notes = [read_traffic_note(k.replace("<", "_").replace(">", ""), workload)
              for k in kernel.split("+")]
-    traffic = None if any(x is None for x in notes) else sum(notes)
+    traffic = None if any(x[0] is None for x in notes) else sum(x[0] for x in notes)
+    traffic_source = None if traffic is None else [x[1] for x in notes]
 
     out = {
         "metric": "device-state GB/s (fingerprint+diff+compact) and % of MI355X HBM peak",
@@ -485,30 +563,52 @@ def main():
             "dirty_chunks": ndirty, "staged_bytes": staged,
             "dirty_fraction": round(dirty_bytes / (S * len(pairs)), 4),
             "shrink": args.shrink,
-            "path": "fused ckpt_snapshot, hint = previous mask" if fused else
+            "path": "fused ckpt_snapshot, hint = previous mask (exact every step)" if fused else
                     "ckpt_fingerprint + ckpt_diff + ckpt_compact (three calls)",
         },
-        "hbm_frac_fp_diff_compact": round(moved / t_fdc / 1e9 / HBM_PEAK_GBPS, 4),
-        "bytes_moved_algorithmic": moved,
+        # fraction of the 8 TB/s peak over fingerprint + diff + compact: on the bytes the path
+        # really moves, and on the (1 + 2d) S of a fingerprint followed by a gather (equal
+        # for the three calls; the fused pass moves less, so its second figure is an
+        # effective rate, not a bandwidth)
+        "hbm_frac_fp_diff_compact": round(moved_path / t_fdc / 1e9 / HBM_PEAK_GBPS, 4),
+        "effective_hbm_frac_vs_two_pass": round(two_pass_bytes / t_fdc / 1e9 / HBM_PEAK_GBPS, 4),
+        "bytes_moved": moved_path,
+        "bytes_moved_two_pass": two_pass_bytes,
         # XXH64 costs two 64-bit multiplies per 8 input bytes; the rate the pass achieves, to set
         # beside the arithmetic-only ceiling that --calibrate measures
         "xxh64_u64_mul_per_s": round(bytes_fp / 4 / t_fdc, 0),
-        "phases_ms_mean": phase_names({k: round(v, 3) for k, v in mean.items()}, fused),
-        "phases_ms_median": phase_names({k: round(v, 3) for k, v in med.items()}, fused),
+        "phases_ms_mean": phase_names({k: round(v, 4) for k, v in mean.items()}, fused),
+        "phases_ms_median": phase_names({k: round(v, 4) for k, v in med.items()}, fused),
+        "phases_ms_min": phase_names({k: round(v, 4) for k, v in low.items()}, fused),
         "restore_GBps_read_plus_write": round(2 * dirty_bytes / (mean["restore"] / 1e3) / 1e9, 1)
         if dirty_bytes else None,
         "compact_GBps_read_plus_write": round(2 * dirty_bytes / (mean["compact"] / 1e3) / 1e9, 1)
         if dirty_bytes and not fused else None,
+        # set-up, outside the timed region: data generation, and plan creation on its own
+        # (host chunk geometry + one table upload per plan; it matters for 100 000 buffers)
         "setup_s": round(t_gen, 1),
+        "plan_create_ms": {"per_plan_mean": round(float(np.mean(Replica.plan_create_ms)), 3),
+                           "per_plan_min": round(float(np.min(Replica.plan_create_ms)), 3),
+                           "plans": len(Replica.plan_create_ms), "buffers_per_plan": len(w.bufs)},
         "roofline": {
             "kernel": kernel, "bound": "hbm", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": traffic,
-            "algorithmic_bytes_per_launch": int(kernel_bytes), "launch_ms": round(fp_launch_ms, 3),
-            "bytes_moved_per_launch": int(moved_bytes),
-            "achieved_on_moved_bytes": round(moved_bytes / (fp_launch_ms / 1e3) / 1e9, 1),
+            "traffic": traffic, "traffic_source": traffic_source,
+            "algorithmic_bytes_per_launch": int(kernel_bytes), "launch_ms": round(fp_launch_ms, 4),
+            "effective_frac_vs_two_pass": round(two_pass_kernel_bytes / (fp_launch_ms / 1e3) / 1e9
+                                                / HBM_PEAK_GBPS, 4),
         },
     }
+    if S < (1 << 30):
+        # a state this small is bound by the chain of dependent kernels, not by bandwidth
+        # (64 MiB also sits in the 256 MB last-level cache): report it as latency
+        out["latency_us"] = {k: round(v * 1e3, 1) for k, v in
+                             phase_names({k: v for k, v in low.items()}, fused).items()}
+        out["latency_us"]["basis"] = "min over timed steps, per phase of one step"
+
+    if fused or args.hint_cases:
+        out["hint_cases"] = hint_cases_leg(w, pairs[0][1], ref, staged[0], ndirty[0], ck, torch, np,
+                                           args)
 
     if args.graph:
         out["hip_graph"] = graph_leg(step_calls, restore_calls, bytes_fp, args, torch)

@@ -221,7 +221,7 @@ uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks);
 /* Diagnostics of a hinted ckpt_snapshot, readable once the stream is synchronised:
  * at this byte offset of d_workspace sit four uint64 -- [0] the hint misses (as
  * *d_hint_misses), [1] and [2] unspecified, [3] the number of chunks the
- * corrective gather copied after the pass (0 with an exact hint; with one wrong
+ * corrective gather copies after the pass (0 with an exact hint; with one wrong
  * chunk, the staged chunks behind it). */
 uint64_t ckpt_snapshot_stats_offset(uint64_t nchunks);
 int ckpt_snapshot(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_t n_ref,

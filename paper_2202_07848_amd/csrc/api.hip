@@ -1,6 +1,7 @@
 // C ABI of libckpt.so: argument checks, the plan object, kernel launches.
 // Semantics and citations are in include/ckpt.h.
 #include <algorithm>
+#include <cstring>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -223,26 +224,35 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
     return e == hipErrorOutOfMemory ? CKPT_ERR_NOMEM : CKPT_ERR_DEVICE;
   }
 
+  // one host image of all tables, one copy to the device
   char *base = static_cast<char *>(plan->d_tables);
-  auto upload = [&](size_t off, const void *src, size_t n) -> hipError_t {
-    if (n == 0) return hipSuccess;
-    return hipMemcpy(base + off, src, n, hipMemcpyHostToDevice);
+  std::vector<char> image;
+  try {
+    image.assign(bytes, 0);          // zeros: the spare block, and the gaps between tables
+  } catch (const std::bad_alloc &) {
+    (void)hipFree(plan->d_tables);
+    (void)hipFree(plan->d_blocksums);
+    delete plan;
+    return CKPT_ERR_NOMEM;
+  }
+  auto put = [&](size_t off, const void *src, size_t n) {
+    if (n != 0) std::memcpy(image.data() + off, src, n);
   };
-  e = upload(o_dptr, dense_ptr.data(), 8 * nb);
-  if (e == hipSuccess) e = upload(o_dnb, dense_nbytes.data(), 8 * nb);
-  if (e == hipSuccess) e = upload(o_dbase, dense_base.data(), 8 * (nb + 1));
-  if (e == hipSuccess) e = upload(o_dorig, dense_orig.data(), 4 * nb);
-  if (e == hipSuccess) e = upload(o_gfirst, group_first.data(), 4 * group_first.size());
-  if (e == hipSuccess) e = upload(o_lptr, list_ptr.data(), 8 * (size_t)nbufs);
-  if (e == hipSuccess) e = upload(o_lnb, list_nbytes.data(), 8 * (size_t)nbufs);
-  if (e == hipSuccess) e = upload(o_fptr, full_ptr.data(), 8 * nf);
-  if (e == hipSuccess) e = upload(o_fc0, full_chunk0.data(), 8 * nf);
-  if (e == hipSuccess) e = upload(o_fbase, full_base.data(), 8 * (nf + 1));
-  if (e == hipSuccess) e = upload(o_fgf, full_group_first.data(), 4 * full_group_first.size());
-  if (e == hipSuccess) e = upload(o_sptr, short_ptr.data(), 8 * ns);
-  if (e == hipSuccess) e = upload(o_sck, short_chunk.data(), 8 * ns);
-  if (e == hipSuccess) e = upload(o_slen, short_len.data(), 4 * ns);
-  if (e == hipSuccess) e = hipMemset(base + o_spare, 0, 256);
+  put(o_dptr, dense_ptr.data(), 8 * nb);
+  put(o_dnb, dense_nbytes.data(), 8 * nb);
+  put(o_dbase, dense_base.data(), 8 * (nb + 1));
+  put(o_dorig, dense_orig.data(), 4 * nb);
+  put(o_gfirst, group_first.data(), 4 * group_first.size());
+  put(o_lptr, list_ptr.data(), 8 * (size_t)nbufs);
+  put(o_lnb, list_nbytes.data(), 8 * (size_t)nbufs);
+  put(o_fptr, full_ptr.data(), 8 * nf);
+  put(o_fc0, full_chunk0.data(), 8 * nf);
+  put(o_fbase, full_base.data(), 8 * (nf + 1));
+  put(o_fgf, full_group_first.data(), 4 * full_group_first.size());
+  put(o_sptr, short_ptr.data(), 8 * ns);
+  put(o_sck, short_chunk.data(), 8 * ns);
+  put(o_slen, short_len.data(), 4 * ns);
+  e = hipMemcpy(base, image.data(), bytes, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)hipFree(plan->d_tables);
     (void)hipFree(plan->d_blocksums);
@@ -352,7 +362,7 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
                                            nullptr, s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
-                            nullptr, nullptr, nullptr, s);
+                            nullptr, nullptr, s);
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
@@ -412,8 +422,7 @@ static int snapshot_impl(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_
                                   d_blocksums, d_counts, hp, d_hint_misses, s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
-                            hp ? h.misses : nullptr, hp ? h.need : nullptr,
-                            hp ? h.misses + 3 : nullptr, s);
+                            hp ? h.misses : nullptr, hp ? h.need : nullptr, s);
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

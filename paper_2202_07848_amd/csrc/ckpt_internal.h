@@ -68,6 +68,31 @@ __device__ __forceinline__ ChunkRef locate_chunk(const PlanDev &p, uint64_t k) {
   return r;
 }
 
+// The same for n consecutive chunks k0 .. k0+n-1 (all < N), for small n: one walk from the
+// group table instead of n, since a chain of dependent loads per chunk is what the scan kernels
+// spend their time on.  From one chunk to the next the row advances by at most one (every row
+// owns at least one chunk).
+__device__ __forceinline__ void locate_run(const PlanDev &p, uint64_t k0, int n, ChunkRef *refs) {
+  if (n <= 0) return;
+  uint32_t row = p.group_first[k0 >> GROUP_LOG2];
+  uint64_t next = p.dense_base[row + 1];
+  while (k0 >= next) next = p.dense_base[++row + 1];          // ends: dense_base[nb] = N > k0
+  uint64_t base = p.dense_base[row], nbytes = p.dense_nbytes[row];
+  const uint64_t c = 1ull << p.chunk_log2;
+  for (int i = 0; i < n; ++i) {
+    const uint64_t k = k0 + i;
+    if (k >= next) {
+      base = next;
+      next = p.dense_base[++row + 1];
+      nbytes = p.dense_nbytes[row];
+    }
+    refs[i].row = row;
+    refs[i].off = (k - base) << p.chunk_log2;
+    const uint64_t rem = nbytes - refs[i].off;
+    refs[i].len = (uint32_t)(rem < c ? rem : c);
+  }
+}
+
 __device__ __forceinline__ uint64_t pad16(uint64_t x) { return (x + 15) & ~15ull; }
 
 // Scan geometry: one workgroup of SCAN_THREADS threads covers SCAN_BLOCK
@@ -113,12 +138,10 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
                                ckpt_counts_t *d_counts, const HintState *h, uint64_t *d_misses_out,
                                hipStream_t s);
 // d_only_if_nonzero (may be null): the kernel does nothing when it points to 0;  d_need (may be
-// null): entries e with d_need[e] == 0 are skipped;  d_copied (may be null): incremented once
-// per entry copied.
+// null): entries e with d_need[e] == 0 are skipped.
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
-                         const uint64_t *d_only_if_nonzero, const uint8_t *d_need,
-                         uint64_t *d_copied, hipStream_t s);
+                         const uint64_t *d_only_if_nonzero, const uint8_t *d_need, hipStream_t s);
 // The fused pass: fingerprint + mask + staging of the hinted chunks.  d_list: one uint32, d_flags:
 // one byte per fingerprint group; d_list_counts: two uint64, zero on entry; split: staging groups
 // and the rest in two launches (pays off from a few hundred MB of state).
@@ -130,7 +153,7 @@ hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, con
 uint64_t fingerprint_groups(const PlanDev &p);
 // 64-bit words at the head of the fused snapshot's counter block, cleared by
 // launch_hint_offsets: [0] hint misses, [1..3] scratch counts of the hint (word 3 ends up zero and
-// then counts the chunks the corrective gather copies), [4..5] group list lengths.
+// then receives the number of chunks the corrective gather has to copy), [4..5] group list lengths.
 constexpr int SNAPSHOT_COUNTERS = 6;
 hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, const HintState &h,
                                uint64_t *d_scratch, ckpt_counts_t *d_tmp_counts,

@@ -34,8 +34,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_move(PlanDev p,
                                                        uint64_t staging_limit,
                                                        unsigned long long *__restrict__ rejected,
                                                        const unsigned long long *only_if_nonzero,
-                                                       const uint8_t *__restrict__ need,
-                                                       unsigned long long *__restrict__ copied) {
+                                                       const uint8_t *__restrict__ need) {
   // the fused snapshot has already staged everything when its hint was exact; when it was not,
   // `need` marks the entries that are not yet where they belong
   if (only_if_nonzero != nullptr && *only_if_nonzero == 0) return;
@@ -75,7 +74,6 @@ __global__ __launch_bounds__(COPY_THREADS) void k_move(PlanDev p,
       continue;
     }
 
-    if (copied != nullptr && piece == 0 && lane == 0) atomicAdd(copied, 1ull);
     uint8_t *buf = reinterpret_cast<uint8_t *>(p.list_ptr[ent.buf]) + ent.buf_off;
     uint8_t *stg = staging + ent.stage_off;
     const uint8_t *src = GATHER ? buf : stg;
@@ -172,16 +170,14 @@ inline uint32_t move_groups(const PlanDev &p, uint64_t max_entries) {
 
 hipError_t launch_gather(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, void *d_staging, uint64_t staging_cap,
-                         const uint64_t *d_only_if_nonzero, const uint8_t *d_need,
-                         uint64_t *d_copied, hipStream_t s) {
+                         const uint64_t *d_only_if_nonzero, const uint8_t *d_need, hipStream_t s) {
   const uint64_t most = p.nchunks < manifest_cap ? p.nchunks : manifest_cap;
   const uint32_t groups = move_groups(p, most);
   if (groups == 0) return hipSuccess;
   hipLaunchKernelGGL(k_move<true>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, most,
                      d_counts, reinterpret_cast<uint8_t *>(d_staging), staging_cap,
                      (unsigned long long *)nullptr,
-                     reinterpret_cast<const unsigned long long *>(d_only_if_nonzero), d_need,
-                     reinterpret_cast<unsigned long long *>(d_copied));
+                     reinterpret_cast<const unsigned long long *>(d_only_if_nonzero), d_need);
   return hipGetLastError();
 }
 
@@ -197,8 +193,7 @@ hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint
                      d_counts,
                      const_cast<uint8_t *>(reinterpret_cast<const uint8_t *>(d_staging)),
                      staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected),
-                     (const unsigned long long *)nullptr, (const uint8_t *)nullptr,
-                     (unsigned long long *)nullptr);
+                     (const unsigned long long *)nullptr, (const uint8_t *)nullptr);
   return hipGetLastError();
 }
 

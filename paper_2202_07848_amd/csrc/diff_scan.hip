@@ -66,15 +66,15 @@ __device__ __forceinline__ uint64_t thread_first_chunk() {
   return (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
 }
 
+// Pair of the marked chunks among a thread's n consecutive ones; refs receives all n.
 __device__ __forceinline__ Pair sum_marked(const PlanDev &p, uint64_t k0, const uint8_t *m, int n,
                                            ChunkRef *refs) {
+  locate_run(p, k0, n, refs);
   Pair s = {0, 0};
   for (int i = 0; i < n; ++i) {
     if (m[i]) {
-      ChunkRef r = locate_chunk(p, k0 + i);
-      if (refs) refs[i] = r;
       s.cnt += 1;
-      s.bytes += pad16(r.len);
+      s.bytes += pad16(refs[i].len);
     }
   }
   return s;
@@ -168,7 +168,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t
       n = i + 1;
     }
   }
-  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  ChunkRef refs[SCAN_PER_THREAD];
+  Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
   finish_pairs(scratch, total, false, counts, nullptr, nullptr);
 }
@@ -198,7 +199,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
       n = i + 1;
     }
   }
-  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  ChunkRef refs[SCAN_PER_THREAD];
+  Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
   finish_pairs(scratch, total, false, counts, nullptr, nullptr);
 }
@@ -233,21 +235,25 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(
     for (int o = 32; o > 0; o >>= 1) bad += __shfl_down(bad, o, 64);
     if ((threadIdx.x & 63) == 0 && bad) atomicAdd(misses, (unsigned long long)bad);
   }
-  Pair mine = sum_marked(p, k0, m, n, nullptr), total;
+  ChunkRef refs[SCAN_PER_THREAD];
+  Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
   finish_pairs(scratch, total, true, counts, misses, misses_out);
 }
 
-// Sum over the workgroup of one value per thread, returned in every thread.
-__device__ uint64_t block_sum(uint64_t v) {
-  __shared__ uint64_t s_part[SCAN_THREADS / 64];
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+// Sum over the workgroup of one pair per thread, returned in every thread.
+__device__ Pair block_sum(Pair v) {
+  __shared__ Pair s_part[SCAN_THREADS / 64];
+  for (int o = 32; o > 0; o >>= 1) {
+    v.cnt += __shfl_down(v.cnt, o, 64);
+    v.bytes += __shfl_down(v.bytes, o, 64);
+  }
   __syncthreads();
   if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = v;
   __syncthreads();
-  uint64_t all = 0;
+  Pair all = {0, 0};
 #pragma unroll
-  for (int w = 0; w < SCAN_THREADS / 64; ++w) all += s_part[w];
+  for (int w = 0; w < SCAN_THREADS / 64; ++w) all = all + s_part[w];
   return all;
 }
 
@@ -278,42 +284,51 @@ __device__ Pair pair_before(const PlanDev &p, const uint8_t *__restrict__ mask, 
     const uint64_t k = p.short_chunk[s];
     if (k < k0 && mask[k] != 0) lost += c - pad16(p.short_len[s]);
   }
-  Pair r;
-  r.cnt = block_sum(cnt);
-  r.bytes = r.cnt * c - block_sum(lost);
+  Pair r = block_sum(Pair{cnt, lost});
+  r.bytes = r.cnt * c - r.bytes;
   return r;
 }
 
 // What one workgroup of the one-kernel paths hands to the last one: marked
-// chunks, entries that missed a capacity and hint misses of its block (each at
-// most SCAN_BLOCK, 20 bits apiece) in one word, padded bytes in the other.
+// chunks, entries that missed a capacity, hint misses and entries left for the
+// gather in its block (each at most SCAN_BLOCK, 16 bits apiece) in one word,
+// padded bytes in the other.  misses (fused snapshot): word 0 receives the hint
+// misses, word 3 the entries left for the gather.
 __device__ void finish_small(uint64_t *scratch, Pair total, uint32_t missed, uint32_t bad,
-                             ckpt_counts_t *counts, unsigned long long *misses,
+                             uint32_t todo, ckpt_counts_t *counts, unsigned long long *misses,
                              unsigned long long *misses_out) {
   uint64_t *pairs = block_pairs(scratch);
-  const uint64_t all_missed = block_sum(missed), all_bad = block_sum(bad);
+  // the three small counts share one reduction: 16-bit fields, none can exceed SCAN_BLOCK
+  const uint64_t small =
+      block_sum(Pair{(uint64_t)missed | ((uint64_t)bad << 16) | ((uint64_t)todo << 32), 0}).cnt;
   if (threadIdx.x == 0) {
-    pairs[2 * (uint64_t)blockIdx.x] = total.cnt | (all_missed << 20) | (all_bad << 40);
+    pairs[2 * (uint64_t)blockIdx.x] = total.cnt | (small << 16);
     pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
   }
   if (arrived_last(scratch)) {
-    uint64_t cnt = 0, bytes = 0, over = 0, wrong = 0;
+    uint64_t cnt = 0, bytes = 0, over = 0, wrong = 0, left = 0;
     for (uint64_t b = threadIdx.x; b < gridDim.x; b += SCAN_THREADS) {
       const uint64_t w = pairs[2 * b];
-      cnt += w & 0xFFFFF;
-      over += (w >> 20) & 0xFFFFF;
-      wrong += w >> 40;
+      cnt += w & 0xFFFF;
+      over += (w >> 16) & 0xFFFF;
+      wrong += (w >> 32) & 0xFFFF;
+      left += w >> 48;
       bytes += pairs[2 * b + 1];
     }
-    cnt = block_sum(cnt);
-    bytes = block_sum(bytes);
-    over = block_sum(over);
-    wrong = block_sum(wrong);
+    const Pair a = block_sum(Pair{cnt, bytes}), b = block_sum(Pair{over, wrong});
+    cnt = a.cnt;
+    bytes = a.bytes;
+    over = b.cnt;
+    wrong = b.bytes;
+    left = block_sum(Pair{left, 0}).cnt;
     if (threadIdx.x == 0) {
       counts->ndirty = cnt;
       counts->staged_bytes = bytes;
       counts->overflow = over;
-      if (misses != nullptr) *misses = wrong;
+      if (misses != nullptr) {
+        misses[0] = wrong;
+        misses[3] = left;
+      }
       if (misses_out != nullptr) *misses_out = wrong;
     }
     reset_ticket(scratch);
@@ -339,14 +354,24 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
     unsigned long long *misses_out) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
+  uint64_t d[SCAN_PER_THREAD], ho[SCAN_PER_THREAD];
+  bool hinted[SCAN_PER_THREAD];
   ChunkRef refs[SCAN_PER_THREAD];
   int n = 0;
   uint32_t bad = 0;
   for (int i = 0; i < SCAN_PER_THREAD; ++i) {
     const uint64_t k = k0 + i;
+    hinted[i] = false;
+    ho[i] = 0;
     if (k < p.nchunks) {
+      // everything the entries need is read up front: no load waits behind the scan
       m[i] = mask[k] != 0;
-      if (SMALL && hint != nullptr) bad += (hint[k] != 0) != (m[i] != 0);
+      d[i] = dig[k];
+      if (hint != nullptr) {          // hoff comes with hint
+        hinted[i] = hint[k] != 0;
+        ho[i] = hoff[k];
+        bad += hinted[i] != (m[i] != 0);
+      }
       n = i + 1;
     }
   }
@@ -360,7 +385,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
     before = {blockoff[2 * (uint64_t)blockIdx.x], blockoff[2 * (uint64_t)blockIdx.x + 1]};
   }
   pos = pos + before;
-  uint32_t missed = 0;
+  uint32_t missed = 0, todo = 0;
   for (int i = 0; i < n; ++i) {
     if (!m[i]) continue;
     const ChunkRef r = refs[i];
@@ -373,19 +398,27 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
       e.len = r.len;
       e.buf_off = r.off;
       e.stage_off = pos.bytes;
-      e.digest = dig[k0 + i];
+      e.digest = d[i];
       manifest[pos.cnt] = e;
-      if (need != nullptr)
-        need[pos.cnt] = !(fits_staging && hint[k0 + i] != 0 && hoff[k0 + i] == pos.bytes);
+      if (need != nullptr) {
+        const bool in_place = fits_staging && hinted[i] && ho[i] == pos.bytes;
+        need[pos.cnt] = !in_place;
+        todo += fits_staging && !in_place;
+      }
     }
     if (!fits_staging) ++missed;
     pos.cnt += 1;
     pos.bytes += padded;
   }
   if (SMALL) {
-    finish_small(scratch, total, missed, bad, counts, misses, misses_out);
-  } else if (missed) {
-    atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow), (unsigned long long)missed);
+    finish_small(scratch, total, missed, bad, todo, counts, misses, misses_out);
+  } else {
+    if (missed)
+      atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow), (unsigned long long)missed);
+    if (need != nullptr) {         // one atomic per wavefront that has something to report
+      for (int o = 32; o > 0; o >>= 1) todo += __shfl_down(todo, o, 64);
+      if ((threadIdx.x & 63) == 0 && todo) atomicAdd(misses + 3, (unsigned long long)todo);
+    }
   }
 }
 
@@ -544,7 +577,7 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
                        d_counts, (uint8_t *)nullptr, (ull *)nullptr, hint, misses, misses_out);
     hipLaunchKernelGGL(k_emit_manifest<false>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
                        d_dig, d_scratch, d_manifest, manifest_cap, staging_cap, d_counts, hint, hoff,
-                       need, (ull *)nullptr, (ull *)nullptr);
+                       need, misses, (ull *)nullptr);
   }
   return hipGetLastError();
 }
