@@ -61,6 +61,10 @@ def parse_args():
                     help="also swap the last replica's delta out to pinned host memory and back in "
                          "(ckpt_swap_out / ckpt_swap_in through a small device ring)")
     ap.add_argument("--swap-slice-mib", type=int, default=256)
+    ap.add_argument("--switch", action="store_true",
+                    help="config 4 only: also time whole context switches between four time-sliced "
+                         "ranks that share one device image (swap-out of the outgoing rank's delta "
+                         "to pinned host memory, swap-in of the incoming rank's, no host read)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in HIP graphs (snapshot part, restore part) and "
                          "time their replays: what a launch-bound small state gains")
@@ -338,6 +342,80 @@ def hint_cases_leg(w, rep, ref, staged, ndirty, ck, torch, np, args):
             "of_peak_vs_two_pass": round((S + 2 * staged) / mean / 1e6 / HBM_PEAK_GBPS, 4),
         }
     return out
+
+
+def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
+    """Round robin of four time-sliced ranks over ONE device image (paper sec. 5.1, 5.2.1, 6):
+    per switch the outgoing rank's delta against the shared base goes to pinned host memory
+    (checksum, compare, gather kernel writing over the host link) and the incoming rank's delta
+    comes back (counted restore reading from pinned host memory); the next rank's first kernel
+    waits on another stream behind one event; the host reads nothing.  Ranks = replicas 1..3
+    and a fourth generated here; base = replica 0 (the state all ranks share)."""
+    from paper_2202_07848_amd.switching import TimeSlicedRanks
+
+    dev = replicas[0].arena.device
+    nranks = 4
+    S, n = w.nbytes, w.nchunks
+    cap_bytes, cap_entries = w.distinct_bytes, w.distinct_chunks
+    # the image starts as a copy of rank 0 (= replica 1); the library sees only this arena
+    image = replicas[1].arena.clone()
+    offs = replicas[1].offs
+    plan = ck.Plan([(image.data_ptr() + int(o), b.nbytes) for o, b in zip(offs, w.bufs)], w.chunk)
+    sw = TimeSlicedRanks(plan, ref, nranks, cap_bytes, cap_entries, dev)
+    states = [replicas[1].arena, replicas[2].arena, replicas[3].arena]
+    extra, _ = wl.torch_replica(w, 4, dev, shared_from=replicas[0].arena)
+    states.append(extra)
+    # every rank has been resident once: its delta is in its host area
+    for r in range(1, nranks):
+        image.copy_(states[r])
+        sw.swap_out(r)
+    image.copy_(states[0])
+    torch.cuda.synchronize()
+    assert sw.same_dirty_set(list(range(1, nranks)))
+    side = torch.cuda.Stream()
+    token = torch.zeros(1, dtype=torch.int64, device=dev)
+    ev = torch.cuda.Event
+    ms, wall_ms = [], []
+    resident, ok = 0, True
+    rounds = 2
+    for step in range(rounds * nranks):
+        nxt = (resident + 1) % nranks
+        e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        sw.switch(resident, nxt)
+        e1.record()
+        with torch.cuda.stream(side):
+            side.wait_event(e1)
+            token.add_(1)                 # the incoming rank's first kernel
+            e2.record()
+        enqueue_ms = (time.perf_counter() - t0) * 1e3
+        torch.cuda.synchronize()
+        wall_ms.append((time.perf_counter() - t0) * 1e3)
+        ms.append((e0.elapsed_time(e1), enqueue_ms))
+        if step < nranks:                 # first rotation: the image is the incoming rank's state
+            ok = ok and bool(torch.equal(image, states[nxt]))
+        resident = nxt
+    assert ok and int(sw.rejected.item()) == 0 and int(token.item()) == rounds * nranks
+    c = sw.counts[0].cpu().numpy().view(np.uint64)
+    staged = int(c[1])
+    timed = [m[0] for m in ms[nranks:]]            # second rotation: everything warm
+    mean = float(np.mean(timed))
+    link_bytes = 2 * staged
+    return {
+        "workload": f"config{w.config}_{w.name}: {nranks} ranks round robin on one device image",
+        "state_bytes_per_rank": S, "delta_bytes_per_rank": staged,
+        "switch_ms_mean": round(mean, 2), "switch_ms_min": round(min(timed), 2),
+        "switch_wall_ms_mean": round(float(np.mean(wall_ms[nranks:])), 2),
+        "host_enqueue_ms_mean": round(float(np.mean([m[1] for m in ms[nranks:]])), 3),
+        "host_link_bytes_per_switch": link_bytes,
+        "host_link_GBps": round(link_bytes / mean / 1e6, 1),
+        "full_state_swap_ms_at_same_rate": round(2 * S / (link_bytes / mean) , 1),
+        "image_equals_incoming_rank_after_each_switch": ok,
+        "paper_context": "sec. 5.2: swapping 32 GB out and in without de-duplication costs 2-4 s "
+                         "per mini-batch on the paper's V100 hosts",
+    }
 
 
 def phase_names(d, fused):
@@ -648,6 +726,11 @@ def main():
         out["host_swap"] = host_swap_leg(w, pairs[-1][1], digs[-1], masks[-1], manifests[-1],
                                          stagings[-1], staged[-1], ndirty[-1], ck, torch,
                                          args.swap_slice_mib << 20)
+
+    if args.switch:
+        if w.nreplicas < 4:
+            raise SystemExit("--switch needs a configuration with four replicas (--config 4)")
+        out["context_switch"] = context_switch_leg(w, replicas, ref, ck, wl, torch, np, args)
 
     if args.match and w.nreplicas == 1:
         out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,

@@ -1,0 +1,126 @@
+"""Context switches between four time-sliced ranks that share one device-memory image
+(paper sec. 5.1, 5.2.1, 6), on a reduced 1.3 B x4 configuration: every switch swaps the
+outgoing rank's delta out to pinned host memory and the incoming rank's delta in, with no
+host read in between.  The oracle plays the same rotation on host arrays (checksum, compare,
+compact, restore); after every switch -- and after a whole rotation enqueued without any
+synchronisation -- the device image, the swapped-out bytes, the manifests and the counts must
+equal the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import DeviceBuffers
+from paper_2202_07848_amd import binding as ck
+from paper_2202_07848_amd import workloads as wl
+from paper_2202_07848_amd.switching import TimeSlicedRanks
+
+pytestmark = pytest.mark.gpu
+
+NRANKS = 4
+
+
+class OracleRanks:
+    """The rotation on the host, step by step with the oracle's functions."""
+
+    def __init__(self, w, base, first_state):
+        self.chunk = w.chunk
+        self.image = [b.copy() for b in first_state]
+        self.ref = oracle.fingerprint(base, w.chunk, 8)
+        self.staging = [None] * NRANKS
+        self.manifest = [None] * NRANKS
+        self.counts = [None] * NRANKS
+
+    def delta_of(self, state):
+        dig = oracle.fingerprint(state, self.chunk, 8)
+        mask, _ = oracle.diff(state, self.chunk, dig, self.ref)
+        return oracle.compact(state, self.chunk, mask, dig)
+
+    def switch(self, outgoing, incoming):
+        self.staging[outgoing], self.manifest[outgoing], self.counts[outgoing] = \
+            self.delta_of(self.image)
+        assert oracle.restore(self.image, self.chunk, self.staging[incoming],
+                              self.manifest[incoming]) == 0
+
+
+def run_a_mini_batch(w, rng, o, dev):
+    """The resident rank changes some of its own (per-rank) state: fresh bytes in a few chunks
+    of gradient and activation buffers, the same bytes on the host and on the device."""
+    own = [i for i, b in enumerate(w.bufs) if not b.shared and b.nbytes >= 64]
+    for i in rng.choice(own, size=6, replace=False).tolist():
+        n = w.bufs[i].nbytes
+        lo = int(rng.integers(0, n - 32))
+        hi = min(n, lo + int(rng.integers(1, 3 * w.chunk)))
+        fresh = rng.integers(0, 256, size=hi - lo, dtype=np.uint8)
+        o.image[i][lo:hi] = fresh
+        dev.arena[dev.offs[i] + lo:dev.offs[i] + hi] = torch.from_numpy(fresh).cuda()
+
+
+def check_rank_area(sw, o, r):
+    c = sw.counts[r].cpu().numpy().view(np.uint64)
+    want = o.counts[r]
+    assert (int(c[0]), int(c[1]), int(c[2])) == (want["ndirty"], want["staged_bytes"], 0)
+    assert np.array_equal(sw.host[r].numpy()[:want["staged_bytes"]], o.staging[r])
+    assert np.array_equal(ck.manifest_to_numpy(sw.manifest[r], want["ndirty"]), o.manifest[r])
+
+
+@pytest.mark.parametrize("sync_every_switch", [True, False], ids=["checked_each_switch", "eager"])
+def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch):
+    w = wl.config(4, 8)
+    base = wl.numpy_replica(w, 0)
+    ranks = [wl.numpy_replica(w, r) for r in range(1, NRANKS + 1)]
+    dev = DeviceBuffers(ranks[0], w.chunk)                  # rank 0 is resident first
+    o = OracleRanks(w, base, ranks[0])
+    n = dev.plan.nchunks
+    ref = torch.from_numpy(o.ref.view(np.int64)).cuda()
+    cap_bytes, cap_entries = w.distinct_bytes + 16 * n, w.distinct_chunks
+    sw = TimeSlicedRanks(dev.plan, ref, NRANKS, cap_bytes, cap_entries)
+
+    # the other ranks' deltas reach their host areas the way they would in a running job:
+    # each was resident once and was swapped out (here from a scratch copy of its state)
+    for r in range(1, NRANKS):
+        tmp = DeviceBuffers(ranks[r], w.chunk)
+        one = TimeSlicedRanks(tmp.plan, ref, 1, cap_bytes, cap_entries)
+        one.swap_out(0)
+        torch.cuda.synchronize()
+        sw.host[r].copy_(one.host[0])
+        sw.manifest[r].copy_(one.manifest[0])
+        sw.counts[r].copy_(one.counts[0])
+        sw.mask[r].copy_(one.mask[0])
+        o.staging[r], o.manifest[r], o.counts[r] = o.delta_of(ranks[r])
+        check_rank_area(sw, o, r)
+
+    rng = np.random.default_rng(4)
+    side = torch.cuda.Stream()
+    first_kernel_ran = torch.zeros(1, dtype=torch.int64, device="cuda")
+    resident = 0
+    for step in range(2 * NRANKS):                          # two full rotations
+        run_a_mini_batch(w, rng, o, dev)
+        nxt = (resident + 1) % NRANKS
+        sw.switch(resident, nxt)
+        o.switch(resident, nxt)
+        # the incoming rank's first kernel, dispatched at once on another stream behind an event
+        done = torch.cuda.Event()
+        done.record()
+        with torch.cuda.stream(side):
+            side.wait_event(done)
+            first_kernel_ran.add_(1)
+        if sync_every_switch:
+            torch.cuda.synchronize()
+            assert int(sw.rejected.item()) == 0
+            check_rank_area(sw, o, resident)
+            got, img = dev.host()
+            assert all(np.array_equal(g, want) for g, want in zip(got, o.image)), step
+            assert dev.canaries_intact(img)
+        resident = nxt
+    torch.cuda.synchronize()
+    assert int(first_kernel_ran.item()) == 2 * NRANKS and int(sw.rejected.item()) == 0
+    assert resident == 0
+    got, img = dev.host()
+    assert all(np.array_equal(g, want) for g, want in zip(got, o.image))
+    assert dev.canaries_intact(img)
+    for r in range(NRANKS):
+        check_rank_area(sw, o, r)
+    assert sw.same_dirty_set()
+    # what is resident is rank 0 as it was when it was swapped out last, not the base
+    assert not all(np.array_equal(g, b) for g, b in zip(got, base))
