@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--hint-cases", action="store_true",
                     help="time ckpt_snapshot with an exact hint, no hint and a hint with one wrong "
                          "chunk also when the main path is the three calls")
+    ap.add_argument("--no-hint-cases", action="store_true",
+                    help="skip the three-hint comparison (keeps a profiler's per-kernel averages "
+                         "to the main path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-gib", type=float, default=8.0)
     ap.add_argument("--match", action="store_true",
@@ -68,6 +71,10 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in HIP graphs (snapshot part, restore part) and "
                          "time their replays: what a launch-bound small state gains")
+    ap.add_argument("--probe", action="store_true",
+                    help="also run the side measurements the design notes cite: the hinted pass as "
+                         "one launch against two, plain and 16-streams-per-wavefront copy and read "
+                         "rates, and the fingerprint over one buffer for chunk sizes 256 B - 64 MiB")
     ap.add_argument("--calibrate", action="store_true",
                     help="also time the plain read and copy kernels on 8 GiB (HBM ceiling, and "
                          "the known-size dispatches that scale the rocprofv3 byte counters) and "
@@ -375,43 +382,48 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
     side = torch.cuda.Stream()
     token = torch.zeros(1, dtype=torch.int64, device=dev)
     ev = torch.cuda.Event
-    ms, wall_ms = [], []
-    resident, ok = 0, True
-    rounds = 2
-    for step in range(rounds * nranks):
-        nxt = (resident + 1) % nranks
-        e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record()
-        sw.switch(resident, nxt)
-        e1.record()
-        with torch.cuda.stream(side):
-            side.wait_event(e1)
-            token.add_(1)                 # the incoming rank's first kernel
-            e2.record()
-        enqueue_ms = (time.perf_counter() - t0) * 1e3
-        torch.cuda.synchronize()
-        wall_ms.append((time.perf_counter() - t0) * 1e3)
-        ms.append((e0.elapsed_time(e1), enqueue_ms))
-        if step < nranks:                 # first rotation: the image is the incoming rank's state
-            ok = ok and bool(torch.equal(image, states[nxt]))
-        resident = nxt
-    assert ok and int(sw.rejected.item()) == 0 and int(token.item()) == rounds * nranks
-    c = sw.counts[0].cpu().numpy().view(np.uint64)
-    staged = int(c[1])
-    timed = [m[0] for m in ms[nranks:]]            # second rotation: everything warm
-    mean = float(np.mean(timed))
-    link_bytes = 2 * staged
+    rounds, ok, modes = 2, True, {}
+    for mode, exchange in (("swap_out_then_swap_in", False), ("exchange_pass", True)):
+        ms, wall_ms, enq_ms, serial = [], [], [], 0
+        resident = 0
+        for step in range(rounds * nranks):
+            nxt = (resident + 1) % nranks
+            e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            sw.switch(resident, nxt, exchange=exchange)
+            e1.record()
+            with torch.cuda.stream(side):
+                side.wait_event(e1)
+                token.add_(1)                 # the incoming rank's first kernel
+                e2.record()
+            enq_ms.append((time.perf_counter() - t0) * 1e3)
+            torch.cuda.synchronize()
+            wall_ms.append((time.perf_counter() - t0) * 1e3)
+            ms.append(e0.elapsed_time(e1))
+            serial += int(sw.serial.item())
+            if step < nranks:             # first rotation: the image is the incoming rank's state
+                ok = ok and bool(torch.equal(image, states[nxt]))
+            resident = nxt
+        assert ok and int(sw.rejected.item()) == 0 and serial == 0
+        staged = int(sw.counts[0].cpu().numpy().view(np.uint64)[1])
+        timed = ms[nranks:]                   # second rotation: everything warm
+        mean = float(np.mean(timed))
+        modes[mode] = {
+            "switch_ms_mean": round(mean, 2), "switch_ms_min": round(min(timed), 2),
+            "switch_wall_ms_mean": round(float(np.mean(wall_ms[nranks:])), 2),
+            "host_enqueue_ms_mean": round(float(np.mean(enq_ms[nranks:])), 3),
+            "host_link_GBps_both_directions": round(2 * staged / mean / 1e6, 1),
+        }
+    assert int(token.item()) == 2 * rounds * nranks
+    slow = modes["swap_out_then_swap_in"]["switch_ms_mean"]
     return {
         "workload": f"config{w.config}_{w.name}: {nranks} ranks round robin on one device image",
         "state_bytes_per_rank": S, "delta_bytes_per_rank": staged,
-        "switch_ms_mean": round(mean, 2), "switch_ms_min": round(min(timed), 2),
-        "switch_wall_ms_mean": round(float(np.mean(wall_ms[nranks:])), 2),
-        "host_enqueue_ms_mean": round(float(np.mean([m[1] for m in ms[nranks:]])), 3),
-        "host_link_bytes_per_switch": link_bytes,
-        "host_link_GBps": round(link_bytes / mean / 1e6, 1),
-        "full_state_swap_ms_at_same_rate": round(2 * S / (link_bytes / mean) , 1),
+        "host_link_bytes_per_switch": 2 * staged,
+        **modes,
+        "full_state_swap_ms_at_the_one_way_rate": round(2 * S / (2 * staged / slow), 1),
         "image_equals_incoming_rank_after_each_switch": ok,
         "paper_context": "sec. 5.2: swapping 32 GB out and in without de-duplication costs 2-4 s "
                          "per mini-batch on the paper's V100 hosts",
@@ -684,7 +696,7 @@ def main():
                              phase_names({k: v for k, v in low.items()}, fused).items()}
         out["latency_us"]["basis"] = "min over timed steps, per phase of one step"
 
-    if fused or args.hint_cases:
+    if (fused or args.hint_cases) and not args.no_hint_cases:
         out["hint_cases"] = hint_cases_leg(w, pairs[0][1], ref, staged[0], ndirty[0], ck, torch, np,
                                            args)
 
@@ -726,6 +738,10 @@ def main():
         out["host_swap"] = host_swap_leg(w, pairs[-1][1], digs[-1], masks[-1], manifests[-1],
                                          stagings[-1], staged[-1], ndirty[-1], ck, torch,
                                          args.swap_slice_mib << 20)
+
+    if args.probe:
+        out["probe"] = probe_leg(w, pairs[0][1], ref, stagings[0], staged[0], ndirty[0], ck, torch,
+                                 np, args)
 
     if args.switch:
         if w.nreplicas < 4:

@@ -95,8 +95,8 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  *               fingerprint runs at a fraction of the memory bandwidth
  *   out         receives the plan; destroy it with ckpt_plan_destroy
  * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
- * ckpt_snapshot, ckpt_upload_owners, ckpt_swap_out and ckpt_apply_moves_inplace
- * write: calls of these on ONE plan must be ordered (one stream, or events);
+ * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_upload_owners, ckpt_swap_out
+ * and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered (one stream, or events);
  * issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
  * the other calls only read the plan and may overlap freely.
  * Two non-empty buffers that share a byte are refused (INVALID_ARG): restoring
@@ -192,6 +192,47 @@ int ckpt_upload_owners(const ckpt_plan_t *plan, const uint64_t *d_gathered, uint
 int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
                  void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
                  uint64_t manifest_cap, ckpt_counts_t *d_counts, void *stream);
+
+/* The metadata half of ckpt_compact alone: d_manifest and d_counts exactly as
+ * ckpt_compact writes them for the same arguments (staging_cap only decides
+ * which entries count as overflow), and not a byte of chunk data moved.  For
+ * callers that move the bytes another way: ckpt_exchange below.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_manifest(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
+                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                  ckpt_counts_t *d_counts, void *stream);
+
+/* A whole context switch between two ranks that share the plan's buffers
+ * (sec. 5.1, 5.2.1): the outgoing rank's chunks (d_manifest_out, from
+ * ckpt_manifest or ckpt_compact on its mask, d_counts_out->ndirty entries) go to
+ * d_staging_out as ckpt_compact would stage them, and the incoming rank's
+ * chunks (d_manifest_in, d_counts_in->ndirty entries, bytes in d_staging_in)
+ * come into the buffers as ckpt_restore_counted would put them -- the same
+ * result as those two calls one after the other.
+ * Ranks of a data-parallel job that are time-sliced on one GPU differ from
+ * their shared base in the same chunks, so the two manifests normally name the
+ * same buffer ranges and staging offsets entry by entry.  The call checks that
+ * on the device; if it holds, one kernel exchanges each chunk in place (reads
+ * the outgoing bytes from the buffer and the incoming bytes from d_staging_in,
+ * writes each where the other came from): with both staging areas in pinned
+ * host memory the host link carries both directions at once.  If it does not
+ * hold, the swap-out and the swap-in run one after the other instead.  Nothing
+ * is read on the host either way.
+ *   staging_out_cap   bytes d_staging_out can hold; staging_in_bytes: valid
+ *                     bytes of d_staging_in.  The two areas must not overlap
+ *                     each other or the buffers.
+ *   manifest_cap      entries each manifest can hold (upper bound on reads)
+ *   d_serial          optional device uint64: 0 if the single exchange pass
+ *                     ran, else the number of places where the manifests differ
+ *   d_rejected        optional device uint64: entries skipped because they do
+ *                     not fit the plan or a staging area (0 = none)
+ * Writes one word of the plan's scratch: order it like ckpt_diff / ckpt_compact.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_exchange(const ckpt_plan_t *plan, const ckpt_entry_t *d_manifest_out,
+                  const ckpt_counts_t *d_counts_out, void *d_staging_out, uint64_t staging_out_cap,
+                  const ckpt_entry_t *d_manifest_in, const ckpt_counts_t *d_counts_in,
+                  const void *d_staging_in, uint64_t staging_in_bytes, uint64_t manifest_cap,
+                  uint64_t *d_serial, uint64_t *d_rejected, void *stream);
 
 /* The three calls above as one, with the same outputs bit for bit (d_digests,
  * d_mask, d_staging, d_manifest, d_counts), optionally in a single pass over the
@@ -426,6 +467,18 @@ int ckpt_validate_mutations(const ckpt_plan_t *plan, const uint64_t *d_before_a,
  * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
 int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream);
 int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *stream);
+
+/* The same two yardsticks with the fingerprint pass's access pattern: nstreams
+ * (multiple of 16) streams of stream_bytes (multiple of 512) bytes each, stream
+ * i at d_src + i * stream_bytes; every wavefront walks 16 streams front to back,
+ * 256 bytes of each per step -- as it walks 16 chunks when it hashes.  With
+ * d_dst each tile is stored to the same offset of d_dst (the staging writes of
+ * ckpt_snapshot with a hint); with d_dst == NULL the streams are only read.
+ * d_sink: at least 16 KiB.  The caller provides nstreams * stream_bytes
+ * readable (and writable) bytes.
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+int ckpt_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams, uint64_t stream_bytes,
+                    uint64_t *d_sink, void *stream);
 
 /* The other yardstick: the XXH64 accumulator arithmetic alone, on words made
  * up in registers, no memory traffic -- what the integer units allow the

@@ -25,13 +25,13 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
-    "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact",
+    "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact", "ckpt_manifest", "ckpt_exchange",
     "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
-    "ckpt_bw_copy", "ckpt_bw_read", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
+    "ckpt_bw_copy", "ckpt_bw_read", "ckpt_bw_streams", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
 )
 
@@ -81,6 +81,10 @@ def _lib():
         lib.ckpt_upload_owners.argtypes = [vp, vp, ctypes.c_uint32, ctypes.c_uint32, vp, vp, vp]
         lib.ckpt_compact.restype = ci
         lib.ckpt_compact.argtypes = [vp, vp, vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_manifest.restype = ci
+        lib.ckpt_manifest.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_exchange.restype = ci
+        lib.ckpt_exchange.argtypes = [vp, vp, vp, vp, u64, vp, vp, vp, u64, u64, vp, vp, vp]
         lib.ckpt_restore.restype = ci
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore_counted.restype = ci
@@ -123,6 +127,8 @@ def _lib():
         lib.ckpt_bw_copy.argtypes = [vp, vp, u64, vp]
         lib.ckpt_bw_read.restype = ci
         lib.ckpt_bw_read.argtypes = [vp, u64, vp, vp]
+        lib.ckpt_bw_streams.restype = ci
+        lib.ckpt_bw_streams.argtypes = [vp, vp, u64, u64, vp, vp]
         lib.ckpt_alu_xxh64.restype = u64
         lib.ckpt_alu_xxh64.argtypes = [u64, vp, vp]
         lib.ckpt_strerror.restype = ctypes.c_char_p
@@ -243,6 +249,25 @@ def compact(plan: Plan, mask, digests, staging, manifest, counts, stream=None,
     _check(_lib().ckpt_compact(plan._h, _ptr(mask), _ptr(digests), _ptr(staging), staging_cap,
                                _ptr(manifest), manifest_cap, _ptr(counts), _stream(stream)),
            "ckpt_compact")
+
+
+def manifest(plan: Plan, mask, digests, manifest_t, counts, staging_cap: int,
+             manifest_cap: Optional[int] = None, stream=None) -> None:
+    """``ckpt_manifest``: manifest entries and counts for a mask, no chunk bytes moved."""
+    if manifest_cap is None:
+        manifest_cap = manifest_t.numel() * manifest_t.element_size() // ENTRY_BYTES
+    _check(_lib().ckpt_manifest(plan._h, _ptr(mask), _ptr(digests), staging_cap, _ptr(manifest_t),
+                                manifest_cap, _ptr(counts), _stream(stream)), "ckpt_manifest")
+
+
+def exchange(plan: Plan, manifest_out, counts_out, staging_out, staging_out_cap: int, manifest_in,
+             counts_in, staging_in, staging_in_bytes: int, manifest_cap: int, serial=None,
+             rejected=None, stream=None) -> None:
+    """``ckpt_exchange``: swap-out of one rank's chunks and swap-in of another's as one pass."""
+    _check(_lib().ckpt_exchange(plan._h, _ptr(manifest_out), _ptr(counts_out), _ptr(staging_out),
+                                staging_out_cap, _ptr(manifest_in), _ptr(counts_in),
+                                _ptr(staging_in), staging_in_bytes, manifest_cap, _ptr(serial),
+                                _ptr(rejected), _stream(stream)), "ckpt_exchange")
 
 
 def snapshot_workspace_bytes(nchunks: int) -> int:
@@ -420,6 +445,13 @@ def bw_copy(dst, src, nbytes: int, stream=None) -> None:
 
 def bw_read(src, nbytes: int, sink, stream=None) -> None:
     _check(_lib().ckpt_bw_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "ckpt_bw_read")
+
+
+def bw_streams(dst, src, nstreams: int, stream_bytes: int, sink, stream=None) -> None:
+    """``ckpt_bw_streams``: copy (or, with dst None, read) nstreams streams of stream_bytes bytes
+    with the fingerprint pass's access pattern."""
+    _check(_lib().ckpt_bw_streams(_ptr(dst), _ptr(src), nstreams, stream_bytes, _ptr(sink),
+                                  _stream(stream)), "ckpt_bw_streams")
 
 
 def alu_xxh64(rounds_per_lane: int, sink, stream=None) -> int:

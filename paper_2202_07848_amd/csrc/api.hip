@@ -212,10 +212,6 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   }
   const uint64_t nscan = (nchunks + ckpt::SCAN_BLOCK - 1) / ckpt::SCAN_BLOCK;
   e = hipMalloc(reinterpret_cast<void **>(&plan->d_blocksums), 16 * (nscan + 1));
-  if (e == hipSuccess) {
-    e = hipMemset(plan->d_blocksums, 0, 16);   // the scan's ticket counter starts at zero
-    if (e != hipSuccess) (void)hipFree(plan->d_blocksums);
-  }
   if (e != hipSuccess) {
     (void)hipFree(plan->d_tables);
     delete plan;
@@ -359,7 +355,7 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = ckpt::launch_compact_scan(plan->dev, d_mask, d_digests, staging_cap, d_manifest,
                                            manifest_cap, plan->d_blocksums, d_counts, nullptr,
-                                           nullptr, s);
+                                           nullptr, false, s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(plan->dev, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
                             nullptr, nullptr, s);
@@ -368,6 +364,47 @@ int ckpt_compact(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t 
 
 uint64_t ckpt_snapshot_workspace_bytes(uint64_t nchunks) { return snapshot_ws_bytes(nchunks); }
 uint64_t ckpt_snapshot_stats_offset(uint64_t nchunks) { return 8 * nchunks; }
+
+int ckpt_manifest(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint64_t *d_digests,
+                  uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                  ckpt_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  const uint64_t n = plan->dev.nchunks;
+  if (n != 0 && (d_mask == nullptr || d_digests == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_manifest, 8) || !aligned(d_digests, 8) || !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_compact_scan(plan->dev, d_mask, d_digests, staging_cap, d_manifest,
+                                           manifest_cap, plan->d_blocksums, d_counts, nullptr,
+                                           nullptr, false, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_exchange(const ckpt_plan_t *plan, const ckpt_entry_t *d_manifest_out,
+                  const ckpt_counts_t *d_counts_out, void *d_staging_out, uint64_t staging_out_cap,
+                  const ckpt_entry_t *d_manifest_in, const ckpt_counts_t *d_counts_in,
+                  const void *d_staging_in, uint64_t staging_in_bytes, uint64_t manifest_cap,
+                  uint64_t *d_serial, uint64_t *d_rejected, void *stream) {
+  if (plan == nullptr || d_counts_out == nullptr || d_counts_in == nullptr)
+    return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && (d_manifest_out == nullptr || d_manifest_in == nullptr))
+    return CKPT_ERR_INVALID_ARG;
+  if (staging_out_cap != 0 && d_staging_out == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (staging_in_bytes != 0 && d_staging_in == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap > (1ull << 40)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_staging_out, 16) || !aligned(d_staging_in, 16) || !aligned(d_manifest_out, 8) ||
+      !aligned(d_manifest_in, 8) || !aligned(d_counts_out, 8) || !aligned(d_counts_in, 8) ||
+      !aligned(d_serial, 8) || !aligned(d_rejected, 8))
+    return CKPT_ERR_ALIGNMENT;
+  // the word that says whether the manifests line up: the spare pair behind the scan scratch
+  const uint64_t nscan = (plan->dev.nchunks + ckpt::SCAN_BLOCK - 1) / ckpt::SCAN_BLOCK;
+  uint64_t *differs = plan->d_blocksums + 2 * nscan;
+  hipError_t e = ckpt::launch_exchange(plan->dev, d_manifest_out, d_counts_out, d_staging_out,
+                                       staging_out_cap, d_manifest_in, d_counts_in, d_staging_in,
+                                       staging_in_bytes, manifest_cap, differs, d_serial, d_rejected,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
 
 // Argument checks and launches of ckpt_snapshot; d_blocksums is the scan scratch to use (the
 // plan's own, or the library's static block).
@@ -406,20 +443,22 @@ static int snapshot_impl(const ckpt_plan_t *plan, const uint64_t *d_ref, uint64_
     h.need = h.copy + npad;
     uint32_t *list = reinterpret_cast<uint32_t *>(h.need + npad);
     uint8_t *flags = reinterpret_cast<uint8_t *>(list + (n / 16 + 2));
-    e = ckpt::launch_hint_offsets(p, d_hint, h, d_blocksums, tmp, manifest_cap, s);
+    e = ckpt::launch_hint_offsets(p, d_hint, h, d_blocksums, tmp, manifest_cap, d_counts,
+                                  d_hint_misses, s);
     if (e == hipSuccess)
       e = ckpt::launch_fingerprint_staging(p, d_digests, d_ref, d_mask, h.copy, h.hoff, d_staging,
                                            staging_cap, list, flags, list_counts,
                                            plan->nbytes >= plan->split_pass_bytes, s);
   } else {
-    e = ckpt::launch_fingerprint_diff(p, d_digests, d_ref, d_mask, s);
+    e = ckpt::launch_fingerprint_diff(p, d_digests, d_ref, d_mask, d_counts, d_hint_misses, s);
   }
   // Kernels up to SMALL_SCAN_CHUNKS chunks: with a hint 4 (its offsets, the pass, the manifest,
-  // the conditional gather; 7 when the pass is split), 3 without.  Above: 6 (9) and 4.
+  // the conditional gather; 7 when the pass is split), 3 without.  Above: 8 (11) and 5.
+  // Either first kernel has cleared what the one-kernel manifest path adds to.
   const ckpt::HintState *hp = d_hint != nullptr ? &h : nullptr;
   if (e == hipSuccess)
     e = ckpt::launch_compact_scan(p, d_mask, d_digests, staging_cap, d_manifest, manifest_cap,
-                                  d_blocksums, d_counts, hp, d_hint_misses, s);
+                                  d_blocksums, d_counts, hp, d_hint_misses, n != 0, s);
   if (e == hipSuccess)
     e = ckpt::launch_gather(p, d_manifest, manifest_cap, d_counts, d_staging, staging_cap,
                             hp ? h.misses : nullptr, hp ? h.need : nullptr, s);
@@ -574,6 +613,20 @@ int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *str
     return CKPT_ERR_INVALID_ARG;
   if (!aligned(d_src, 16) || !aligned(d_sink, 8)) return CKPT_ERR_ALIGNMENT;
   hipError_t e = ckpt::launch_bw_read(d_src, nbytes, d_sink, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+int ckpt_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams, uint64_t stream_bytes,
+                    uint64_t *d_sink, void *stream) {
+  if (nstreams == 0) return CKPT_OK;
+  if (d_src == nullptr || d_sink == nullptr) return CKPT_ERR_INVALID_ARG;
+  if ((nstreams & 15) != 0 || (stream_bytes & 511) != 0 || stream_bytes == 0 ||
+      nstreams / 16 > 0x7FFFFFFFull || stream_bytes > (1ull << 40) ||
+      nstreams > (~0ull) / stream_bytes)
+    return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_dst, 16) || !aligned(d_src, 16) || !aligned(d_sink, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_bw_streams(d_dst, d_src, nstreams, stream_bytes, d_sink,
+                                         static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

@@ -100,9 +100,8 @@ __device__ __forceinline__ uint64_t pad16(uint64_t x) { return (x + 15) & ~15ull
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_PER_THREAD = 4;
 constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
-// Scan scratch (owned by a plan, 2 + 2 * ceil(N / SCAN_BLOCK) words): word 0 is a ticket counter
-// that is zero whenever no scan kernel is running, word 1 is spare, then one pair per block.
-constexpr int SCRATCH_HEAD = 2;
+// Scan scratch (owned by a plan): one (count, bytes) pair per SCAN_BLOCK chunks, and one spare
+// pair whose first word ckpt_exchange uses.
 // Up to this many chunks a workgroup finds its own scan offset by counting the mask bytes in
 // front of its block (at most 256 KiB per workgroup), which makes the scan a single kernel.
 constexpr uint64_t SMALL_SCAN_CHUNKS = 1ull << 18;
@@ -123,19 +122,21 @@ constexpr int COPY_MAX_GROUPS = 65536;
 
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t s);
-// The same pass, also writing d_mask[k] = (d_ref == null || digest != d_ref[k]).
+// The same pass, also writing d_mask[k] = (d_ref == null || digest != d_ref[k]) and clearing
+// d_counts->overflow and *d_misses_out (may be null) for the manifest kernel that follows.
 hipError_t launch_fingerprint_diff(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
-                                   uint8_t *d_mask, hipStream_t s);
+                                   uint8_t *d_mask, ckpt_counts_t *d_counts, uint64_t *d_misses_out,
+                                   hipStream_t s);
 hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                       uint8_t *d_mask, uint64_t *d_scratch, ckpt_counts_t *d_counts,
-                       hipStream_t s);
+                       uint8_t *d_mask, uint64_t *d_pairs, ckpt_counts_t *d_counts, hipStream_t s);
 // Manifest and counts for a mask.  h (fused snapshot, may be null): hint misses are counted into
 // h->misses[0] and entries the pass has already staged in place are marked in h->need;
-// *d_misses_out (may be null) receives the miss count, 0 without h.
+// *d_misses_out (may be null) receives the miss count, 0 without h.  cleared: an earlier kernel
+// of the same call has zeroed d_counts->overflow, *d_misses_out and h's counters.
 hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
                                uint64_t staging_cap, ckpt_entry_t *d_manifest,
-                               uint64_t manifest_cap, uint64_t *d_scratch,
-                               ckpt_counts_t *d_counts, const HintState *h, uint64_t *d_misses_out,
+                               uint64_t manifest_cap, uint64_t *d_pairs, ckpt_counts_t *d_counts,
+                               const HintState *h, uint64_t *d_misses_out, bool cleared,
                                hipStream_t s);
 // d_only_if_nonzero (may be null): the kernel does nothing when it points to 0;  d_need (may be
 // null): entries e with d_need[e] == 0 are skipped.
@@ -156,12 +157,27 @@ uint64_t fingerprint_groups(const PlanDev &p);
 // then receives the number of chunks the corrective gather has to copy), [4..5] group list lengths.
 constexpr int SNAPSHOT_COUNTERS = 6;
 hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, const HintState &h,
-                               uint64_t *d_scratch, ckpt_counts_t *d_tmp_counts,
-                               uint64_t manifest_cap, hipStream_t s);
+                               uint64_t *d_pairs, ckpt_counts_t *d_tmp_counts, uint64_t manifest_cap,
+                               ckpt_counts_t *d_counts, uint64_t *d_misses_out, hipStream_t s);
 // Applies min(nentries, d_counts->ndirty) entries when d_counts is not null, else nentries.
 hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
                           const ckpt_counts_t *d_counts, const void *d_staging,
                           uint64_t staging_bytes, uint64_t *d_rejected, hipStream_t s);
+// As launch_scatter, but the kernel does nothing when *d_only_if_nonzero == 0, and d_rejected
+// (may be null) is added to, not cleared first.
+hipError_t launch_scatter_gated(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
+                                const ckpt_counts_t *d_counts, const void *d_staging,
+                                uint64_t staging_bytes, uint64_t *d_rejected,
+                                const uint64_t *d_only_if_nonzero, hipStream_t s);
+// Swap-out of one manifest's chunks and swap-in of another's in one pass when the two describe
+// the same places, else one after the other; *d_differs (scratch word) receives the number of
+// places where they differ, *d_serial (may be null) a copy of it.
+hipError_t launch_exchange(const PlanDev &p, const ckpt_entry_t *d_manifest_out,
+                           const ckpt_counts_t *d_counts_out, void *d_stage_out, uint64_t out_cap,
+                           const ckpt_entry_t *d_manifest_in, const ckpt_counts_t *d_counts_in,
+                           const void *d_stage_in, uint64_t in_bytes, uint64_t manifest_cap,
+                           uint64_t *d_differs, uint64_t *d_serial, uint64_t *d_rejected,
+                           hipStream_t s);
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);
@@ -183,6 +199,8 @@ hipError_t launch_slice(bool gather, const PlanDev &p, const ckpt_entry_t *d_man
 hipError_t launch_zero_u64(uint64_t *d_value, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
+hipError_t launch_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams,
+                             uint64_t stream_bytes, uint64_t *d_sink, hipStream_t s);
 constexpr uint32_t ALU_PROBE_GROUPS = 2048;   // workgroups of 256 lanes in the hash-only probe
 hipError_t launch_alu_xxh64(uint64_t rounds_per_lane, uint64_t *d_sink, hipStream_t s);
 

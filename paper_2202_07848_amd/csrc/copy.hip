@@ -133,6 +133,61 @@ __global__ __launch_bounds__(256) void k_bw_read(const uint4 *__restrict__ src, 
   if (threadIdx.x == 0) sink[blockIdx.x] = s_x[0];
 }
 
+// The fingerprint kernel's memory access pattern without its arithmetic: single-wavefront
+// workgroups, 16 streams per wavefront (stream i = bytes [i, i+1) * stream_bytes of src), each
+// load instruction fetching one 256-byte tile from each of four streams, two tiles per stream
+// prefetched in registers.  COPY: every tile is stored to the same offset of dst (what the fused
+// snapshot pass does with staged chunks); otherwise the tiles are XOR-ed into one word per
+// wavefront.  Its rate is the ceiling this access pattern leaves the fingerprint pass.
+template <bool COPY>
+__global__ __launch_bounds__(64) void k_bw_streams(const uint8_t *__restrict__ src,
+                                                   uint8_t *__restrict__ dst,
+                                                   uint64_t stream_bytes,
+                                                   uint64_t *__restrict__ sink) {
+  const uint32_t lane = threadIdx.x;
+  const uint64_t first = (uint64_t)blockIdx.x * 16;
+  const uint8_t *lp[4];
+  uint8_t *sp[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint64_t off = (first + 4 * i + (lane >> 4)) * stream_bytes + 16 * (lane & 15);
+    lp[i] = src + off;
+    sp[i] = dst + off;
+  }
+  const uint64_t tiles = stream_bytes >> 8;        // even and >= 2 (checked on the host)
+  uint4 q0[4], q1[4], acc = make_uint4(0, 0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    q0[i] = stream_load16(lp[i]);
+    q1[i] = stream_load16(lp[i] + 256);
+  }
+  for (uint64_t t = 0; t < tiles; t += 2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (COPY) {
+        stream_store16(sp[i] + (t << 8), q0[i]);
+      } else {
+        acc.x ^= q0[i].x; acc.y ^= q0[i].y; acc.z ^= q0[i].z; acc.w ^= q0[i].w;
+      }
+      if (t + 2 < tiles) q0[i] = stream_load16(lp[i] + ((t + 2) << 8));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (COPY) {
+        stream_store16(sp[i] + ((t + 1) << 8), q1[i]);
+      } else {
+        acc.x ^= q1[i].x; acc.y ^= q1[i].y; acc.z ^= q1[i].z; acc.w ^= q1[i].w;
+      }
+      if (t + 3 < tiles) q1[i] = stream_load16(lp[i] + ((t + 3) << 8));
+    }
+  }
+  if (!COPY) {
+    uint64_t v = ((uint64_t)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
+    for (int o = 32; o > 0; o >>= 1) v ^= __shfl_down(v, o, 64);
+    if (lane == 0) sink[blockIdx.x % 2048] = v;      // keeps the loads alive; value unused
+  }
+}
+
 // The hash arithmetic alone: every lane runs `rounds` XXH64 accumulator steps on words it
 // makes up in registers (one 64-bit add per word), no memory traffic.  Its rate, times 8 bytes
 // per step, is the ceiling the integer units set for the fingerprint kernel.
@@ -197,6 +252,22 @@ hipError_t launch_scatter(const PlanDev &p, const ckpt_entry_t *d_manifest, uint
   return hipGetLastError();
 }
 
+hipError_t launch_scatter_gated(const PlanDev &p, const ckpt_entry_t *d_manifest, uint64_t nentries,
+                                const ckpt_counts_t *d_counts, const void *d_staging,
+                                uint64_t staging_bytes, uint64_t *d_rejected,
+                                const uint64_t *d_only_if_nonzero, hipStream_t s) {
+  const uint64_t most = p.nchunks < nentries ? p.nchunks : nentries;
+  const uint32_t groups = move_groups(p, most);
+  if (groups == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_move<false>, dim3(groups), dim3(COPY_THREADS), 0, s, p, d_manifest, most,
+                     d_counts,
+                     const_cast<uint8_t *>(reinterpret_cast<const uint8_t *>(d_staging)),
+                     staging_bytes, reinterpret_cast<unsigned long long *>(d_rejected),
+                     reinterpret_cast<const unsigned long long *>(d_only_if_nonzero),
+                     (const uint8_t *)nullptr);
+  return hipGetLastError();
+}
+
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s) {
   const uint64_t n16 = nbytes / 16;
   if (n16 == 0) return hipSuccess;
@@ -204,6 +275,20 @@ hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipSt
   if (groups > 2048) groups = 2048;
   hipLaunchKernelGGL(k_bw_copy, dim3((uint32_t)groups), dim3(256), 0, s,
                      reinterpret_cast<uint4 *>(d_dst), reinterpret_cast<const uint4 *>(d_src), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams,
+                             uint64_t stream_bytes, uint64_t *d_sink, hipStream_t s) {
+  const uint32_t groups = (uint32_t)(nstreams / 16);
+  if (groups == 0) return hipSuccess;
+  const uint8_t *src = reinterpret_cast<const uint8_t *>(d_src);
+  if (d_dst != nullptr)
+    hipLaunchKernelGGL(k_bw_streams<true>, dim3(groups), dim3(64), 0, s, src,
+                       reinterpret_cast<uint8_t *>(d_dst), stream_bytes, d_sink);
+  else
+    hipLaunchKernelGGL(k_bw_streams<false>, dim3(groups), dim3(64), 0, s, src,
+                       (uint8_t *)nullptr, stream_bytes, d_sink);
   return hipGetLastError();
 }
 

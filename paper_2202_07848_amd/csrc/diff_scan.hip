@@ -6,15 +6,18 @@
 //
 // compact, metadata half: stable compaction.  Staging order must be ascending
 // chunk id, so offsets come from an exclusive prefix sum over
-// (mask, mask * pad16(len)) pairs.  No workgroup ever waits for another one:
-//   * every workgroup stores the pair of its SCAN_BLOCK chunks and takes a
-//     ticket; the one that draws the last ticket knows all pairs are stored
-//     and scans them (a single kernel where there used to be two);
-//   * a second kernel rescans each block from its offset and writes the
-//     manifest;
-//   * up to SMALL_SCAN_CHUNKS chunks even that is one kernel: a workgroup
-//     gets its offset by counting the mask bytes in front of its block
-//     itself (at most 256 KiB, out of L2), so nothing has to be handed over.
+// (mask, mask * pad16(len)) pairs, in deterministic steps with no workgroup
+// ever waiting for another and no memory fence inside a kernel (a device-scope
+// fence writes back and invalidates the L2 of the XCD that issues it: measured
+// with 6 000 workgroups, one fence each turned a 50 us kernel into 500 us):
+//   * above SMALL_SCAN_CHUNKS chunks: per-workgroup sums, a single-workgroup
+//     scan of those sums, then a per-workgroup rescan that writes the manifest;
+//   * up to SMALL_SCAN_CHUNKS chunks one kernel does it all: a workgroup gets
+//     its offset by counting the mask bytes in front of its block itself (at
+//     most 256 KiB, out of L2), so nothing has to be handed over; the last
+//     workgroup's offset plus its own sum are the totals; the few counters that
+//     need every workgroup's share are added with plain atomics into words an
+//     earlier kernel of the same call has cleared.
 #include "ckpt_internal.h"
 
 namespace ckpt {
@@ -80,38 +83,23 @@ __device__ __forceinline__ Pair sum_marked(const PlanDev &p, uint64_t k0, const 
   return s;
 }
 
-// Scan scratch: word 0 is the ticket counter (zero between kernels), word 1 is
-// spare, block b's pair sits in words SCRATCH_HEAD + 2b, + 2b + 1.
-__device__ __forceinline__ uint64_t *block_pairs(uint64_t *scratch) { return scratch + SCRATCH_HEAD; }
-
-// Every workgroup calls this after storing what it hands on.  True in exactly
-// one workgroup: the one that arrives last, by which time every other
-// workgroup's stores are visible to it.  Nobody waits.  That workgroup must put
-// the ticket back to zero before it ends (reset_ticket).
-__device__ bool arrived_last(uint64_t *scratch) {
-  __shared__ bool s_last;
-  __threadfence();                 // this workgroup's stores, device-wide
-  __syncthreads();
+// Stores the workgroup's pair where the scan kernel finds it.
+__device__ __forceinline__ void store_block_pair(uint64_t *pairs, Pair total) {
   if (threadIdx.x == 0) {
-    const unsigned long long t = atomicAdd(reinterpret_cast<unsigned long long *>(scratch), 1ull);
-    s_last = t == (unsigned long long)gridDim.x - 1;
+    pairs[2 * (uint64_t)blockIdx.x] = total.cnt;
+    pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
   }
-  __syncthreads();
-  const bool last = s_last;
-  if (last) __threadfence();       // the other workgroups' stores
-  return last;
-}
-
-__device__ __forceinline__ void reset_ticket(uint64_t *scratch) {
-  if (threadIdx.x == 0) *reinterpret_cast<volatile uint64_t *>(scratch) = 0;
 }
 
 // One workgroup: turns pairs[0..nblocks) into their exclusive prefix sums
 // (when `rewrite`) and writes the grand totals to counts, overflow = 0.
 // Fused snapshot: *publish_dst (when not null) receives *publish_src, or 0
-// when there is no source -- the hint-miss count.
-__device__ void scan_pairs(uint64_t *pairs, uint64_t nblocks, bool rewrite, ckpt_counts_t *counts,
-                           const unsigned long long *publish_src, unsigned long long *publish_dst) {
+// when there is no source -- the hint-miss count, complete once the kernel
+// before this one is.
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_blocks(
+    uint64_t *__restrict__ pairs, uint64_t nblocks, int rewrite,
+    ckpt_counts_t *__restrict__ counts, const unsigned long long *publish_src,
+    unsigned long long *publish_dst) {
   Pair carry = {0, 0};
   for (uint64_t base = 0; base < nblocks; base += SCAN_THREADS) {
     const uint64_t b = base + threadIdx.x;
@@ -129,34 +117,15 @@ __device__ void scan_pairs(uint64_t *pairs, uint64_t nblocks, bool rewrite, ckpt
     counts->ndirty = carry.cnt;
     counts->staged_bytes = carry.bytes;
     counts->overflow = 0;
-    if (publish_dst != nullptr)
-      *publish_dst = publish_src != nullptr ? *reinterpret_cast<const volatile unsigned long long *>(publish_src)
-                                            : 0ull;
+    if (publish_dst != nullptr) *publish_dst = publish_src != nullptr ? *publish_src : 0ull;
   }
 }
 
-// Tail of every kernel that produces block pairs: store, ticket, and in the
-// last workgroup the scan over all of them.
-__device__ void finish_pairs(uint64_t *scratch, Pair total, bool rewrite, ckpt_counts_t *counts,
-                             const unsigned long long *publish_src,
-                             unsigned long long *publish_dst) {
-  uint64_t *pairs = block_pairs(scratch);
-  if (threadIdx.x == 0) {
-    pairs[2 * (uint64_t)blockIdx.x] = total.cnt;
-    pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
-  }
-  if (arrived_last(scratch)) {
-    scan_pairs(pairs, gridDim.x, rewrite, counts, publish_src, publish_dst);
-    reset_ticket(scratch);
-  }
-}
-
-// mask[k] = (ref == nullptr || dig[k] != ref[k]); counts = totals over the mask.
+// mask[k] = (ref == nullptr || dig[k] != ref[k]); per-workgroup sums of the marked chunks.
 __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t *__restrict__ dig,
                                                        const uint64_t *__restrict__ ref,
                                                        uint8_t *__restrict__ mask,
-                                                       uint64_t *__restrict__ scratch,
-                                                       ckpt_counts_t *__restrict__ counts) {
+                                                       uint64_t *__restrict__ pairs) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
@@ -171,7 +140,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t
   ChunkRef refs[SCAN_PER_THREAD];
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
-  finish_pairs(scratch, total, false, counts, nullptr, nullptr);
+  store_block_pair(pairs, total);
 }
 
 // Cross-worker upload ownership (sec. 4.6): gathered holds `world` rows of N
@@ -180,7 +149,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_diff(PlanDev p, const uint64_t
 // A thread reads `world` values per chunk, each row access coalesced over k.
 __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
     PlanDev p, const uint64_t *__restrict__ gathered, uint32_t world, uint32_t rank,
-    uint8_t *__restrict__ mask, uint64_t *__restrict__ scratch, ckpt_counts_t *__restrict__ counts) {
+    uint8_t *__restrict__ mask, uint64_t *__restrict__ pairs) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
@@ -202,19 +171,18 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_upload_owners(
   ChunkRef refs[SCAN_PER_THREAD];
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
-  finish_pairs(scratch, total, false, counts, nullptr, nullptr);
+  store_block_pair(pairs, total);
 }
 
-// Block pairs of a caller-supplied mask (any non-zero byte marks a chunk), then
-// their exclusive prefix sums and the totals.
+// Per-workgroup sums for a caller-supplied mask (any non-zero byte marks a chunk).
 // Fused snapshot, first use (the hint): the mask is also copied to `keep`, and
 // the snapshot's counters zero_me[0 .. SNAPSHOT_COUNTERS) are cleared.  Second
 // use (the real mask): chunks whose mask differs from `hint` are added to
-// *misses, and *misses_out receives the sum once every workgroup has added.
+// *misses (k_scan_blocks publishes the sum).
 __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(
-    PlanDev p, const uint8_t *__restrict__ mask, uint64_t *__restrict__ scratch,
-    ckpt_counts_t *__restrict__ counts, uint8_t *__restrict__ keep, unsigned long long *zero_me,
-    const uint8_t *__restrict__ hint, unsigned long long *misses, unsigned long long *misses_out) {
+    PlanDev p, const uint8_t *__restrict__ mask, uint64_t *__restrict__ pairs,
+    uint8_t *__restrict__ keep, unsigned long long *zero_me, const uint8_t *__restrict__ hint,
+    unsigned long long *misses) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   int n = 0;
@@ -238,7 +206,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_block_sums(
   ChunkRef refs[SCAN_PER_THREAD];
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   block_exclusive_scan(mine, &total);
-  finish_pairs(scratch, total, true, counts, misses, misses_out);
+  store_block_pair(pairs, total);
 }
 
 // Sum over the workgroup of one pair per thread, returned in every thread.
@@ -289,57 +257,33 @@ __device__ Pair pair_before(const PlanDev &p, const uint8_t *__restrict__ mask, 
   return r;
 }
 
-// What one workgroup of the one-kernel paths hands to the last one: marked
-// chunks, entries that missed a capacity, hint misses and entries left for the
-// gather in its block (each at most SCAN_BLOCK, 16 bits apiece) in one word,
-// padded bytes in the other.  misses (fused snapshot): word 0 receives the hint
-// misses, word 3 the entries left for the gather.
-__device__ void finish_small(uint64_t *scratch, Pair total, uint32_t missed, uint32_t bad,
-                             uint32_t todo, ckpt_counts_t *counts, unsigned long long *misses,
+// End of the one-kernel manifest path.  The last workgroup's offset plus its own sum are the
+// totals.  Entries that missed a capacity, hint misses and entries left for the gather are
+// added to their counters by whichever workgroups have any: those words (counts->overflow,
+// misses[0], misses[3], *misses_out) were cleared by an earlier kernel of the same call.
+__device__ void finish_small(Pair before, Pair total, uint32_t missed, uint32_t bad, uint32_t todo,
+                             ckpt_counts_t *counts, unsigned long long *misses,
                              unsigned long long *misses_out) {
-  uint64_t *pairs = block_pairs(scratch);
   // the three small counts share one reduction: 16-bit fields, none can exceed SCAN_BLOCK
   const uint64_t small =
       block_sum(Pair{(uint64_t)missed | ((uint64_t)bad << 16) | ((uint64_t)todo << 32), 0}).cnt;
-  if (threadIdx.x == 0) {
-    pairs[2 * (uint64_t)blockIdx.x] = total.cnt | (small << 16);
-    pairs[2 * (uint64_t)blockIdx.x + 1] = total.bytes;
+  if (threadIdx.x != 0) return;
+  if (blockIdx.x == gridDim.x - 1) {
+    counts->ndirty = before.cnt + total.cnt;
+    counts->staged_bytes = before.bytes + total.bytes;
   }
-  if (arrived_last(scratch)) {
-    uint64_t cnt = 0, bytes = 0, over = 0, wrong = 0, left = 0;
-    for (uint64_t b = threadIdx.x; b < gridDim.x; b += SCAN_THREADS) {
-      const uint64_t w = pairs[2 * b];
-      cnt += w & 0xFFFF;
-      over += (w >> 16) & 0xFFFF;
-      wrong += (w >> 32) & 0xFFFF;
-      left += w >> 48;
-      bytes += pairs[2 * b + 1];
-    }
-    const Pair a = block_sum(Pair{cnt, bytes}), b = block_sum(Pair{over, wrong});
-    cnt = a.cnt;
-    bytes = a.bytes;
-    over = b.cnt;
-    wrong = b.bytes;
-    left = block_sum(Pair{left, 0}).cnt;
-    if (threadIdx.x == 0) {
-      counts->ndirty = cnt;
-      counts->staged_bytes = bytes;
-      counts->overflow = over;
-      if (misses != nullptr) {
-        misses[0] = wrong;
-        misses[3] = left;
-      }
-      if (misses_out != nullptr) *misses_out = wrong;
-    }
-    reset_ticket(scratch);
-  }
+  const unsigned long long over = small & 0xFFFF, wrong = (small >> 16) & 0xFFFF, left = small >> 32;
+  if (over) atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow), over);
+  if (wrong && misses != nullptr) atomicAdd(misses, wrong);
+  if (wrong && misses_out != nullptr) atomicAdd(misses_out, wrong);
+  if (left && misses != nullptr) atomicAdd(misses + 3, left);
 }
 
 // Final pass: every marked chunk learns its entry index and staging offset and
-// writes its manifest entry.  !SMALL: scratch holds the exclusive block sums,
-// counts the totals; entries that miss a capacity are added to
-// counts->overflow.  SMALL: the workgroup computes its own offset
-// (pair_before), and the last workgroup writes the counts.
+// writes its manifest entry.  !SMALL: `pairs` holds the exclusive block sums and
+// counts the totals (k_scan_blocks).  SMALL: the workgroup computes its own
+// offset (pair_before), the last one writes the totals.  Either way entries that
+// miss a capacity are added to counts->overflow, which an earlier kernel cleared.
 // Fused snapshot (hint, hoff, need not null): entry e gets need[e] = 0 if the
 // fingerprint pass has already staged the chunk at this very offset (it was
 // hinted, its hinted offset equals the real one, and it fitted), else 1 -- the
@@ -348,7 +292,7 @@ __device__ void finish_small(uint64_t *scratch, Pair total, uint32_t missed, uin
 template <bool SMALL>
 __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
     PlanDev p, const uint8_t *__restrict__ mask, const uint64_t *__restrict__ dig,
-    uint64_t *__restrict__ scratch, ckpt_entry_t *__restrict__ manifest, uint64_t manifest_cap,
+    const uint64_t *__restrict__ pairs, ckpt_entry_t *__restrict__ manifest, uint64_t manifest_cap,
     uint64_t staging_cap, ckpt_counts_t *__restrict__ counts, const uint8_t *__restrict__ hint,
     const uint64_t *__restrict__ hoff, uint8_t *__restrict__ need, unsigned long long *misses,
     unsigned long long *misses_out) {
@@ -381,8 +325,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
   if (SMALL) {
     before = pair_before(p, mask, (uint64_t)blockIdx.x * SCAN_BLOCK);
   } else {
-    const uint64_t *blockoff = block_pairs(scratch);
-    before = {blockoff[2 * (uint64_t)blockIdx.x], blockoff[2 * (uint64_t)blockIdx.x + 1]};
+    before = {pairs[2 * (uint64_t)blockIdx.x], pairs[2 * (uint64_t)blockIdx.x + 1]};
   }
   pos = pos + before;
   uint32_t missed = 0, todo = 0;
@@ -411,7 +354,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
     pos.bytes += padded;
   }
   if (SMALL) {
-    finish_small(scratch, total, missed, bad, todo, counts, misses, misses_out);
+    finish_small(before, total, missed, bad, todo, counts, misses, misses_out);
   } else {
     if (missed)
       atomicAdd(reinterpret_cast<unsigned long long *>(&counts->overflow), (unsigned long long)missed);
@@ -429,9 +372,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_emit_manifest(
 // counters; otherwise k_block_sums has done those and left the block offsets.
 template <bool SMALL>
 __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(
-    PlanDev p, const uint8_t *__restrict__ hint, const uint64_t *__restrict__ scratch,
+    PlanDev p, const uint8_t *__restrict__ hint, const uint64_t *__restrict__ pairs,
     uint64_t manifest_cap, uint64_t *__restrict__ hoff, uint8_t *__restrict__ keep,
-    unsigned long long *zero_me) {
+    unsigned long long *zero_me, unsigned long long *zero_a, unsigned long long *zero_b) {
   const uint64_t k0 = thread_first_chunk();
   uint8_t m[SCAN_PER_THREAD];
   ChunkRef refs[SCAN_PER_THREAD];
@@ -445,15 +388,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(
       n = i + 1;
     }
   }
-  if (SMALL && blockIdx.x == 0 && threadIdx.x < SNAPSHOT_COUNTERS) zero_me[threadIdx.x] = 0;
+  if (SMALL && blockIdx.x == 0) {
+    // everything the manifest kernel later adds to starts at zero
+    if (threadIdx.x < SNAPSHOT_COUNTERS) zero_me[threadIdx.x] = 0;
+    if (threadIdx.x == 0 && zero_a != nullptr) *zero_a = 0;
+    if (threadIdx.x == 0 && zero_b != nullptr) *zero_b = 0;
+  }
   Pair mine = sum_marked(p, k0, m, n, refs), total;
   Pair pos = block_exclusive_scan(mine, &total);
   Pair before;
   if (SMALL) {
     before = pair_before(p, hint, (uint64_t)blockIdx.x * SCAN_BLOCK);
   } else {
-    const uint64_t *blockoff = scratch + SCRATCH_HEAD;
-    before = {blockoff[2 * (uint64_t)blockIdx.x], blockoff[2 * (uint64_t)blockIdx.x + 1]};
+    before = {pairs[2 * (uint64_t)blockIdx.x], pairs[2 * (uint64_t)blockIdx.x + 1]};
   }
   pos = pos + before;
   for (int i = 0; i < n; ++i) {
@@ -466,11 +413,12 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_hint_offsets(
   }
 }
 
-// No chunks at all: the counts (and the miss counters) are still written.
-__global__ void k_empty_counts(ckpt_counts_t *counts, unsigned long long *misses,
+// Zero counts and miss counters: what a call over no chunks reports, and the cleared state the
+// one-kernel manifest path adds to when no earlier kernel of the call could do the clearing.
+__global__ void k_clear_counts(ckpt_counts_t *counts, unsigned long long *misses,
                                unsigned long long *misses_out) {
   counts->ndirty = counts->staged_bytes = counts->overflow = 0;
-  if (misses != nullptr) *misses = 0;
+  if (misses != nullptr) misses[0] = misses[3] = 0;
   if (misses_out != nullptr) *misses_out = 0;
 }
 
@@ -527,38 +475,37 @@ typedef unsigned long long ull;
 }  // namespace
 
 hipError_t launch_diff(const PlanDev &p, const uint64_t *d_dig, const uint64_t *d_ref,
-                       uint8_t *d_mask, uint64_t *d_scratch, ckpt_counts_t *d_counts,
-                       hipStream_t s) {
+                       uint8_t *d_mask, uint64_t *d_pairs, ckpt_counts_t *d_counts, hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_diff, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_dig, d_ref, d_mask,
-                       d_scratch, d_counts);
-  else
-    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, (ull *)nullptr,
-                       (ull *)nullptr);
+                       d_pairs);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_pairs, (uint64_t)nblocks, 0,
+                     d_counts, (const ull *)nullptr, (ull *)nullptr);
   return hipGetLastError();
 }
 
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
-                                uint32_t rank, uint8_t *d_mask, uint64_t *d_scratch,
+                                uint32_t rank, uint8_t *d_mask, uint64_t *d_pairs,
                                 ckpt_counts_t *d_counts, hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   if (nblocks)
     hipLaunchKernelGGL(k_upload_owners, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_gathered,
-                       world, rank, d_mask, d_scratch, d_counts);
-  else
-    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, (ull *)nullptr,
-                       (ull *)nullptr);
+                       world, rank, d_mask, d_pairs);
+  hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_pairs, (uint64_t)nblocks, 0,
+                     d_counts, (const ull *)nullptr, (ull *)nullptr);
   return hipGetLastError();
 }
 
 // The metadata half of compact for a given mask: one kernel up to SMALL_SCAN_CHUNKS chunks,
-// two above.  With h (fused snapshot) the hint misses are counted and the entries the pass has
-// already staged are marked in h->need.
+// three above.  With h (fused snapshot) the hint misses are counted and the entries the pass has
+// already staged are marked in h->need.  cleared: an earlier kernel of the same call has zeroed
+// d_counts->overflow, *d_misses_out and h's counters (see launch_hint_offsets and the
+// fingerprint pass); otherwise the one-kernel path clears them with a kernel of its own.
 hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const uint64_t *d_dig,
                                uint64_t staging_cap, ckpt_entry_t *d_manifest,
-                               uint64_t manifest_cap, uint64_t *d_scratch,
-                               ckpt_counts_t *d_counts, const HintState *h, uint64_t *d_misses_out,
+                               uint64_t manifest_cap, uint64_t *d_pairs, ckpt_counts_t *d_counts,
+                               const HintState *h, uint64_t *d_misses_out, bool cleared,
                                hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   const uint8_t *hint = h ? h->copy : nullptr;
@@ -567,39 +514,47 @@ hipError_t launch_compact_scan(const PlanDev &p, const uint8_t *d_mask, const ui
   ull *misses = h ? reinterpret_cast<ull *>(h->misses) : nullptr;
   ull *misses_out = reinterpret_cast<ull *>(d_misses_out);
   if (nblocks == 0) {
-    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_counts, misses, misses_out);
+    hipLaunchKernelGGL(k_clear_counts, dim3(1), dim3(1), 0, s, d_counts, misses, misses_out);
   } else if (p.nchunks <= SMALL_SCAN_CHUNKS) {
+    if (!cleared)
+      hipLaunchKernelGGL(k_clear_counts, dim3(1), dim3(1), 0, s, d_counts, misses, misses_out);
     hipLaunchKernelGGL(k_emit_manifest<true>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
-                       d_dig, d_scratch, d_manifest, manifest_cap, staging_cap, d_counts, hint, hoff,
-                       need, misses, misses_out);
+                       d_dig, (const uint64_t *)nullptr, d_manifest, manifest_cap, staging_cap,
+                       d_counts, hint, hoff, need, misses, misses_out);
   } else {
-    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_scratch,
-                       d_counts, (uint8_t *)nullptr, (ull *)nullptr, hint, misses, misses_out);
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_pairs,
+                       (uint8_t *)nullptr, (ull *)nullptr, hint, misses);
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_pairs, (uint64_t)nblocks,
+                       1, d_counts, (const ull *)misses, misses_out);
     hipLaunchKernelGGL(k_emit_manifest<false>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask,
-                       d_dig, d_scratch, d_manifest, manifest_cap, staging_cap, d_counts, hint, hoff,
-                       need, misses, (ull *)nullptr);
+                       d_dig, (const uint64_t *)d_pairs, d_manifest, manifest_cap, staging_cap,
+                       d_counts, hint, hoff, need, misses, (ull *)nullptr);
   }
   return hipGetLastError();
 }
 
-// Staging offsets of the hinted chunks, the private copy of the hint, cleared counters.
+// Staging offsets of the hinted chunks, the private copy of the hint, cleared counters; in the
+// one-kernel shape also d_counts->overflow and *d_misses_out, for the manifest kernel to add to.
 hipError_t launch_hint_offsets(const PlanDev &p, const uint8_t *d_hint_in, const HintState &h,
-                               uint64_t *d_scratch, ckpt_counts_t *d_tmp_counts,
-                               uint64_t manifest_cap, hipStream_t s) {
+                               uint64_t *d_pairs, ckpt_counts_t *d_tmp_counts, uint64_t manifest_cap,
+                               ckpt_counts_t *d_counts, uint64_t *d_misses_out, hipStream_t s) {
   const uint32_t nblocks = scan_blocks(p.nchunks);
   ull *zero_me = reinterpret_cast<ull *>(h.misses);
   if (nblocks == 0) {
-    hipLaunchKernelGGL(k_empty_counts, dim3(1), dim3(1), 0, s, d_tmp_counts, zero_me, (ull *)nullptr);
+    hipLaunchKernelGGL(k_clear_counts, dim3(1), dim3(1), 0, s, d_tmp_counts, zero_me, (ull *)nullptr);
   } else if (p.nchunks <= SMALL_SCAN_CHUNKS) {
     hipLaunchKernelGGL(k_hint_offsets<true>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in,
-                       (const uint64_t *)nullptr, manifest_cap, h.hoff, h.copy, zero_me);
+                       (const uint64_t *)nullptr, manifest_cap, h.hoff, h.copy, zero_me,
+                       reinterpret_cast<ull *>(&d_counts->overflow),
+                       reinterpret_cast<ull *>(d_misses_out));
   } else {
-    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in,
-                       d_scratch, d_tmp_counts, h.copy, zero_me, (const uint8_t *)nullptr,
-                       (ull *)nullptr, (ull *)nullptr);
+    hipLaunchKernelGGL(k_block_sums, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_hint_in, d_pairs,
+                       h.copy, zero_me, (const uint8_t *)nullptr, (ull *)nullptr);
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(SCAN_THREADS), 0, s, d_pairs, (uint64_t)nblocks,
+                       1, d_tmp_counts, (const ull *)nullptr, (ull *)nullptr);
     hipLaunchKernelGGL(k_hint_offsets<false>, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p,
-                       (const uint8_t *)h.copy, (const uint64_t *)d_scratch, manifest_cap, h.hoff,
-                       (uint8_t *)nullptr, (ull *)nullptr);
+                       (const uint8_t *)h.copy, (const uint64_t *)d_pairs, manifest_cap, h.hoff,
+                       (uint8_t *)nullptr, (ull *)nullptr, (ull *)nullptr, (ull *)nullptr);
   }
   return hipGetLastError();
 }

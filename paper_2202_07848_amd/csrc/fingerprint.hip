@@ -176,6 +176,8 @@ struct StageArgs {
   // written by the lane that finishes the digest (mask null: not wanted)
   const uint64_t *ref;
   uint8_t *mask;
+  // words the first workgroup clears for the kernels that follow the pass (each may be null)
+  unsigned long long *clear_a, *clear_b;
 };
 
 // Slot `lane` of group `group`: the chunk's address, global id and length (0: empty slot).
@@ -302,6 +304,10 @@ __global__ __launch_bounds__(64) void k_fingerprint(PlanDev p, uint64_t *__restr
 
   const int lane = threadIdx.x;
   uint64_t group = blockIdx.x;
+  if (blockIdx.x == 0 && lane == 0) {
+    if (st.clear_a != nullptr) *st.clear_a = 0;
+    if (st.clear_b != nullptr) *st.clear_b = 0;
+  }
   if (MODE == MODE_STAGING) {
     if (group >= st.counts[0]) return;                   // one wavefront: uniform for the workgroup
     group = st.list[group];
@@ -432,18 +438,22 @@ hipError_t launch_fingerprint(const PlanDev &p, uint64_t *d_digests, hipStream_t
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_fingerprint<MODE_PLAIN>, dim3((uint32_t)groups), dim3(64), 0, s, p,
                      d_digests,
-                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr});
+                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, nullptr, nullptr,
+                               nullptr, nullptr});
   return hipGetLastError();
 }
 
 hipError_t launch_fingerprint_diff(const PlanDev &p, uint64_t *d_digests, const uint64_t *d_ref,
-                                   uint8_t *d_mask, hipStream_t s) {
+                                   uint8_t *d_mask, ckpt_counts_t *d_counts, uint64_t *d_misses_out,
+                                   hipStream_t s) {
   if (p.nchunks == 0) return hipSuccess;
   const uint64_t groups = fingerprint_groups(p);
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_fingerprint<MODE_PLAIN>, dim3((uint32_t)groups), dim3(64), 0, s, p,
                      d_digests,
-                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, d_ref, d_mask});
+                     StageArgs{nullptr, nullptr, nullptr, 0, nullptr, nullptr, 0, d_ref, d_mask,
+                               reinterpret_cast<unsigned long long *>(&d_counts->overflow),
+                               reinterpret_cast<unsigned long long *>(d_misses_out)});
   return hipGetLastError();
 }
 
@@ -460,7 +470,7 @@ hipError_t launch_fingerprint_staging(const PlanDev &p, uint64_t *d_digests, con
   if (groups > 0x7FFFFFFFull) return hipErrorInvalidValue;
   unsigned long long *counts = reinterpret_cast<unsigned long long *>(d_list_counts);
   const StageArgs st{d_hint, d_hint_off, reinterpret_cast<uint8_t *>(d_staging), staging_cap,
-                     d_list,  counts,    (uint32_t)groups, d_ref, d_mask};
+                     d_list,  counts,    (uint32_t)groups, d_ref, d_mask, nullptr, nullptr};
   if (!split) {
     hipLaunchKernelGGL(k_fingerprint<MODE_MIXED>, dim3((uint32_t)groups), dim3(64), 0, s, p,
                        d_digests, st);

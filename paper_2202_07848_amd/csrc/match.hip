@@ -322,7 +322,7 @@ hipError_t launch_moves_inplace(const PlanDev &p, const int64_t *d_src, void *d_
   if (groups) hipLaunchKernelGGL(k_mark_moves, dim3(groups), dim3(256), 0, s, d_src, n, moved);
   // the manifest scan, with src[k] travelling in the digest field of each entry
   hipError_t e = launch_compact_scan(p, moved, reinterpret_cast<const uint64_t *>(d_src), temp_cap,
-                                     moves, n, d_blocksums, d_counts, nullptr, nullptr, s);
+                                     moves, n, d_blocksums, d_counts, nullptr, nullptr, false, s);
   if (e != hipSuccess || n == 0) return e;
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
   const uint64_t items = n << (p.chunk_log2 - piece_log2);

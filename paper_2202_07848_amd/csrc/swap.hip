@@ -86,7 +86,7 @@ int ckpt_swap_out(ckpt_swapper_t *sw, const ckpt_plan_t *plan, const uint8_t *d_
   // metadata: offsets and manifest; no staging capacity applies on the device
   hipError_t e = ckpt::launch_compact_scan(p, d_mask, d_digests, ~0ull, d_manifest, manifest_cap,
                                            ckpt::plan_scratch(plan), sw->d_counts, nullptr, nullptr,
-                                           s);
+                                           false, s);
   if (e == hipSuccess)
     e = hipMemcpyAsync(h_counts, sw->d_counts, sizeof(ckpt_counts_t), hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);

@@ -14,7 +14,9 @@ state); `ref_digests` are the base's checksums.  A switch
 
 is enqueued on one stream without the host reading any result (the entry count
 of the swap-in is read on the device), so the incoming rank's first kernel can
-be dispatched at once behind an event (sec. 6).
+be dispatched at once behind an event (sec. 6).  Since both deltas normally
+cover the same chunks, the two halves run as one exchange pass that keeps both
+directions of the host link busy (``ckpt_exchange``).
 
 Precondition, as in the paper's setting: the chunks in which a rank differs from
 the base are the same set for every rank (its gradients and activations), so
@@ -38,6 +40,7 @@ class TimeSlicedRanks:
         n = plan.nchunks
         self.digests = torch.zeros(max(1, n), dtype=torch.int64, device=device)
         self.rejected = torch.zeros(1, dtype=torch.int64, device=device)
+        self.serial = torch.zeros(1, dtype=torch.int64, device=device)   # last switch: 0 = one pass
         # per rank: delta bytes in pinned host memory, manifest / mask / counts on the device
         self.host: List = [torch.empty(max(16, staging_cap), dtype=torch.uint8, pin_memory=True)
                            for _ in range(nranks)]
@@ -61,10 +64,27 @@ class TimeSlicedRanks:
         ck.restore_counted(self.plan, self.host[rank], self.staging_cap, self.manifest[rank],
                            self.manifest_cap, self.counts[rank], self.rejected, stream=stream)
 
-    def switch(self, outgoing: int, incoming: int, stream=None) -> None:
-        """Enqueue one context switch; nothing is read on the host."""
-        self.swap_out(outgoing, stream)
-        self.swap_in(incoming, stream)
+    def switch(self, outgoing: int, incoming: int, stream=None, exchange: bool = True) -> None:
+        """Enqueue one context switch; nothing is read on the host.
+
+        exchange=True: checksums, comparison and manifest of the outgoing rank, then
+        ``ckpt_exchange``: where both ranks' deltas cover the same chunks (the usual case) every
+        chunk is swapped out and in by one pass, both directions of the host link busy at once;
+        otherwise the library falls back, on the device, to swap-out followed by swap-in.
+        exchange=False: swap-out, then swap-in."""
+        if not exchange:
+            self.swap_out(outgoing, stream)
+            self.swap_in(incoming, stream)
+            return
+        ck.fingerprint(self.plan, self.digests, stream)
+        ck.diff(self.plan, self.digests, self.ref, self.mask[outgoing], self.counts[outgoing],
+                stream)
+        ck.manifest(self.plan, self.mask[outgoing], self.digests, self.manifest[outgoing],
+                    self.counts[outgoing], self.staging_cap, self.manifest_cap, stream)
+        ck.exchange(self.plan, self.manifest[outgoing], self.counts[outgoing], self.host[outgoing],
+                    self.staging_cap, self.manifest[incoming], self.counts[incoming],
+                    self.host[incoming], self.staging_cap, self.manifest_cap, self.serial,
+                    self.rejected, stream)
 
     def same_dirty_set(self, ranks: Optional[List[int]] = None) -> bool:
         """True if the given ranks (default: all) differ from the base in the same chunks."""

@@ -64,8 +64,9 @@ def check_rank_area(sw, o, r):
     assert np.array_equal(ck.manifest_to_numpy(sw.manifest[r], want["ndirty"]), o.manifest[r])
 
 
+@pytest.mark.parametrize("exchange", [True, False], ids=["exchange_pass", "out_then_in"])
 @pytest.mark.parametrize("sync_every_switch", [True, False], ids=["checked_each_switch", "eager"])
-def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch):
+def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch, exchange):
     w = wl.config(4, 8)
     base = wl.numpy_replica(w, 0)
     ranks = [wl.numpy_replica(w, r) for r in range(1, NRANKS + 1)]
@@ -97,7 +98,7 @@ def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch):
     for step in range(2 * NRANKS):                          # two full rotations
         run_a_mini_batch(w, rng, o, dev)
         nxt = (resident + 1) % NRANKS
-        sw.switch(resident, nxt)
+        sw.switch(resident, nxt, exchange=exchange)
         o.switch(resident, nxt)
         # the incoming rank's first kernel, dispatched at once on another stream behind an event
         done = torch.cuda.Event()
@@ -108,6 +109,7 @@ def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch):
         if sync_every_switch:
             torch.cuda.synchronize()
             assert int(sw.rejected.item()) == 0
+            assert int(sw.serial.item()) == 0          # the deltas line up: one exchange pass
             check_rank_area(sw, o, resident)
             got, img = dev.host()
             assert all(np.array_equal(g, want) for g, want in zip(got, o.image)), step
@@ -124,3 +126,47 @@ def test_round_robin_of_four_ranks_matches_the_oracle(sync_every_switch):
     assert sw.same_dirty_set()
     # what is resident is rank 0 as it was when it was swapped out last, not the base
     assert not all(np.array_equal(g, b) for g, b in zip(got, base))
+
+
+def test_exchange_falls_back_to_out_then_in_when_the_deltas_do_not_line_up():
+    """A rank that also changed a chunk of shared state has one entry more than the rank that
+    comes in: ckpt_exchange notices on the device and does swap-out, then swap-in; the result is
+    what the oracle's compact followed by restore gives (that the incoming rank then sees the
+    changed shared chunk is the caller's business, and the oracle's rotation sees it too)."""
+    w = wl.config(4, 12)
+    base = wl.numpy_replica(w, 0)
+    ranks = [wl.numpy_replica(w, r) for r in (1, 2)]
+    dev = DeviceBuffers(ranks[0], w.chunk)
+    o = OracleRanks(w, base, ranks[0])
+    n = dev.plan.nchunks
+    ref = torch.from_numpy(o.ref.view(np.int64)).cuda()
+    cap_bytes, cap_entries = w.nbytes + 16 * n, n
+    sw = TimeSlicedRanks(dev.plan, ref, 2, cap_bytes, cap_entries)
+    tmp = DeviceBuffers(ranks[1], w.chunk)
+    one = TimeSlicedRanks(tmp.plan, ref, 1, cap_bytes, cap_entries)
+    one.swap_out(0)
+    torch.cuda.synchronize()
+    for name in ("host", "manifest", "counts", "mask"):
+        getattr(sw, name)[1].copy_(getattr(one, name)[0])
+    o.staging[1], o.manifest[1], o.counts[1] = o.delta_of(ranks[1])
+    # the resident rank touches a shared buffer (an early one, so every later entry shifts)
+    shared = next(i for i, b in enumerate(w.bufs) if b.shared and b.nbytes >= w.chunk)
+    o.image[shared][5] ^= 0x40
+    dev.arena[dev.offs[shared] + 5] ^= 0x40
+    for exchange in (True, False):
+        sw.switch(0, 1, exchange=exchange)
+        o.switch(0, 1)
+        torch.cuda.synchronize()
+        assert int(sw.rejected.item()) == 0
+        if exchange:
+            assert int(sw.serial.item()) > 0
+        check_rank_area(sw, o, 0)
+        got, img = dev.host()
+        assert all(np.array_equal(g, want) for g, want in zip(got, o.image))
+        assert dev.canaries_intact(img)
+        sw.switch(1, 0, exchange=exchange)                 # and back, again with one entry more
+        o.switch(1, 0)
+        torch.cuda.synchronize()
+        check_rank_area(sw, o, 1)
+        got, img = dev.host()
+        assert all(np.array_equal(g, want) for g, want in zip(got, o.image))

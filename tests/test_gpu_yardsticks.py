@@ -65,3 +65,20 @@ def test_alu_probe_runs_the_xxh64_accumulator_step():
     with pytest.raises(ck.CkptError):
         ck.alu_xxh64(8, None)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("nstreams,stream_bytes", [(16, 512), (48, 4096), (32, 1 << 20)])
+def test_bw_streams_copies_every_stream_and_nothing_else(nstreams, stream_bytes):
+    n = nstreams * stream_bytes
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.full((n + 4096,), 0x6B, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4096, dtype=torch.int64, device="cuda")
+    ck.bw_streams(dst, src, nstreams, stream_bytes, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and bool((dst[n:] == 0x6B).all())
+    ck.bw_streams(None, src, nstreams, stream_bytes, sink)        # read only
+    torch.cuda.synchronize()
+    for bad in ((15, stream_bytes), (nstreams, stream_bytes + 256), (nstreams, 0)):
+        with pytest.raises(ck.CkptError) as e:
+            ck.bw_streams(dst, src, bad[0], bad[1], sink)
+        assert e.value.status == -1
