@@ -430,6 +430,82 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
     }
 
 
+def probe_leg(w, rep, ref, staging, staged, ndirty, ck, torch, np, args):
+    """The measurements the design notes lean on, each through the C ABI so that they can be
+    repeated from this file: (a) the hinted snapshot pass as one launch against two (staging
+    groups first, then the rest); (b) copy and read rates of plain streaming kernels against
+    the fingerprint pass's access pattern (16 streams per wavefront, 256 bytes of each per
+    step), on as many streams of one chunk's size as the snapshot stages chunks; (c) the plain
+    fingerprint over one large buffer for chunk sizes from 256 B to 64 MiB."""
+    dev = rep.arena.device
+    ev = torch.cuda.Event
+    n = w.nchunks
+
+    def timed(fn, reps=5):
+        fn()
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    # (a) one launch against two
+    dig = torch.zeros(n, dtype=torch.int64, device=dev)
+    mask = torch.zeros(n, dtype=torch.uint8, device=dev)
+    cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+    ws = torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    manifest = torch.empty(max(1, ndirty) * 32, dtype=torch.uint8, device=dev)
+    ck.fingerprint(rep.plan, dig)
+    ck.diff(rep.plan, dig, ref, mask, cnt)
+    hint = mask.clone()
+    before = rep.plan.split_threshold
+    shapes = {}
+    for name, thr in (("one_launch", 2**64 - 1), ("two_launches", 0)):
+        rep.plan.split_threshold = thr
+        shapes[name + "_ms"] = round(timed(lambda: ck.snapshot(
+            rep.plan, ref, hint, dig, mask, staging, manifest, cnt, None, ws,
+            staging_cap=staged, manifest_cap=ndirty)), 4)
+    rep.plan.split_threshold = before
+    out["hinted_pass_launch_shape"] = shapes
+
+    # (b) access patterns; the copy goes from the replica's arena into the staging buffer
+    stream_bytes = max(512, w.chunk)
+    nstreams = min(staged, rep.arena.numel()) // stream_bytes // 16 * 16
+    if nstreams:
+        nb = nstreams * stream_bytes
+        sink = torch.zeros(4096, dtype=torch.int64, device=dev)
+        pat = {"bytes": nb, "streams": nstreams, "stream_bytes": stream_bytes}
+        for name, fn, factor in (
+                ("sweep_copy", lambda: ck.bw_copy(staging, rep.arena, nb), 2),
+                ("stream_copy", lambda: ck.bw_streams(staging, rep.arena, nstreams, stream_bytes,
+                                                      sink), 2),
+                ("sweep_read", lambda: ck.bw_read(rep.arena, nb, sink), 1),
+                ("stream_read", lambda: ck.bw_streams(None, rep.arena, nstreams, stream_bytes,
+                                                      sink), 1)):
+            ms = timed(fn)
+            pat[name] = {"ms": round(ms, 4), "GBps_read_plus_write": round(factor * nb / ms / 1e6, 1)}
+        out["access_patterns"] = pat
+
+    # (c) chunk size against parallelism: one buffer, every chunk size
+    big = min(rep.arena.numel(), 24 << 30) // (64 << 20) * (64 << 20)
+    if big:
+        sweep = {}
+        base = rep.arena.data_ptr()
+        for log2 in (8, 10, 12, 14, 16, 18, 20, 22, 24, 26):
+            c = 1 << log2
+            plan = ck.Plan([(base, big)], c)
+            d = torch.zeros(plan.nchunks, dtype=torch.int64, device=dev)
+            ms = timed(lambda: ck.fingerprint(plan, d), reps=3)
+            sweep[str(c)] = {"chunks": plan.nchunks, "ms": round(ms, 3),
+                             "GBps": round(big / ms / 1e6, 1)}
+            plan.close()
+        out["fingerprint_chunk_size_sweep"] = {"buffer_bytes": big, "by_chunk_bytes": sweep}
+    return out
+
+
 def phase_names(d, fused):
     """With the fused call there is one snapshot phase instead of three."""
     if not fused:

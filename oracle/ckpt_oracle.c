@@ -10,7 +10,7 @@
  *     here at the granularity of fixed-size chunks inside each buffer, with
  *     XXH64 (seed 0) as the checksum function -- the paper names none;
  *   - a comparison of those checksums with another rank's / an earlier
- *     snapshot's checksums (sec. 5.2.1 "same content checksum", sec. 4.6
+ *     snapshot's checksums (sec. 5.2.1 equal checksum = equal content, sec. 4.6
  *     de-dup across workers and across time, sec. 5.2.3 mutation = difference
  *     of checksum state);
  *   - the swap-out of only the non-deduplicated data (sec. 5.2.1), here a

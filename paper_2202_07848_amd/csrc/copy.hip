@@ -20,7 +20,7 @@ namespace ckpt {
 
 namespace {
 
-constexpr int UNROLL = 4;        // streaming yardsticks
+constexpr int UNROLL = 8;        // streaming yardsticks: 16-byte units per lane in flight
 
 // GATHER: buffers -> staging (zero padded to 16).  !GATHER: staging -> buffers
 // (exactly len bytes).  `count_dev`, when not null, supplies the entry count
@@ -92,15 +92,18 @@ __global__ void k_zero_u64(unsigned long long *p) { *p = 0; }
 
 __global__ __launch_bounds__(256) void k_bw_copy(uint4 *__restrict__ dst,
                                                  const uint4 *__restrict__ src, uint64_t n16) {
+  // non-temporal both ways, like every streaming access of the path
+  const uint8_t *s8 = reinterpret_cast<const uint8_t *>(src);
+  uint8_t *d8 = reinterpret_cast<uint8_t *>(dst);
   const uint64_t stride = (uint64_t)gridDim.x * 256 * UNROLL;
   for (uint64_t i = (uint64_t)blockIdx.x * 256 * UNROLL + threadIdx.x; i < n16; i += stride) {
     uint4 v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
-      if (i + u * 256 < n16) v[u] = src[i + u * 256];
+      if (i + u * 256 < n16) v[u] = stream_load16(s8 + 16 * (i + u * 256));
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
-      if (i + u * 256 < n16) dst[i + u * 256] = v[u];
+      if (i + u * 256 < n16) stream_store16(d8 + 16 * (i + u * 256), v[u]);
   }
 }
 
@@ -113,7 +116,8 @@ __global__ __launch_bounds__(256) void k_bw_read(const uint4 *__restrict__ src, 
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       v[u] = make_uint4(0, 0, 0, 0);
-      if (i + u * 256 < n16) v[u] = src[i + u * 256];
+      if (i + u * 256 < n16)
+        v[u] = stream_load16(reinterpret_cast<const uint8_t *>(src) + 16 * (i + u * 256));
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -272,7 +276,7 @@ hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipSt
   const uint64_t n16 = nbytes / 16;
   if (n16 == 0) return hipSuccess;
   uint64_t groups = (n16 + 256 * UNROLL - 1) / (256 * UNROLL);
-  if (groups > 2048) groups = 2048;
+  if (groups > 65536) groups = 65536;   // short-lived workgroups: the copy sweeps memory front to back
   hipLaunchKernelGGL(k_bw_copy, dim3((uint32_t)groups), dim3(256), 0, s,
                      reinterpret_cast<uint4 *>(d_dst), reinterpret_cast<const uint4 *>(d_src), n16);
   return hipGetLastError();

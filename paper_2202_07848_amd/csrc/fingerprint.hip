@@ -1,6 +1,6 @@
 // Fingerprint kernel: one XXH64 (seed 0) per chunk of every live buffer -- the
-// "content checksum of each live buffer" of the Singularity paper (sec. 5.2.1,
-// sec. 6), at chunk granularity.
+// per-buffer content checksums of the Singularity paper (sec. 5.2.1, sec. 6),
+// at chunk granularity.
 //
 // Mapping.  XXH64 offers four independent chains per chunk and nothing more, so
 // a wavefront takes GROUP = 16 chunks of equal (or, for short last chunks,

@@ -2,8 +2,8 @@
 //
 // The Singularity paper looks a checksum up by content (sec. 5.2.1): a buffer
 // whose checksum is already present is not swapped, and if the content sits at
-// another device address it is moved device-to-device, "cheaper than a swap-in
-// from host".  Here the lookup is a hash join on the device: the reference's
+// another device address it is moved device-to-device, which costs less than
+// bringing it in from the host.  Here the lookup is a hash join on the device: the reference's
 // digests go into an open-addressing table (key = digest, value = lowest
 // position that carries it), so do the snapshot's own digests (value = first
 // occurrence), and one probe per snapshot chunk classifies it as same place /

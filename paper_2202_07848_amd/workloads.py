@@ -6,7 +6,8 @@ models are proprietary).  These generators stand in for them: buffer lists with
 the shapes of the paper's memory taxonomy (sec. 5.2.1): parameters P and
 optimizer state O, identical across the data-parallel replicas that share a
 GPU, gradients G and activations A, different per replica -- plus an
-allocator-fragmentation case ("thousands of buffers", sec. 5.2.1).
+allocator-fragmentation case (a rank's state is spread over thousands of
+buffers, sec. 5.2.1).
 
 A workload is a list of ``BufSpec`` (size, value distribution, shared or
 per-replica) and a chunk size.  It can be materialised two ways, both seeded:
