@@ -153,6 +153,10 @@ def host_swap_leg(w, rep, dig, mask, manifest, d_staging, staged, ndirty, ck, to
     the host clock (the calls block until the data has landed).  The host image must equal
     the device staging buffer that ckpt_compact produced for the same mask."""
     host = torch.empty(max(16, staged), dtype=torch.uint8, pin_memory=True)
+    # the device staging buffer is the yardstick below; other legs use it as scratch, so fill it
+    fresh = torch.zeros(3, dtype=torch.int64, device=mask.device)
+    ck.compact(rep.plan, mask, dig, d_staging, manifest, fresh, staging_cap=staged,
+               manifest_cap=ndirty)
     sw = ck.Swapper(slice_bytes)
     t = {}
     for name in ("warm", "timed"):
@@ -815,10 +819,6 @@ def main():
                                          stagings[-1], staged[-1], ndirty[-1], ck, torch,
                                          args.swap_slice_mib << 20)
 
-    if args.probe:
-        out["probe"] = probe_leg(w, pairs[0][1], ref, stagings[0], staged[0], ndirty[0], ck, torch,
-                                 np, args)
-
     if args.switch:
         if w.nreplicas < 4:
             raise SystemExit("--switch needs a configuration with four replicas (--config 4)")
@@ -827,6 +827,10 @@ def main():
     if args.match and w.nreplicas == 1:
         out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,
                                                          np, args.steps)
+
+    if args.probe:        # last of the GPU legs: it uses the staging buffer as a copy target
+        out["probe"] = probe_leg(w, pairs[0][1], ref, stagings[0], staged[0], ndirty[0], ck, torch,
+                                 np, args)
 
     if not args.no_cpu_baseline:
         base, (idx, o_dig, o_mask) = cpu_baseline(w, pairs[0][0], pairs[0][1],
