@@ -258,3 +258,36 @@ def test_random_permutation_inside_one_memory_image(seed):
     got, img = image.host()
     assert all(np.array_equal(g, s) for g, s in zip(got, snap))
     assert image.canaries_intact(img)
+
+
+def test_inplace_move_with_an_impossible_source_leaves_its_destination_alone():
+    """A move whose source is no chunk of the plan, or a chunk of another length, is rejected in
+    both phases: its temporary slot is never filled and its destination keeps its bytes (it used
+    to receive whatever the slot held); the other moves of the same call are carried out."""
+    chunk = 1024
+    rng = np.random.default_rng(77)
+    ref = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in (5 * chunk, 3 * chunk + 100)]
+    image = DeviceBuffers(ref, chunk)
+    n = image.plan.nchunks                                    # 5 + 4 chunks, chunk 8 is short
+    src = np.arange(n, dtype=np.int64)
+    src[0], src[1] = 1, 0                                     # a good swap
+    src[2] = n + 5                                            # no such chunk
+    src[3] = 8                                                # the short chunk: another length
+    src[6] = 4                                                # a good move
+    moved = (src >= 0) & (src != np.arange(n))
+    need = int(moved.sum()) * chunk
+    temp = torch.full((need + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ck.moves_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ck.apply_moves_inplace(image.plan, torch.from_numpy(src).cuda(), temp, ws, counts, rejected,
+                           temp_cap=need)
+    torch.cuda.synchronize()
+    assert int(rejected.item()) == 2
+    want = [b.copy() for b in ref]
+    want[0][0:chunk], want[0][chunk:2 * chunk] = ref[0][chunk:2 * chunk], ref[0][0:chunk]
+    want[1][chunk:2 * chunk] = ref[0][4 * chunk:5 * chunk]    # chunk 6 = buffer 1, second chunk
+    got, img = image.host()
+    for g, w in zip(got, want):                              # chunks 2 and 3 still hold the reference
+        assert np.array_equal(g, w)
+    assert image.canaries_intact(img)
