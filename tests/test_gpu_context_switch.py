@@ -170,3 +170,58 @@ def test_exchange_falls_back_to_out_then_in_when_the_deltas_do_not_line_up():
         check_rank_area(sw, o, 1)
         got, img = dev.host()
         assert all(np.array_equal(g, want) for g, want in zip(got, o.image))
+
+
+def test_switches_replay_from_hip_graphs():
+    """A switch enqueues kernels only, so it can be captured once per (outgoing, incoming) pair
+    and replayed: two ranks ping-pong through two graphs, with mutations of the resident rank and
+    eager synchronisations between replays; every replay is checked against the oracle."""
+    w = wl.config(4, 12)
+    base = wl.numpy_replica(w, 0)
+    ranks = [wl.numpy_replica(w, r) for r in (1, 2)]
+    dev = DeviceBuffers(ranks[0], w.chunk)
+    o = OracleRanks(w, base, ranks[0])
+    n = dev.plan.nchunks
+    ref = torch.from_numpy(o.ref.view(np.int64)).cuda()
+    cap_bytes, cap_entries = w.distinct_bytes + 16 * n, w.distinct_chunks
+    sw = TimeSlicedRanks(dev.plan, ref, 2, cap_bytes, cap_entries)
+    tmp = DeviceBuffers(ranks[1], w.chunk)
+    one = TimeSlicedRanks(tmp.plan, ref, 1, cap_bytes, cap_entries)
+    one.swap_out(0)
+    torch.cuda.synchronize()
+    for name in ("host", "manifest", "counts", "mask"):
+        getattr(sw, name)[1].copy_(getattr(one, name)[0])
+    o.staging[1], o.manifest[1], o.counts[1] = o.delta_of(ranks[1])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = {}
+    with torch.cuda.stream(side):
+        # an eager round trip on the capture stream first (and its twin on the host)
+        for a, b in ((0, 1), (1, 0)):
+            sw.switch(a, b, stream=side)
+            o.switch(a, b)
+        side.synchronize()
+        for a, b in ((0, 1), (1, 0)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                sw.switch(a, b, stream=side)
+            graphs[(a, b)] = g
+    torch.cuda.synchronize()
+    got, _ = dev.host()
+    assert all(np.array_equal(x, y) for x, y in zip(got, o.image))
+
+    rng = np.random.default_rng(9)
+    resident = 0
+    for step in range(6):
+        run_a_mini_batch(w, rng, o, dev)
+        nxt = 1 - resident
+        graphs[(resident, nxt)].replay()
+        o.switch(resident, nxt)
+        torch.cuda.synchronize()
+        assert int(sw.rejected.item()) == 0 and int(sw.serial.item()) == 0
+        check_rank_area(sw, o, resident)
+        got, img = dev.host()
+        assert all(np.array_equal(x, y) for x, y in zip(got, o.image)), step
+        assert dev.canaries_intact(img)
+        resident = nxt
