@@ -709,7 +709,10 @@ def main():
         kernel_bytes = two_pass_kernel_bytes = S
         fp_launch_ms = (mean["fingerprint_ref"] + mean["fingerprint"]) / launches
     achieved = kernel_bytes / (fp_launch_ms / 1e3) / 1e9
-    notes = [read_traffic_note(k.replace("<", "_").replace(">", ""), workload)
+    # counter-measured traffic of the same launches, from the rocprofv3 summaries under profiles/
+    # (config 3's are per rewritten fraction)
+    profiled = workload + (f"_dirty{int(round(args.dirty * 100)):02d}" if w.nreplicas == 1 else "")
+    notes = [read_traffic_note(k.replace("<", "_").replace(">", ""), profiled)
              for k in kernel.split("+")]
     traffic = None if any(x[0] is None for x in notes) else sum(x[0] for x in notes)
     traffic_source = None if traffic is None else [x[1] for x in notes]
