@@ -232,3 +232,76 @@ def test_snapshot_empty_plan_and_argument_errors():
         ck.snapshot(dev.plan, t(3, torch.int64), None, t(4, torch.int64), t(4), t(4096),
                     t(4 * 32), t(3, torch.int64), n_ref=3)
     assert e.value.status == -4
+
+
+def test_thousands_of_buffers_shorter_than_a_chunk():
+    """Nearly every chunk is a short last chunk: the one-kernel manifest path gets its byte
+    offsets from the plan's short-chunk list, which here is as long as the chunk list itself."""
+    rng = np.random.default_rng(51)
+    sizes = rng.integers(0, 5000, size=6000).tolist() + [4096 * 3, 4096, 1]
+    ref = host_bufs(52, sizes)
+    snap = [b.copy() for b in ref]
+    for i in rng.choice(len(snap), size=2500, replace=False).tolist():
+        if snap[i].size:
+            snap[i][int(rng.integers(0, snap[i].size))] ^= 0x80
+    for kind in ("exact", "none", "random", "one_flip"):
+        cnt, misses = check_against_oracle(snap, ref, 4096, kind)
+        assert 2000 < cnt["ndirty"] < 3000
+
+
+@pytest.mark.parametrize("nchunks", [1, 2, 1023, 1024, 1025, 2048, 4097])
+def test_chunk_counts_around_the_scan_block(nchunks):
+    """One scan block is 1024 chunks: plans with exactly, one fewer and one more, and a single
+    chunk."""
+    ref = host_bufs(60 + nchunks, [256 * (nchunks - 1) + 77])
+    snap = [ref[0].copy()]
+    snap[0][::512] ^= 1                                   # every second chunk differs
+    for kind in ("exact", "zeros"):
+        cnt, _ = check_against_oracle(snap, ref, 256, kind)
+        assert cnt["ndirty"] == (nchunks + 1) // 2
+
+
+def test_mask_and_hint_at_odd_addresses():
+    """The mask and the hint are byte arrays with no alignment requirement; the manifest kernel
+    reads them 16 bytes at a time where it can and bytewise at the ragged ends."""
+    ref = host_bufs(71, [256 * 5000 + 3, 100, 256 * 300])
+    snap = [b.copy() for b in ref]
+    rng = np.random.default_rng(72)
+    for b in snap:
+        b[rng.integers(0, b.size, size=b.size // 600)] ^= 0x22
+    chunk = 256
+    dev = DeviceBuffers(snap, chunk)
+    n = dev.plan.nchunks
+    o_dig, o_ref = oracle.fingerprint(snap, chunk, 8), oracle.fingerprint(ref, chunk, 8)
+    o_mask, _ = oracle.diff(snap, chunk, o_dig, o_ref)
+    o_st, o_man, o_cnt = oracle.compact(snap, chunk, o_mask, o_dig)
+    ref_t = torch.from_numpy(o_ref.view(np.int64)).cuda()
+    dig_t = torch.from_numpy(o_dig.view(np.int64)).cuda()
+    for shift in (1, 3, 15, 17):
+        mask = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")[shift:shift + n]
+        hint = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")[shift + 4:shift + 4 + n]
+        assert mask.data_ptr() % 16 == shift % 16
+        hint.copy_(torch.from_numpy(o_mask).cuda())
+        staging = torch.full((o_st.size + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        manifest = torch.full((o_man.size * 32 + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+        dig = torch.zeros(n, dtype=torch.int64, device="cuda")
+        misses = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        ck.snapshot(dev.plan, ref_t, hint, dig, mask, staging, manifest, counts, misses, ws,
+                    staging_cap=o_st.size, manifest_cap=o_man.size)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy(), o_mask) and int(misses.item()) == 0
+        assert counts_dict(counts) == o_cnt
+        assert np.array_equal(staging.cpu().numpy()[:o_st.size], o_st)
+        assert np.array_equal(ck.manifest_to_numpy(manifest, o_man.size), o_man)
+        # the three-call path with the same odd mask address
+        staging.fill_(0xA5)
+        manifest.fill_(0xA5)
+        ck.compact(dev.plan, mask, dig_t, staging, manifest, counts, staging_cap=o_st.size,
+                   manifest_cap=o_man.size)
+        torch.cuda.synchronize()
+        assert counts_dict(counts) == o_cnt
+        assert np.array_equal(staging.cpu().numpy()[:o_st.size], o_st)
+        assert np.array_equal(ck.manifest_to_numpy(manifest, o_man.size), o_man)
+        assert bool((staging[o_st.size:] == 0xA5).all())
