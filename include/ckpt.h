@@ -96,8 +96,8 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  *   out         receives the plan; destroy it with ckpt_plan_destroy
  * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
  * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_upload_owners, ckpt_swap_out
- * and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered (one stream, or events);
- * issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
+ * and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered
+ * (one stream, or events); issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
  * the other calls only read the plan and may overlap freely.
  * Two non-empty buffers that share a byte are refused (INVALID_ARG): restoring
  * into such a list has no defined result, and an allocator never hands out
