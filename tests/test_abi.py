@@ -65,6 +65,15 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.ckpt_diff(None, None, None, 0, None, None, None) == -1
     assert lib.ckpt_compact(None, None, None, None, 0, None, 0, None, None) == -1
     assert lib.ckpt_restore(None, None, 0, None, 0, None, None) == -1
+    assert lib.ckpt_manifest(None, None, None, 0, None, 0, None, None) == -1
+    assert lib.ckpt_exchange(None, None, None, None, 0, None, None, None, 0, 0, None, None, None) == -1
+    assert lib.ckpt_snapshot(None, None, 0, None, None, None, None, 0, None, 0, None, None, None, 0,
+                             None) == -1
+    assert lib.ckpt_snapshot_static(None, None, 0, None, None, None, None, 0, None, 0, None, None,
+                                    None) == -1
+    assert lib.ckpt_snapshot_static_max_chunks() == 1 << 18
+    assert lib.ckpt_snapshot_stats_offset(1000) == 8000
+    assert lib.ckpt_bw_streams(None, None, 16, 512, None, None) == -1
     assert lib.ckpt_plan_destroy(None) == 0
     assert lib.ckpt_plan_nchunks(None) == 0
 

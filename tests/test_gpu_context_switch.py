@@ -225,3 +225,83 @@ def test_switches_replay_from_hip_graphs():
         assert all(np.array_equal(x, y) for x, y in zip(got, o.image)), step
         assert dev.canaries_intact(img)
         resident = nxt
+
+
+def test_manifest_alone_equals_the_manifest_of_compact():
+    """ckpt_manifest writes what ckpt_compact writes as metadata -- entries, counts, overflow
+    under capacity limits -- and moves no chunk bytes."""
+    rng = np.random.default_rng(31)
+    sizes = [70001, 0, 4096, 300000, 17, 65536 + 40]
+    snap = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]
+    chunk = 1024
+    dev = DeviceBuffers(snap, chunk)
+    n = dev.plan.nchunks
+    o_dig = oracle.fingerprint(snap, chunk)
+    mask_h = (rng.random(n) < 0.4).astype(np.uint8)
+    mask, dig = torch.from_numpy(mask_h).cuda(), torch.from_numpy(o_dig.view(np.int64)).cuda()
+    full_st, full_man, _ = oracle.compact(snap, chunk, mask_h, o_dig)
+    for st_cap, man_cap in ((full_st.size, full_man.size), (full_st.size // 2, full_man.size),
+                            (full_st.size, 3), (0, 0)):
+        o_st, o_man, o_cnt = oracle.compact(snap, chunk, mask_h, o_dig, staging_cap=st_cap,
+                                            manifest_cap=man_cap)
+        manifest = torch.full((man_cap * 32 + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+        ck.manifest(dev.plan, mask, dig, manifest, counts, st_cap, man_cap)
+        torch.cuda.synchronize()
+        c = counts.cpu().numpy().view(np.uint64)
+        assert {"ndirty": int(c[0]), "staged_bytes": int(c[1]), "overflow": int(c[2])} == o_cnt
+        raw = manifest.cpu().numpy()
+        assert np.array_equal(raw[:32 * man_cap].view(oracle.ENTRY_DTYPE), o_man)
+        assert np.all(raw[32 * man_cap:] == 0xA5)
+        got, img = dev.host()
+        assert all(np.array_equal(a, b) for a, b in zip(got, snap)) and dev.canaries_intact(img)
+
+
+def test_exchange_skips_entries_that_do_not_fit_and_checks_its_arguments():
+    """An entry whose bytes do not fit a staging area is left alone in both directions and
+    counted; the others are exchanged.  Host-side argument errors are synchronous."""
+    rng = np.random.default_rng(41)
+    chunk = 4096
+    a = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in (5 * chunk, 2 * chunk + 100)]
+    b = [rng.integers(0, 256, size=x.size, dtype=np.uint8) for x in a]
+    dev = DeviceBuffers(a, chunk)                      # rank A resident
+    n = dev.plan.nchunks
+    dig_a, dig_b = oracle.fingerprint(a, chunk), oracle.fingerprint(b, chunk)
+    ones = np.ones(n, np.uint8)
+    st_a, man_a, cnt_a = oracle.compact(a, chunk, ones, dig_a)
+    st_b, man_b, cnt_b = oracle.compact(b, chunk, ones, dig_b)
+    need = st_a.size
+    short = need - 4096 - 112                          # the last two entries no longer fit
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x).view(np.uint8).reshape(-1)).cuda()
+    man_out, man_in = t(man_a), t(man_b)
+    counts = torch.tensor([n, need, 0], dtype=torch.int64, device="cuda")
+    out = torch.full((need + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    inn = torch.cat([t(st_b), torch.zeros(64, dtype=torch.uint8, device="cuda")])
+    serial = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    rejected = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    ck.exchange(dev.plan, man_out, counts, out, short, man_in, counts, inn, need, n, serial,
+                rejected)
+    torch.cuda.synchronize()
+    assert int(serial.item()) == 0
+    fits = (man_a["stage_off"].astype(np.int64) + (man_a["len"].astype(np.int64) + 15) // 16 * 16
+            <= short)
+    assert int(rejected.item()) == int((~fits).sum()) == 2
+    got, img = dev.host()
+    want = [x.copy() for x in a]
+    assert oracle.restore(want, chunk, st_b, man_b[fits]) == 0
+    assert all(np.array_equal(g, w) for g, w in zip(got, want)) and dev.canaries_intact(img)
+    host_out = out.cpu().numpy()
+    kept = int(man_a["stage_off"][fits][-1] + (int(man_a["len"][fits][-1]) + 15) // 16 * 16)
+    assert np.array_equal(host_out[:kept], st_a[:kept]) and np.all(host_out[kept:] == 0xA5)
+    # argument errors
+    for bad in (dict(counts_out=None), dict(staging_out=None), dict(manifest_in=None)):
+        args = dict(manifest_out=man_out, counts_out=counts, staging_out=out, manifest_in=man_in,
+                    counts_in=counts, staging_in=inn)
+        args.update(bad)
+        with pytest.raises(ck.CkptError) as e:
+            ck.exchange(dev.plan, args["manifest_out"], args["counts_out"], args["staging_out"],
+                        need, args["manifest_in"], args["counts_in"], args["staging_in"], need, n)
+        assert e.value.status == -1
+    with pytest.raises(ck.CkptError) as e:
+        ck.exchange(dev.plan, man_out, counts, out[8:], need, man_in, counts, inn, need, n)
+    assert e.value.status == -2
