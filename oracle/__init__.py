@@ -37,6 +37,11 @@ class _Buf(ctypes.Structure):
     _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
 
 
+class _Link(ctypes.Structure):
+    _fields_ = [("staging", ctypes.c_void_p), ("staging_bytes", ctypes.c_uint64),
+                ("manifest", ctypes.c_void_p), ("nentries", ctypes.c_uint64)]
+
+
 class _Counts(ctypes.Structure):
     _fields_ = [("ndirty", ctypes.c_uint64), ("staged_bytes", ctypes.c_uint64),
                 ("overflow", ctypes.c_uint64)]
@@ -81,6 +86,8 @@ def _load():
         lib.ora_upload_owners.argtypes = [vp, u64, u64, vp, ctypes.c_uint32, ctypes.c_uint32, vp, vp]
         lib.ora_restore.restype = ctypes.c_uint64
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
+        lib.ora_restore_chain.restype = ctypes.c_int
+        lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp]
         _lib = lib
     return _lib
 
@@ -246,3 +253,25 @@ def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np
             raise TypeError("destination buffers must be writable")
     return int(_load().ora_restore(_desc(dst), len(dst), chunk, _p(staging), staging_bytes,
                                    _p(manifest), manifest.size))
+
+
+def restore_chain(dst: List[np.ndarray], chunk: int,
+                  links: Sequence[Tuple[np.ndarray, np.ndarray]]) -> dict:
+    """Apply a chain of incremental snapshots, oldest first, to ``dst`` (modified in
+    place): ``links`` holds one (staging, manifest) pair per snapshot (sec. 4.6).
+    Only entries that are whole chunks of ``dst`` are applied.  Returns the numbers
+    of chunks written, of applied entries a later one overwrote, and of entries skipped."""
+    for b in dst:
+        if not b.flags["WRITEABLE"]:
+            raise TypeError("destination buffers must be writable")
+    keep = []
+    arr = (_Link * max(1, len(links)))()
+    for i, (staging, manifest) in enumerate(links):
+        staging = np.ascontiguousarray(staging, dtype=np.uint8)
+        manifest = np.ascontiguousarray(manifest, dtype=ENTRY_DTYPE)
+        keep.append((staging, manifest))
+        arr[i] = _Link(_p(staging), staging.size, _p(manifest), manifest.size)
+    stats = (ctypes.c_uint64 * 3)()
+    if _load().ora_restore_chain(_desc(dst), len(dst), chunk, arr, len(links), stats) != 0:
+        raise MemoryError("ora_restore_chain")
+    return {"written": int(stats[0]), "superseded": int(stats[1]), "rejected": int(stats[2])}

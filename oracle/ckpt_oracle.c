@@ -19,7 +19,9 @@
  *     from (sec. 4.5), here a scatter driven by the manifest;
  *   - the paper's own content-addressed form of the comparison (sec. 5.2.1):
  *     a checksum found at another position means a device-to-device move, not
- *     a swap (ora_match, ora_apply_matches).
+ *     a swap (ora_match, ora_apply_matches);
+ *   - restore from a chain of incremental snapshots (sec. 4.6: de-dup across
+ *     time), the links applied oldest first (ora_restore_chain).
  *
  * Every function is the definition written out: one loop over buffers, one
  * over chunks, memcpy for copies.  No blocking, no fusion.  The only
@@ -30,7 +32,8 @@
  * with the installed xxHash library and with a separate big-integer
  * implementation, brute-force byte comparison, prefix-sum and round-trip
  * invariants, NumPy closed forms for staging and manifest, pair-by-pair
- * brute force for the content-addressed match.
+ * brute force for the content-addressed match, a per-chunk "latest link that
+ * holds it" composition in NumPy for the chain restore.
  */
 #include <pthread.h>
 #include <stddef.h>
@@ -352,6 +355,75 @@ uint64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const
     memcpy((uint8_t *)dst[m->buf].ptr + m->buf_off, in + m->stage_off, m->len);
   }
   return rejected;
+}
+
+/* ---------------------------------------------------------- restore chain */
+/* Restore from a chain of incremental snapshots (sec. 4.6: successive
+ * checkpoints of one process mostly coincide, so each later one holds only
+ * what changed since the one before).  Link 0 is the oldest.  The links are
+ * applied one after the other, each entry in manifest order, so where two
+ * links hold the same chunk the later link's bytes stay.  Every link was taken
+ * with the destination's chunk geometry, so an entry is applied only if it is a
+ * whole chunk of the destination: besides what ora_restore asks, buf_off is a
+ * multiple of the chunk size and len is that chunk's length (the chunk size,
+ * or what is left of the buffer).  Other entries are skipped and counted.
+ *   stats[0] = chunks of the destination written at least once
+ *   stats[1] = applied entries whose chunk a later entry wrote again
+ *   stats[2] = entries skipped
+ * Returns 0, or -1 when the table of written chunks cannot be allocated. */
+typedef struct {
+  const void *staging;
+  uint64_t staging_bytes;
+  const ora_entry_t *manifest;
+  uint64_t nentries;
+} ora_link_t;
+
+int ora_restore_chain(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const ora_link_t *links,
+                      uint64_t nlinks, uint64_t *stats) {
+  uint64_t n = 0;
+  uint64_t *base = (uint64_t *)malloc((nbufs + 1) * sizeof(uint64_t));
+  if (!base) return -1;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    base[i] = n;
+    n += (dst[i].nbytes + chunk - 1) / chunk;
+  }
+  uint8_t *written = (uint8_t *)calloc(n + 1, 1);
+  if (!written) {
+    free(base);
+    return -1;
+  }
+  uint64_t applied = 0, distinct = 0, skipped = 0;
+  for (uint64_t l = 0; l < nlinks; ++l) {
+    const uint8_t *from = (const uint8_t *)links[l].staging;
+    for (uint64_t e = 0; e < links[l].nentries; ++e) {
+      const ora_entry_t *t = &links[l].manifest[e];
+      int ok = t->buf < nbufs && t->stage_off % 16 == 0 && t->buf_off % chunk == 0;
+      if (ok) ok = t->buf_off < dst[t->buf].nbytes;
+      if (ok) {
+        uint64_t left = dst[t->buf].nbytes - t->buf_off;
+        ok = t->len == (left < chunk ? left : chunk);
+      }
+      if (ok) ok = t->stage_off <= links[l].staging_bytes &&
+                   t->len <= links[l].staging_bytes - t->stage_off;
+      if (!ok) {
+        skipped += 1;
+        continue;
+      }
+      memcpy((uint8_t *)dst[t->buf].ptr + t->buf_off, from + t->stage_off, t->len);
+      uint64_t k = base[t->buf] + t->buf_off / chunk;
+      applied += 1;
+      if (!written[k]) {
+        written[k] = 1;
+        distinct += 1;
+      }
+    }
+  }
+  stats[0] = distinct;
+  stats[1] = applied - distinct;
+  stats[2] = skipped;
+  free(written);
+  free(base);
+  return 0;
 }
 
 /* ------------------------------------------------- content-addressed match */

@@ -65,6 +65,7 @@ def pins_hold() -> bool:
             assert np.array_equal(d, b) and np.all(a[:32] == 0xEE) and np.all(a[32 + b.size:] == 0xEE)
         owner_pins()
         widened_pins()
+        chain_pins()
         return True
     except AssertionError:
         return False
@@ -88,6 +89,20 @@ def widened_pins():
     for kind in tv.KINDS:
         tv.test_oracle_verdict_matches_construction(kind)
     tv.test_oracle_no_mutation_at_all_and_empty()
+
+
+def chain_pins():
+    """The pins of the chain restore, as tests/test_oracle_chain.py states them."""
+    import test_oracle_chain as tc
+    for seed in (1, 2, 3, 4):
+        for nlinks in (1, 2, 5):
+            tc.test_chain_equals_latest_holder_per_chunk(seed, nlinks)
+    tc.test_order_of_the_links_decides()
+    tc.test_empty_chain_and_empty_links_touch_nothing()
+    tc.test_entries_that_are_not_whole_chunks_of_the_destination_are_skipped()
+    tc.test_a_rejected_entry_of_a_later_link_leaves_the_earlier_bytes()
+    tc.test_each_link_is_bounded_by_its_own_staging()
+    tc.test_full_snapshot_then_deltas_from_the_oracle_path_restore_the_latest_state()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -160,8 +175,8 @@ def use_library(path):
     good = oracle._load()
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
-               "ora_compact", "ora_restore", "ora_upload_owners", "ora_match", "ora_apply_matches",
-               "ora_validate_mutations"):
+               "ora_compact", "ora_restore", "ora_restore_chain", "ora_upload_owners", "ora_match",
+               "ora_apply_matches", "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     oracle._lib = other

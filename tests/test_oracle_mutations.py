@@ -74,6 +74,20 @@ MUTATIONS = [
      "size += 1;\n        if (r == rank) my_place = size;"),
     ("owner: rotation by rank count instead of group size", "(k % size == my_place)",
      "(k % world == my_place)"),
+    ("chain: the first link that holds a chunk wins",
+     "memcpy((uint8_t *)dst[t->buf].ptr + t->buf_off, from + t->stage_off, t->len);",
+     "if (!written[base[t->buf] + t->buf_off / chunk]) memcpy((uint8_t *)dst[t->buf].ptr + t->buf_off, from + t->stage_off, t->len);"),
+    ("chain: shortened chunks accepted", "ok = t->len == (left < chunk ? left : chunk);",
+     "ok = t->len <= (left < chunk ? left : chunk);"),
+    ("chain: offsets inside a chunk accepted", "t->buf_off % chunk == 0;", "t->buf_off % 16 == 0;"),
+    ("chain: staging bound taken from the first link",
+     "t->len <= links[l].staging_bytes - t->stage_off;", "t->len <= links[0].staging_bytes - t->stage_off;"),
+    ("chain: chunk id without the buffer's base", "uint64_t k = base[t->buf] + t->buf_off / chunk;",
+     "uint64_t k = t->buf_off / chunk;"),
+    ("chain: every applied entry counted as superseded", "stats[1] = applied - distinct;",
+     "stats[1] = applied;"),
+    ("chain: skipped entries not counted", "        skipped += 1;\n        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]",
+     "        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]"),
     ("owner: row stride of gathered checksums", "if (gathered[(uint64_t)r * N + k] != mine) continue;",
      "if (gathered[(uint64_t)r * (N - 1) + k] != mine) continue;"),
 ]
