@@ -329,6 +329,54 @@ int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uin
                          const ckpt_entry_t *d_manifest, uint64_t manifest_cap,
                          const ckpt_counts_t *d_counts, uint64_t *d_rejected, void *stream);
 
+/* ---- restore from a chain of incremental snapshots ------------------------ */
+
+/* Sec. 4.6 de-duplicates successive checkpoints of one process against each
+ * other, so every checkpoint after the first holds only what changed since the
+ * one before, and a restore applies a chain of them.  ckpt_restore_chain gives
+ * the result of calling ckpt_restore_counted for links[0], links[1], ... in that
+ * order (links[0] is the oldest), but writes every chunk of the destination once,
+ * from the last entry of the chain that holds it: state that changes in every
+ * link (gradients, activations) is not copied once per link.
+ * An entry is applied only if it is a whole chunk of dst_plan -- every link was
+ * taken with dst_plan's geometry: buf < B, buf_off a multiple of C inside the
+ * buffer, len equal to that chunk's length, stage_off a multiple of 16 and
+ * [stage_off, stage_off + len) inside the link's staging area.  Other entries
+ * are skipped and counted, and a chunk only they name keeps what an earlier
+ * link, or the caller, put there.
+ *   links        HOST array of nlinks descriptors (read during the call); every
+ *                pointer inside is a device pointer the caller owns
+ *     d_staging, staging_bytes   the link's staging area (16-byte aligned)
+ *     d_manifest, manifest_cap   its manifest and how many entries it can hold
+ *     d_counts   optional device ckpt_counts_t: min(manifest_cap, ndirty)
+ *                entries are applied, read on the device when the kernels run;
+ *                NULL: manifest_cap entries
+ *   nlinks       at most CKPT_CHAIN_MAX; a longer chain is restored by
+ *                consecutive calls, oldest links first
+ *   d_workspace  device scratch of at least
+ *                ckpt_restore_chain_workspace_bytes(N) bytes, 16-byte aligned
+ *   d_stats      optional device ckpt_chain_stats_t, 8-byte aligned
+ * Stream-ordered, no allocation, nothing read back.
+ * Errors: INVALID_ARG (NULL, nlinks > CKPT_CHAIN_MAX, manifest_cap >= 2^40),
+ * ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
+#define CKPT_CHAIN_MAX 16
+typedef struct ckpt_link {
+  const void *d_staging;
+  uint64_t staging_bytes;
+  const ckpt_entry_t *d_manifest;
+  uint64_t manifest_cap;
+  const ckpt_counts_t *d_counts;
+} ckpt_link_t;
+typedef struct ckpt_chain_stats {
+  uint64_t written;    /* chunks of the destination written (each once) */
+  uint64_t superseded; /* whole-chunk entries not copied because a later entry holds the chunk */
+  uint64_t rejected;   /* entries skipped because they are not whole chunks of dst_plan */
+} ckpt_chain_stats_t;
+uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks);
+int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
+                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
+                       void *stream);
+
 /* ---- content-addressed comparison (the paper's own rule) ------------------- */
 
 /* Sec. 5.2.1 looks a checksum up by content wherever it lives: a hit at the same

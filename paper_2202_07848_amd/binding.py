@@ -26,7 +26,8 @@ COUNTS_WORDS = 3          # ndirty, staged_bytes, overflow
 EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact", "ckpt_manifest", "ckpt_exchange",
-    "ckpt_restore", "ckpt_restore_counted", "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
+    "ckpt_restore", "ckpt_restore_counted", "ckpt_restore_chain_workspace_bytes", "ckpt_restore_chain",
+    "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners",
@@ -47,6 +48,12 @@ class CkptError(RuntimeError):
 
 class _Buf(ctypes.Structure):
     _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
+
+
+class _Link(ctypes.Structure):
+    _fields_ = [("d_staging", ctypes.c_void_p), ("staging_bytes", ctypes.c_uint64),
+                ("d_manifest", ctypes.c_void_p), ("manifest_cap", ctypes.c_uint64),
+                ("d_counts", ctypes.c_void_p)]
 
 
 _handle = None
@@ -89,6 +96,10 @@ def _lib():
         lib.ckpt_restore.argtypes = [vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_restore_counted.restype = ci
         lib.ckpt_restore_counted.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
+        lib.ckpt_restore_chain_workspace_bytes.restype = u64
+        lib.ckpt_restore_chain_workspace_bytes.argtypes = [u64]
+        lib.ckpt_restore_chain.restype = ci
+        lib.ckpt_restore_chain.argtypes = [vp, vp, u64, vp, u64, vp, vp]
         lib.ckpt_plan_split_threshold.restype = u64
         lib.ckpt_plan_split_threshold.argtypes = [vp]
         lib.ckpt_plan_set_split_threshold.restype = ci
@@ -335,6 +346,26 @@ def restore_counted(dst_plan: Plan, staging, staging_bytes: int, manifest, manif
     _check(_lib().ckpt_restore_counted(dst_plan._h, _ptr(staging), staging_bytes, _ptr(manifest),
                                        manifest_cap, _ptr(counts), _ptr(rejected), _stream(stream)),
            "ckpt_restore_counted")
+
+
+CHAIN_MAX = 16
+CHAIN_STAT_FIELDS = ("written", "superseded", "rejected")
+
+
+def restore_chain_workspace_bytes(nchunks: int) -> int:
+    return int(_lib().ckpt_restore_chain_workspace_bytes(nchunks))
+
+
+def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None) -> None:
+    """``ckpt_restore_chain``: ``links`` is a sequence, oldest first, of
+    (staging, staging_bytes, manifest, manifest_cap, counts or None); workspace is a uint8
+    tensor, stats (optional) 3 x int64."""
+    arr = (_Link * max(1, len(links)))()
+    for i, (staging, staging_bytes, manifest, cap, counts) in enumerate(links):
+        arr[i] = _Link(_ptr(staging), staging_bytes, _ptr(manifest), cap, _ptr(counts))
+    _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _ptr(stats),
+                                     _stream(stream)), "ckpt_restore_chain")
 
 
 MATCH_COUNT_FIELDS = ("nsame", "nmoved", "ndup", "nnew", "staged_bytes", "table_full")

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckpt.so")
 SOURCES = ["api.hip", "fingerprint.hip", "diff_scan.hip", "copy.hip", "match.hip",
-           "transport.hip", "swap.hip", "exchange.hip"]
+           "transport.hip", "swap.hip", "exchange.hip", "chain.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

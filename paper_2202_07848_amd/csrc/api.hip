@@ -83,7 +83,7 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   uint32_t chunk_log2 = 0;
   while ((1ull << chunk_log2) < chunk_bytes) ++chunk_log2;
 
-  std::vector<uint64_t> dense_ptr, dense_nbytes, dense_base, list_ptr, list_nbytes;
+  std::vector<uint64_t> dense_ptr, dense_nbytes, dense_base, list_ptr, list_nbytes, list_base;
   std::vector<uint32_t> dense_orig, group_first;
   std::vector<uint64_t> full_ptr, full_chunk0, full_base, short_ptr, short_chunk;
   std::vector<uint32_t> full_group_first, short_len;
@@ -91,6 +91,7 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   try {
     list_ptr.reserve(nbufs);
     list_nbytes.reserve(nbufs);
+    list_base.reserve(nbufs);
     for (uint64_t i = 0; i < nbufs; ++i) {
       const uint64_t n = bufs[i].nbytes;
       if (n != 0) {
@@ -101,6 +102,7 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
       }
       list_ptr.push_back(reinterpret_cast<uint64_t>(n ? bufs[i].ptr : nullptr));
       list_nbytes.push_back(n);
+      list_base.push_back(nchunks);
       if (n == 0) continue;
       dense_ptr.push_back(reinterpret_cast<uint64_t>(bufs[i].ptr));
       dense_nbytes.push_back(n);
@@ -193,7 +195,8 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   const size_t o_lptr = o_gfirst + up16(4 * group_first.size());
   const size_t o_lnb = o_lptr + up16(8 * (size_t)nbufs);
   const size_t nf = full_ptr.size(), ns = short_ptr.size();
-  const size_t o_fptr = o_lnb + up16(8 * (size_t)nbufs);
+  const size_t o_lbase = o_lnb + up16(8 * (size_t)nbufs);
+  const size_t o_fptr = o_lbase + up16(8 * (size_t)nbufs);
   const size_t o_fc0 = o_fptr + up16(8 * nf);
   const size_t o_fbase = o_fc0 + up16(8 * nf);
   const size_t o_fgf = o_fbase + up16(8 * (nf + 1));
@@ -241,6 +244,7 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   put(o_gfirst, group_first.data(), 4 * group_first.size());
   put(o_lptr, list_ptr.data(), 8 * (size_t)nbufs);
   put(o_lnb, list_nbytes.data(), 8 * (size_t)nbufs);
+  put(o_lbase, list_base.data(), 8 * (size_t)nbufs);
   put(o_fptr, full_ptr.data(), 8 * nf);
   put(o_fc0, full_chunk0.data(), 8 * nf);
   put(o_fbase, full_base.data(), 8 * (nf + 1));
@@ -264,6 +268,7 @@ int ckpt_plan_create(const ckpt_buf_t *bufs, uint64_t nbufs, uint64_t chunk_byte
   d.group_first = reinterpret_cast<const uint32_t *>(base + o_gfirst);
   d.list_ptr = reinterpret_cast<const uint64_t *>(base + o_lptr);
   d.list_nbytes = reinterpret_cast<const uint64_t *>(base + o_lnb);
+  d.list_base = reinterpret_cast<const uint64_t *>(base + o_lbase);
   d.spare = reinterpret_cast<const uint8_t *>(base + o_spare);
   d.full_ptr = reinterpret_cast<const uint64_t *>(base + o_fptr);
   d.full_chunk0 = reinterpret_cast<const uint64_t *>(base + o_fc0);
@@ -529,6 +534,37 @@ int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uin
     return CKPT_ERR_ALIGNMENT;
   hipError_t e = ckpt::launch_scatter(dst_plan->dev, d_manifest, manifest_cap, d_counts, d_staging,
                                       staging_bytes, d_rejected, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks) { return 8 * nchunks + 16; }
+
+int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
+                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
+                       void *stream) {
+  if (dst_plan == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (nlinks > CKPT_CHAIN_MAX || (nlinks != 0 && links == nullptr)) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_workspace, 16) || !aligned(d_stats, 8)) return CKPT_ERR_ALIGNMENT;
+  ckpt::ChainArgs a{};
+  a.nlinks = (uint32_t)nlinks;
+  for (uint64_t l = 0; l < nlinks; ++l) {
+    const ckpt_link_t &k = links[l];
+    if (k.manifest_cap != 0 && k.d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+    if (k.staging_bytes != 0 && k.d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+    if (k.manifest_cap >= (1ull << 40)) return CKPT_ERR_INVALID_ARG;
+    if (!aligned(k.d_staging, 16) || !aligned(k.d_manifest, 8) || !aligned(k.d_counts, 8))
+      return CKPT_ERR_ALIGNMENT;
+    a.staging[l] = static_cast<const uint8_t *>(k.d_staging);
+    a.staging_bytes[l] = k.staging_bytes;
+    a.manifest[l] = k.d_manifest;
+    a.cap[l] = k.manifest_cap;
+    a.counts[l] = k.d_counts;
+  }
+  if (workspace_bytes < ckpt_restore_chain_workspace_bytes(dst_plan->dev.nchunks))
+    return CKPT_ERR_CAPACITY;
+  hipError_t e = ckpt::launch_restore_chain(dst_plan->dev, a, static_cast<uint64_t *>(d_workspace),
+                                            reinterpret_cast<uint64_t *>(d_stats),
+                                            static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

@@ -1,0 +1,163 @@
+// Restore from a chain of incremental snapshots as ONE pass over the destination
+// (Singularity paper sec. 4.6: successive checkpoints of one process mostly
+// coincide, so a later one holds only what changed since the one before; a
+// restore therefore starts from an early snapshot and applies the later ones).
+//
+// Applying the links one after the other writes a chunk once per link that
+// holds it.  Gradients and activations change at every step, so in a chain of m
+// snapshots of a training job the same third of the state would be written m
+// times.  Here every chunk is written once, from the last link that holds it:
+//   k_chain_clear  last[k] = 0
+//   k_chain_mark   every whole-chunk entry e of link l raises last[k] to
+//                  (l + 1, e) with a 64-bit atomic maximum, k being the chunk the
+//                  entry names; the entry that finds 0 there is the first for its
+//                  chunk, which gives the number of chunks written
+//   k_chain_move   an entry copies its bytes only if last[k] is still its own key
+// The maximum over (link, entry index) is the entry a one-by-one restore would
+// apply last, so the result is the same for any manifests, including ones that
+// hold a chunk twice.
+#include "ckpt_internal.h"
+#include "stream_copy.h"
+
+namespace ckpt {
+
+namespace {
+
+constexpr int CHAIN_ENTRY_BITS = 40;   // key = (link + 1) << 40 | entry index
+
+__device__ __forceinline__ uint64_t link_entries(const ChainArgs &a, uint32_t l) {
+  uint64_t n = a.cap[l];
+  if (a.counts[l] != nullptr) {
+    const uint64_t c = a.counts[l]->ndirty;
+    if (c < n) n = c;
+  }
+  return n;
+}
+
+// Is t a whole chunk of the destination whose bytes lie inside the link's staging area?
+// Sets *k to the chunk's global id.  Written so that no sum can wrap.
+__device__ __forceinline__ bool whole_chunk(const PlanDev &p, const ckpt_entry_t &t,
+                                            uint64_t staging_bytes, uint64_t *k) {
+  const uint64_t c = 1ull << p.chunk_log2;
+  if (t.buf >= p.nbufs || (t.stage_off & 15) != 0 || (t.buf_off & (c - 1)) != 0) return false;
+  const uint64_t nb = p.list_nbytes[t.buf];
+  if (t.buf_off >= nb) return false;
+  const uint64_t left = nb - t.buf_off;
+  if (t.len != (left < c ? left : c)) return false;
+  if (t.stage_off > staging_bytes || t.len > staging_bytes - t.stage_off) return false;
+  *k = p.list_base[t.buf] + (t.buf_off >> p.chunk_log2);
+  return true;
+}
+
+__global__ __launch_bounds__(256) void k_chain_clear(unsigned long long *__restrict__ last,
+                                                     uint64_t n, unsigned long long *stats) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) last[k] = 0;
+  if (stats != nullptr && blockIdx.x == 0 && threadIdx.x < 3) stats[threadIdx.x] = 0;
+}
+
+// grid = (workgroups per link, links)
+__global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
+                                                    unsigned long long *__restrict__ last,
+                                                    unsigned long long *stats) {
+  const uint32_t l = blockIdx.y;
+  const uint64_t n = link_entries(a, l);
+  const ckpt_entry_t *manifest = a.manifest[l];
+  const uint64_t staging_bytes = a.staging_bytes[l];
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  uint32_t applied = 0, first = 0, skipped = 0;
+  for (uint64_t e = (uint64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
+    const ckpt_entry_t t = manifest[e];
+    uint64_t k;
+    if (!whole_chunk(p, t, staging_bytes, &k)) {
+      ++skipped;
+      continue;
+    }
+    const unsigned long long key = ((unsigned long long)(l + 1) << CHAIN_ENTRY_BITS) | e;
+    const unsigned long long old = atomicMax(&last[k], key);
+    ++applied;
+    first += old == 0;
+  }
+  if (stats == nullptr) return;
+  uint32_t again = applied - first;
+  for (int o = 32; o > 0; o >>= 1) {
+    first += __shfl_down(first, o, 64);
+    again += __shfl_down(again, o, 64);
+    skipped += __shfl_down(skipped, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (first) atomicAdd(&stats[0], (unsigned long long)first);
+    if (again) atomicAdd(&stats[1], (unsigned long long)again);
+    if (skipped) atomicAdd(&stats[2], (unsigned long long)skipped);
+  }
+}
+
+// grid = (workgroups per link, links).  Work item = one piece (min(C, 16 KiB)) of one entry of
+// the workgroup's link, dealt round-robin over the link's waves like the plain scatter.
+__global__ __launch_bounds__(COPY_THREADS) void k_chain_move(
+    PlanDev p, ChainArgs a, const unsigned long long *__restrict__ last) {
+  const uint32_t l = blockIdx.y;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
+  const ckpt_entry_t *manifest = a.manifest[l];
+  const uint64_t staging_bytes = a.staging_bytes[l];
+  const uint8_t *staging = a.staging[l];
+  const uint64_t nitems = link_entries(a, l) << ppc_log2;
+
+  for (uint64_t item = (uint64_t)blockIdx.x * (COPY_THREADS / 64) + wave_in_group; item < nitems;
+       item += nwaves) {
+    const uint64_t e = item >> ppc_log2;
+    const uint32_t piece = (uint32_t)(item & ((1ull << ppc_log2) - 1));
+    const ckpt_entry_t t = manifest[e];
+    uint64_t k;
+    if (!whole_chunk(p, t, staging_bytes, &k)) continue;     // the same test as in k_chain_mark
+    const unsigned long long key = ((unsigned long long)(l + 1) << CHAIN_ENTRY_BITS) | e;
+    if (last[k] != key) continue;                            // a later entry holds this chunk
+    const uint32_t lo = piece << piece_log2;
+    uint32_t hi = lo + (1u << piece_log2);
+    const uint32_t padded = (uint32_t)pad16(t.len);
+    if (hi > padded) hi = padded;
+    move_piece<false>(staging + t.stage_off,
+                      reinterpret_cast<uint8_t *>(p.list_ptr[t.buf]) + t.buf_off, lo, hi, t.len,
+                      lane);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_last,
+                                uint64_t *d_stats, hipStream_t s) {
+  unsigned long long *last = reinterpret_cast<unsigned long long *>(d_last);
+  unsigned long long *stats = reinterpret_cast<unsigned long long *>(d_stats);
+  uint64_t clear_groups = (p.nchunks + 256 * 8 - 1) / (256 * 8);
+  if (clear_groups > 4096) clear_groups = 4096;
+  if (clear_groups == 0) clear_groups = 1;
+  hipLaunchKernelGGL(k_chain_clear, dim3((uint32_t)clear_groups), dim3(256), 0, s, last, p.nchunks,
+                     stats);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.nlinks == 0) return e;
+
+  uint64_t most = 0;                               // entries of the longest link (host bound)
+  for (uint32_t l = 0; l < a.nlinks; ++l) most = a.cap[l] > most ? a.cap[l] : most;
+  if (most == 0) return hipSuccess;
+  uint64_t mark_groups = (most + 255) / 256;
+  if (mark_groups > 2048) mark_groups = 2048;
+  hipLaunchKernelGGL(k_chain_mark, dim3((uint32_t)mark_groups, a.nlinks), dim3(256), 0, s, p, a,
+                     last, stats);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint64_t items = most << (p.chunk_log2 - piece_log2);
+  uint64_t groups = (items + COPY_THREADS / 64 - 1) / (COPY_THREADS / 64);
+  const uint64_t per_link = COPY_MAX_GROUPS / a.nlinks;
+  if (groups > per_link) groups = per_link;
+  hipLaunchKernelGGL(k_chain_move, dim3((uint32_t)groups, a.nlinks), dim3(COPY_THREADS), 0, s, p, a,
+                     last);
+  return hipGetLastError();
+}
+
+}  // namespace ckpt

@@ -27,6 +27,7 @@ struct PlanDev {
   const uint32_t *group_first;   // [ceil(N/GROUP)] dense row that holds chunk GROUP*g
   const uint64_t *list_ptr;      // [nbufs]
   const uint64_t *list_nbytes;   // [nbufs]
+  const uint64_t *list_base;     // [nbufs] global id of the buffer's first chunk
   const uint8_t *spare;          // 256 readable bytes (zero), 256-byte aligned
   // Work lists of the fingerprint kernel.  Full chunks (length C) and last
   // chunks shorter than C are grouped separately so that the 16 chunks a
@@ -178,6 +179,18 @@ hipError_t launch_exchange(const PlanDev &p, const ckpt_entry_t *d_manifest_out,
                            const void *d_stage_in, uint64_t in_bytes, uint64_t manifest_cap,
                            uint64_t *d_differs, uint64_t *d_serial, uint64_t *d_rejected,
                            hipStream_t s);
+// A chain of incremental snapshots, oldest first, as the kernels take it (by value).
+struct ChainArgs {
+  const uint8_t *staging[CKPT_CHAIN_MAX];
+  uint64_t staging_bytes[CKPT_CHAIN_MAX];
+  const ckpt_entry_t *manifest[CKPT_CHAIN_MAX];
+  uint64_t cap[CKPT_CHAIN_MAX];                 // entries the manifest can hold
+  const ckpt_counts_t *counts[CKPT_CHAIN_MAX];  // null: cap entries; else min(cap, ndirty)
+  uint32_t nlinks;
+};
+// d_last: one uint64 per chunk of p (scratch); d_stats (may be null): written, superseded, skipped.
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_last,
+                                uint64_t *d_stats, hipStream_t s);
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);
