@@ -68,6 +68,10 @@ def parse_args():
                     help="config 4 only: also time whole context switches between four time-sliced "
                          "ranks that share one device image (swap-out of the outgoing rank's delta "
                          "to pinned host memory, swap-in of the incoming rank's, no host read)")
+    ap.add_argument("--chain", action="store_true",
+                    help="configs with three or more replicas (--config 4): also restore the chain "
+                         "of the replicas' deltas, one ckpt_restore_counted per link against one "
+                         "ckpt_restore_chain over all of them")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in HIP graphs (snapshot part, restore part) and "
                          "time their replays: what a launch-bound small state gains")
@@ -431,6 +435,67 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
         "image_equals_incoming_rank_after_each_switch": ok,
         "paper_context": "sec. 5.2: swapping 32 GB out and in without de-duplication costs 2-4 s "
                          "per mini-batch on the paper's V100 hosts",
+    }
+
+
+def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
+    """Restore from a chain of incremental snapshots (paper sec. 4.6).  The links are the
+    deltas of replicas 1, 2, ... against the reference: every link holds the same chunks (the
+    per-replica gradients and activations), as the steps of one job do.  Applied link by link
+    each of those chunks is written once per link; ckpt_restore_chain writes it once."""
+    dev = ref.device
+    n = w.nchunks
+    dig = torch.zeros(n, dtype=torch.int64, device=dev)
+    mask = torch.zeros(n, dtype=torch.uint8, device=dev)
+    links, staged = [], []
+    for (_, rep), staging, manifest in zip(pairs, stagings, manifests):
+        cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+        ck.fingerprint(rep.plan, dig)
+        ck.diff(rep.plan, dig, ref, mask, cnt)
+        ck.compact(rep.plan, mask, dig, staging, manifest, cnt, staging_cap=staging.numel(),
+                   manifest_cap=manifest.numel() // 32)
+        torch.cuda.synchronize()
+        assert int(cnt[2]) == 0
+        staged.append(int(cnt[1]))
+        links.append((staging, int(cnt[1]), manifest, manifest.numel() // 32, cnt))
+    image = replicas[0].arena.clone()
+    plan = ck.Plan([(image.data_ptr() + int(o), b.nbytes) for o, b in zip(replicas[0].offs, w.bufs)],
+                   w.chunk)
+    ws = torch.empty(ck.restore_chain_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    stats = torch.zeros(3, dtype=torch.int64, device=dev)
+
+    def one_by_one():
+        for staging, nbytes, manifest, cap, cnt in links:
+            ck.restore_counted(plan, staging, nbytes, manifest, cap, cnt)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        assert torch.equal(image, pairs[-1][1].arena)
+        image.copy_(replicas[0].arena)
+        fn()
+        e0, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_each = timed(one_by_one)
+    ms_chain = timed(lambda: ck.restore_chain(plan, links, ws, stats))
+    written, superseded, rejected = (int(x) for x in stats.cpu().numpy().view(np.uint64))
+    assert rejected == 0 and superseded == sum(int(l[4][0]) for l in links) - written
+    return {
+        "workload": f"config{w.config}_{w.name}: chain of {len(links)} deltas restored into a copy "
+                    "of the reference replica",
+        "links": len(links), "bytes_per_link": staged,
+        "chunks_written": written, "entries_superseded": superseded,
+        "one_restore_per_link_ms": round(ms_each, 3),
+        "restore_chain_ms": round(ms_chain, 3),
+        "speedup": round(ms_each / ms_chain, 2),
+        "restore_chain_hbm_GBps_read_plus_write": round(2 * staged[-1] / ms_chain / 1e6, 1),
+        "image_equals_last_replica": True,
     }
 
 
@@ -826,6 +891,11 @@ def main():
         if w.nreplicas < 4:
             raise SystemExit("--switch needs a configuration with four replicas (--config 4)")
         out["context_switch"] = context_switch_leg(w, replicas, ref, ck, wl, torch, np, args)
+
+    if args.chain:
+        if len(pairs) < 2:
+            raise SystemExit("--chain needs a configuration with three or more replicas (--config 4)")
+        out["restore_chain"] = chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np)
 
     if args.match and w.nreplicas == 1:
         out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,

@@ -537,7 +537,7 @@ int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uin
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
-uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks) { return 8 * nchunks + 16; }
+uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks) { return 16 * nchunks + 16; }
 
 int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
                        void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,

@@ -12,7 +12,9 @@
 //                  (l + 1, e) with a 64-bit atomic maximum, k being the chunk the
 //                  entry names; the entry that finds 0 there is the first for its
 //                  chunk, which gives the number of chunks written
-//   k_chain_move   an entry copies its bytes only if last[k] is still its own key
+//   k_chain_list   the keys that are left, one per chunk that any link holds, as a
+//                  dense list
+//   k_chain_move   every listed key copies its entry's bytes
 // The maximum over (link, entry index) is the entry a one-by-one restore would
 // apply last, so the result is the same for any manifests, including ones that
 // hold a chunk twice.
@@ -50,9 +52,11 @@ __device__ __forceinline__ bool whole_chunk(const PlanDev &p, const ckpt_entry_t
 }
 
 __global__ __launch_bounds__(256) void k_chain_clear(unsigned long long *__restrict__ last,
-                                                     uint64_t n, unsigned long long *stats) {
+                                                     uint64_t n, unsigned long long *count,
+                                                     unsigned long long *stats) {
   const uint64_t stride = (uint64_t)gridDim.x * 256;
   for (uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) last[k] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 3) *count = 0;
   if (stats != nullptr && blockIdx.x == 0 && threadIdx.x < 3) stats[threadIdx.x] = 0;
 }
 
@@ -92,35 +96,53 @@ __global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
   }
 }
 
-// grid = (workgroups per link, links).  Work item = one piece (min(C, 16 KiB)) of one entry of
-// the workgroup's link, dealt round-robin over the link's waves like the plain scatter.
+// The keys of the chunks that have one, gathered into list[0 .. *count): a wavefront looks at 64
+// consecutive chunk ids and appends its keys in chunk order behind one atomic add, so the list
+// is in ascending chunk order inside every run of 64 and roughly so overall (the order decides
+// nothing but which waves of k_chain_move run side by side).
+__global__ __launch_bounds__(256) void k_chain_list(const unsigned long long *__restrict__ last,
+                                                    uint64_t n, unsigned long long *__restrict__ list,
+                                                    unsigned long long *count) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t k0 = (uint64_t)blockIdx.x * 256 + (threadIdx.x & ~63u); k0 < n; k0 += stride) {
+    const uint64_t k = k0 + lane;
+    const unsigned long long key = k < n ? last[k] : 0;
+    const uint64_t holders = __ballot(key != 0);
+    if (holders == 0) continue;
+    unsigned long long base = 0;
+    if (lane == 0) base = atomicAdd(count, (unsigned long long)__popcll(holders));
+    base = __shfl(base, 0, 64);
+    if (key != 0) list[base + __popcll(holders & ((1ull << lane) - 1))] = key;
+  }
+}
+
+// Work item = one piece (min(C, 16 KiB)) of one listed chunk, dealt round-robin over a fixed
+// grid like the plain scatter; the key names the link and the entry that holds the bytes.
 __global__ __launch_bounds__(COPY_THREADS) void k_chain_move(
-    PlanDev p, ChainArgs a, const unsigned long long *__restrict__ last) {
-  const uint32_t l = blockIdx.y;
+    PlanDev p, ChainArgs a, const unsigned long long *__restrict__ list,
+    const unsigned long long *__restrict__ count) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
   const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
-  const ckpt_entry_t *manifest = a.manifest[l];
-  const uint64_t staging_bytes = a.staging_bytes[l];
-  const uint8_t *staging = a.staging[l];
-  const uint64_t nitems = link_entries(a, l) << ppc_log2;
+  const uint64_t nitems = *count << ppc_log2;
 
   for (uint64_t item = (uint64_t)blockIdx.x * (COPY_THREADS / 64) + wave_in_group; item < nitems;
        item += nwaves) {
-    const uint64_t e = item >> ppc_log2;
+    const unsigned long long key = list[item >> ppc_log2];
     const uint32_t piece = (uint32_t)(item & ((1ull << ppc_log2) - 1));
-    const ckpt_entry_t t = manifest[e];
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(key >> CHAIN_ENTRY_BITS)) - 1;
+    if (l >= a.nlinks) continue;                             // cannot happen: keys come from k_chain_mark
+    const ckpt_entry_t t = a.manifest[l][key & ((1ull << CHAIN_ENTRY_BITS) - 1)];
     uint64_t k;
-    if (!whole_chunk(p, t, staging_bytes, &k)) continue;     // the same test as in k_chain_mark
-    const unsigned long long key = ((unsigned long long)(l + 1) << CHAIN_ENTRY_BITS) | e;
-    if (last[k] != key) continue;                            // a later entry holds this chunk
+    if (!whole_chunk(p, t, a.staging_bytes[l], &k)) continue;   // the same test as in k_chain_mark
     const uint32_t lo = piece << piece_log2;
     uint32_t hi = lo + (1u << piece_log2);
     const uint32_t padded = (uint32_t)pad16(t.len);
     if (hi > padded) hi = padded;
-    move_piece<false>(staging + t.stage_off,
+    move_piece<false>(a.staging[l] + t.stage_off,
                       reinterpret_cast<uint8_t *>(p.list_ptr[t.buf]) + t.buf_off, lo, hi, t.len,
                       lane);
   }
@@ -128,35 +150,44 @@ __global__ __launch_bounds__(COPY_THREADS) void k_chain_move(
 
 }  // namespace
 
-hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_last,
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
                                 uint64_t *d_stats, hipStream_t s) {
-  unsigned long long *last = reinterpret_cast<unsigned long long *>(d_last);
+  // workspace: last[N], list[N], one counter
+  unsigned long long *last = reinterpret_cast<unsigned long long *>(d_workspace);
+  unsigned long long *list = last + p.nchunks;
+  unsigned long long *count = list + p.nchunks;
   unsigned long long *stats = reinterpret_cast<unsigned long long *>(d_stats);
-  uint64_t clear_groups = (p.nchunks + 256 * 8 - 1) / (256 * 8);
-  if (clear_groups > 4096) clear_groups = 4096;
-  if (clear_groups == 0) clear_groups = 1;
-  hipLaunchKernelGGL(k_chain_clear, dim3((uint32_t)clear_groups), dim3(256), 0, s, last, p.nchunks,
-                     stats);
+  auto groups_for = [](uint64_t n, uint64_t per_group, uint64_t most) {
+    uint64_t g = (n + per_group - 1) / per_group;
+    return (uint32_t)(g > most ? most : (g == 0 ? 1 : g));
+  };
+  hipLaunchKernelGGL(k_chain_clear, dim3(groups_for(p.nchunks, 256 * 8, 4096)), dim3(256), 0, s,
+                     last, p.nchunks, count, stats);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.nlinks == 0) return e;
 
-  uint64_t most = 0;                               // entries of the longest link (host bound)
-  for (uint32_t l = 0; l < a.nlinks; ++l) most = a.cap[l] > most ? a.cap[l] : most;
+  uint64_t most = 0, sum = 0;                      // host bounds on the entries of a link / of all
+  for (uint32_t l = 0; l < a.nlinks; ++l) {
+    most = a.cap[l] > most ? a.cap[l] : most;
+    sum += a.cap[l];
+  }
   if (most == 0) return hipSuccess;
-  uint64_t mark_groups = (most + 255) / 256;
-  if (mark_groups > 2048) mark_groups = 2048;
-  hipLaunchKernelGGL(k_chain_mark, dim3((uint32_t)mark_groups, a.nlinks), dim3(256), 0, s, p, a,
-                     last, stats);
+  hipLaunchKernelGGL(k_chain_mark, dim3(groups_for(most, 256, 2048), a.nlinks), dim3(256), 0, s, p,
+                     a, last, stats);
+  e = hipGetLastError();
+  if (e != hipSuccess || p.nchunks == 0) return e;   // an empty destination: entries counted, none applied
+
+  hipLaunchKernelGGL(k_chain_list, dim3(groups_for(p.nchunks, 256, 4096)), dim3(256), 0, s, last,
+                     p.nchunks, list, count);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
-  const uint64_t items = most << (p.chunk_log2 - piece_log2);
-  uint64_t groups = (items + COPY_THREADS / 64 - 1) / (COPY_THREADS / 64);
-  const uint64_t per_link = COPY_MAX_GROUPS / a.nlinks;
-  if (groups > per_link) groups = per_link;
-  hipLaunchKernelGGL(k_chain_move, dim3((uint32_t)groups, a.nlinks), dim3(COPY_THREADS), 0, s, p, a,
-                     last);
+  const uint64_t chunks = sum < p.nchunks ? sum : p.nchunks;        // at most this many are listed
+  const uint64_t items = chunks << (p.chunk_log2 - piece_log2);
+  hipLaunchKernelGGL(k_chain_move,
+                     dim3(groups_for(items, COPY_THREADS / 64, COPY_MAX_GROUPS)),
+                     dim3(COPY_THREADS), 0, s, p, a, list, count);
   return hipGetLastError();
 }
 

@@ -188,8 +188,8 @@ struct ChainArgs {
   const ckpt_counts_t *counts[CKPT_CHAIN_MAX];  // null: cap entries; else min(cap, ndirty)
   uint32_t nlinks;
 };
-// d_last: one uint64 per chunk of p (scratch); d_stats (may be null): written, superseded, skipped.
-hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_last,
+// d_workspace: 2 N + 1 uint64 (scratch); d_stats (may be null): written, superseded, skipped.
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
                                 uint64_t *d_stats, hipStream_t s);
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
