@@ -267,3 +267,51 @@ def test_argument_checks():
     with pytest.raises(ck.CkptError) as e:
         ck.restore_chain(dst.plan, [(link[0], link[1], link[2], 1 << 40, None)], ws)
     assert e.value.status == -1
+
+
+def test_chain_restore_replays_from_a_hip_graph_with_changing_entry_counts():
+    """The call only enqueues kernels and reads the entry counts on the device, so it can be
+    captured; between replays the links' counts and the destination change through eager work,
+    and every replay must give what the oracle gives for those counts."""
+    import torch
+    from gpu_util import DeviceBuffers
+    from paper_2202_07848_amd import binding as ck
+    sizes, chunk = [50000, 4096, 0, 12345, 70001], 4096
+    rng = np.random.default_rng(41)
+    states = [[rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes] for _ in range(3)]
+    n = sum((s + chunk - 1) // chunk for s in sizes)
+    chosen = [list(range(n)), list(range(0, n, 2)), list(range(1, n, 3))]
+    links = [sliced_link(s, chunk, c) for s, c in zip(states, chosen)]
+    counts = [torch.tensor([len(c), 0, 0], dtype=torch.int64, device="cuda") for c in chosen]
+    dev = [d[:4] + (c,) for d, c in zip(upload(links), counts)]
+    dst = DeviceBuffers([np.zeros(s, np.uint8) for s in sizes], chunk)
+    ws = torch.zeros(ck.restore_chain_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(3, dtype=torch.int64, device="cuda")
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ck.restore_chain(dst.plan, dev, ws, stats, stream=side)      # eager warm-up
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ck.restore_chain(dst.plan, dev, ws, stats, stream=side)
+    torch.cuda.synchronize()
+
+    for replay, cut in enumerate([(n, len(chosen[1]), len(chosen[2])), (5, 0, 3), (n, 2, 0),
+                                  (0, 0, 0), (n, len(chosen[1]), len(chosen[2]))]):
+        for c, k in zip(counts, cut):
+            c[0] = k
+        dst.arena.copy_(DeviceBuffers([np.full(s, replay, np.uint8) for s in sizes], chunk).arena)
+        ws.fill_(0xEE)
+        stats.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = [np.full(s, replay, np.uint8) for s in sizes]
+        want_stats = oracle.restore_chain(want, chunk, [(l[0], l[1][:k]) for l, k in zip(links, cut)])
+        got, img = dst.host()
+        assert all(np.array_equal(g, w) for g, w in zip(got, want)), replay
+        assert dst.canaries_intact(img), replay
+        v = stats.cpu().numpy().view(np.uint64)
+        assert {"written": int(v[0]), "superseded": int(v[1]), "rejected": int(v[2])} == want_stats
