@@ -296,3 +296,53 @@ def test_config3_full_size_every_element(fraction):
           f"(N = {n}, both paths)")
     assert got == n
     gpu_restore_check(t0, t1, snaps["three_calls"])
+
+
+def test_config4_chain_restore_full_size():
+    """ckpt_restore_chain at config 4's size (paper sec. 4.6).  States: replica 0, replica 1,
+    replica 2, then replica 2 with two shared buffers rewritten; every link is the delta against
+    the state before it.  The links hold different chunk sets (all per-replica chunks twice, a
+    few shared chunks once); restored in one pass into a copy of replica 0 the image must equal
+    the last state byte for byte -- which no part of the library computed -- and its fingerprint
+    the last state's digests; the counts follow from the construction."""
+    w = wl.config(4)
+    a0, offs = wl.torch_replica(w, 0, "cuda")
+    r0 = Rep(w, a0, offs)
+    n = r0.plan.nchunks
+    prev = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ck.fingerprint(r0.plan, prev)
+    image = Rep(w, a0.clone(), offs)
+    buf, _, _ = wl.chunk_table(w)
+    private = np.array([not b.shared for b in w.bufs])[buf]
+    links, sets, state = [], [], None
+    for step in (1, 2, 3):
+        if step < 3:
+            a, _ = wl.torch_replica(w, step, "cuda", shared_from=a0)
+            state = Rep(w, a, offs)
+            sets.append(private.copy())
+        else:
+            # two shared buffers of the last state change: a large one and a ragged small one
+            shared = [i for i, b in enumerate(w.bufs) if b.shared]
+            big = max(shared, key=lambda i: w.bufs[i].nbytes)
+            small = next(i for i in shared if 0 < w.bufs[i].nbytes < w.chunk)
+            for i in (big, small):
+                state.arena[int(offs[i]):int(offs[i]) + w.bufs[i].nbytes] ^= 0x5C
+            sets.append(np.isin(buf, [big, small]))
+        s = Snapshot(state, prev, "three_calls")
+        assert np.array_equal(s.h_mask, sets[-1].astype(np.uint8))
+        links.append((s.staging, s.staged, s.manifest, s.ndirty, s.counts))
+        prev = s.dig
+    assert not device_equal(image, state)
+    ws = torch.empty(ck.restore_chain_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    stats = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    ck.restore_chain(image.plan, links, ws, stats)
+    torch.cuda.synchronize()
+    assert device_equal(image, state)
+    again = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ck.fingerprint(image.plan, again)
+    torch.cuda.synchronize()
+    assert torch.equal(again, prev)
+    union = int(np.logical_or.reduce(sets).sum())
+    total = int(sum(s.sum() for s in sets))
+    assert [int(x) for x in stats.cpu().numpy().view(np.uint64)] == [union, total - union, 0]
+    print(f"config 4 chain: {len(links)} links, {total} entries, {union} chunks written once")
