@@ -88,6 +88,8 @@ def _load():
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         lib.ora_restore_chain.restype = ctypes.c_int
         lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp]
+        lib.ora_merge_chain.restype = ctypes.c_int
+        lib.ora_merge_chain.argtypes = [vp, u64, u64, vp, u64, vp, u64, vp, u64, vp, vp]
         _lib = lib
     return _lib
 
@@ -255,6 +257,44 @@ def restore(dst: List[np.ndarray], chunk: int, staging: np.ndarray, manifest: np
                                    _p(manifest), manifest.size))
 
 
+def _links(links):
+    keep = []
+    arr = (_Link * max(1, len(links)))()
+    for i, (staging, manifest) in enumerate(links):
+        staging = np.ascontiguousarray(staging, dtype=np.uint8)
+        manifest = np.ascontiguousarray(manifest, dtype=ENTRY_DTYPE)
+        keep.append((staging, manifest))
+        arr[i] = _Link(_p(staging), staging.size, _p(manifest), manifest.size)
+    return arr, keep
+
+
+def merge_chain(sizes: Sequence[int], chunk: int, links: Sequence[Tuple[np.ndarray, np.ndarray]],
+                staging_cap: Optional[int] = None, manifest_cap: Optional[int] = None,
+                fill: int = 0xA5) -> Tuple[np.ndarray, np.ndarray, dict, dict]:
+    """Fold a chain (oldest first) into one link for buffers of the given sizes.  Returns
+    (staging, manifest, counts, stats); without capacities both are sized to the need, found by
+    a first call with none.  Bytes / entries the call does not write keep ``fill``."""
+    arr, keep = _links(links)
+    sz = np.ascontiguousarray(sizes, dtype=np.uint64)
+    c, stats = _Counts(), (ctypes.c_uint64 * 3)()
+
+    def call(staging, scap, manifest, mcap):
+        if _load().ora_merge_chain(_p(sz), sz.size, chunk, arr, len(links), _p(staging), scap,
+                                   _p(manifest), mcap, ctypes.byref(c), stats) != 0:
+            raise MemoryError("ora_merge_chain")
+
+    if staging_cap is None or manifest_cap is None:
+        call(None, 0, None, 0)
+        staging_cap = c.staged_bytes if staging_cap is None else staging_cap
+        manifest_cap = c.ndirty if manifest_cap is None else manifest_cap
+    staging = np.full(staging_cap, fill, dtype=np.uint8)
+    manifest = np.frombuffer(bytes([fill]) * (32 * manifest_cap), dtype=ENTRY_DTYPE).copy()
+    call(staging, staging_cap, manifest, manifest_cap)
+    return (staging, manifest,
+            {"ndirty": c.ndirty, "staged_bytes": c.staged_bytes, "overflow": c.overflow},
+            {"written": int(stats[0]), "superseded": int(stats[1]), "rejected": int(stats[2])})
+
+
 def restore_chain(dst: List[np.ndarray], chunk: int,
                   links: Sequence[Tuple[np.ndarray, np.ndarray]]) -> dict:
     """Apply a chain of incremental snapshots, oldest first, to ``dst`` (modified in
@@ -264,13 +304,7 @@ def restore_chain(dst: List[np.ndarray], chunk: int,
     for b in dst:
         if not b.flags["WRITEABLE"]:
             raise TypeError("destination buffers must be writable")
-    keep = []
-    arr = (_Link * max(1, len(links)))()
-    for i, (staging, manifest) in enumerate(links):
-        staging = np.ascontiguousarray(staging, dtype=np.uint8)
-        manifest = np.ascontiguousarray(manifest, dtype=ENTRY_DTYPE)
-        keep.append((staging, manifest))
-        arr[i] = _Link(_p(staging), staging.size, _p(manifest), manifest.size)
+    arr, keep = _links(links)
     stats = (ctypes.c_uint64 * 3)()
     if _load().ora_restore_chain(_desc(dst), len(dst), chunk, arr, len(links), stats) != 0:
         raise MemoryError("ora_restore_chain")

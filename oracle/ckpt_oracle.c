@@ -21,7 +21,8 @@
  *     a checksum found at another position means a device-to-device move, not
  *     a swap (ora_match, ora_apply_matches);
  *   - restore from a chain of incremental snapshots (sec. 4.6: de-dup across
- *     time), the links applied oldest first (ora_restore_chain).
+ *     time), the links applied oldest first (ora_restore_chain), and the
+ *     folding of such a chain into one link (ora_merge_chain).
  *
  * Every function is the definition written out: one loop over buffers, one
  * over chunks, memcpy for copies.  No blocking, no fusion.  The only
@@ -423,6 +424,92 @@ int ora_restore_chain(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, cons
   stats[2] = skipped;
   free(written);
   free(base);
+  return 0;
+}
+
+/* ------------------------------------------------------------ merge chain */
+/* Fold a chain of incremental snapshots into ONE link that restores to the same
+ * result (sec. 4.6: a long chain of increments is shortened by merging them;
+ * what a later increment replaced need not be kept).  The destination's bytes
+ * are not needed, only its geometry: sizes[i] is the length of buffer i.
+ * Pass one takes the links oldest first and their entries in manifest order;
+ * every entry that ora_restore_chain would apply becomes the holder of its
+ * chunk, replacing an earlier holder.  Pass two walks the chunks in ascending
+ * id: a chunk with a holder gets the next manifest entry and the next
+ * pad16(len) bytes of staging, laid out as ora_compact lays out a snapshot
+ * (bytes, then zeros to the 16-byte boundary; offsets = exclusive prefix sum),
+ * and the entry carries the holder's digest.  Capacities and counts as
+ * ora_compact; stats as ora_restore_chain.  Returns 0, or -1 without memory. */
+int ora_merge_chain(const uint64_t *sizes, uint64_t nbufs, uint64_t chunk, const ora_link_t *links,
+                    uint64_t nlinks, void *staging, uint64_t staging_cap, ora_entry_t *manifest,
+                    uint64_t manifest_cap, ora_counts_t *counts, uint64_t *stats) {
+  uint64_t n = 0;
+  uint64_t *first_chunk = (uint64_t *)malloc((nbufs + 1) * sizeof(uint64_t));
+  if (!first_chunk) return -1;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    first_chunk[i] = n;
+    n += (sizes[i] + chunk - 1) / chunk;
+  }
+  const ora_entry_t **holder = (const ora_entry_t **)calloc(n + 1, sizeof(*holder));
+  const uint8_t **bytes_of = (const uint8_t **)calloc(n + 1, sizeof(*bytes_of));
+  if (!holder || !bytes_of) {
+    free(first_chunk);
+    free(holder);
+    free(bytes_of);
+    return -1;
+  }
+  uint64_t taken = 0, held = 0, skipped = 0;
+  for (uint64_t l = 0; l < nlinks; ++l) {
+    for (uint64_t e = 0; e < links[l].nentries; ++e) {
+      const ora_entry_t *c = &links[l].manifest[e];
+      int ok = c->buf < nbufs && c->stage_off % 16 == 0 && c->buf_off % chunk == 0;
+      if (ok) ok = c->buf_off < sizes[c->buf];
+      if (ok) {
+        uint64_t rest = sizes[c->buf] - c->buf_off;
+        ok = c->len == (rest < chunk ? rest : chunk);
+      }
+      if (ok) ok = c->stage_off <= links[l].staging_bytes &&
+                   c->len <= links[l].staging_bytes - c->stage_off;
+      if (!ok) {
+        skipped += 1;
+        continue;
+      }
+      uint64_t k = first_chunk[c->buf] + c->buf_off / chunk;
+      taken += 1;
+      if (!holder[k]) held += 1;
+      holder[k] = c;
+      bytes_of[k] = (const uint8_t *)links[l].staging + c->stage_off;
+    }
+  }
+  uint8_t *merged = (uint8_t *)staging;
+  uint64_t made = 0, at = 0, missed = 0;
+  for (uint64_t k = 0; k < n; ++k) {
+    if (!holder[k]) continue;
+    uint64_t width = holder[k]->len, slot = pad16(width);
+    int entry_fits = made < manifest_cap;
+    int bytes_fit = entry_fits && at + slot <= staging_cap;
+    if (entry_fits) {
+      manifest[made] = *holder[k];
+      manifest[made].stage_off = at;
+    }
+    if (bytes_fit) {
+      memcpy(merged + at, bytes_of[k], width);
+      memset(merged + at + width, 0, slot - width);
+    } else {
+      missed += 1;
+    }
+    made += 1;
+    at += slot;
+  }
+  counts->ndirty = made;
+  counts->staged_bytes = at;
+  counts->overflow = missed;
+  stats[0] = held;
+  stats[1] = taken - held;
+  stats[2] = skipped;
+  free(first_chunk);
+  free(holder);
+  free(bytes_of);
   return 0;
 }
 

@@ -103,6 +103,14 @@ def chain_pins():
     tc.test_a_rejected_entry_of_a_later_link_leaves_the_earlier_bytes()
     tc.test_each_link_is_bounded_by_its_own_staging()
     tc.test_full_snapshot_then_deltas_from_the_oracle_path_restore_the_latest_state()
+    for seed in (1, 2, 3, 4):
+        for nlinks in (1, 2, 5):
+            tc.test_merged_link_is_the_latest_holder_of_every_chunk_in_ascending_order(seed, nlinks)
+    for seed in (5, 6):
+        tc.test_merged_link_restores_to_what_the_chain_restores_to(seed)
+    tc.test_merge_skips_what_the_chain_restore_skips_and_keeps_the_earlier_holder()
+    tc.test_merge_capacities_follow_the_compaction_rule()
+    tc.test_merge_of_nothing_is_empty()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -175,7 +183,8 @@ def use_library(path):
     good = oracle._load()
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
-               "ora_compact", "ora_restore", "ora_restore_chain", "ora_upload_owners", "ora_match",
+               "ora_compact", "ora_restore", "ora_restore_chain", "ora_merge_chain",
+               "ora_upload_owners", "ora_match",
                "ora_apply_matches", "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes

@@ -170,3 +170,104 @@ def test_full_snapshot_then_deltas_from_the_oracle_path_restore_the_latest_state
         stats = oracle.restore_chain(dst, CHUNK, links[:upto])
         assert all(np.array_equal(d, s) for d, s in zip(dst, states[upto - 1]))
         assert stats["rejected"] == 0 and stats["written"] == len(pieces(SIZES, CHUNK))
+
+
+# ---- folding a chain into one link -----------------------------------------------------------
+
+def composed_link(sizes, states, chosen, chunk):
+    """What the merged link must be, built by slicing: chunks in ascending id, each from the
+    state of the latest link that holds it; digests are the ones link_of gave that link."""
+    pcs = pieces(sizes, chunk)
+    parts, rows, soff = [], [], 0
+    for k, (i, o, n) in enumerate(pcs):
+        holders = [l for l, c in enumerate(chosen) if k in set(c.tolist())]
+        if not holders:
+            continue
+        parts += [states[holders[-1]][i][o:o + n], np.zeros((-n) % 16, np.uint8)]
+        rows.append((i, n, o, soff, 0xD16E57 + k))
+        soff += n + (-n) % 16
+    man = np.array(rows, dtype=oracle.ENTRY_DTYPE) if rows else np.zeros(0, oracle.ENTRY_DTYPE)
+    return (np.concatenate(parts) if parts else np.zeros(0, np.uint8)), man
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+@pytest.mark.parametrize("nlinks", [1, 2, 5])
+def test_merged_link_is_the_latest_holder_of_every_chunk_in_ascending_order(seed, nlinks):
+    states, chosen = random_chain(seed, nlinks)
+    # digests differ per link so that a merged entry shows which link it came from
+    links = []
+    for l, (s, c) in enumerate(zip(states, chosen)):
+        staging, man = link_of(s, CHUNK, c)
+        man["digest"] += np.uint64(l << 32)
+        links.append((staging, man))
+    staging, man, counts, stats = oracle.merge_chain(SIZES, CHUNK, links)
+    want_staging, want_man = composed_link(SIZES, states, chosen, CHUNK)
+    pcs = pieces(SIZES, CHUNK)
+    for row in want_man:                      # the digest of the holder: its link's offset added
+        k = pcs.index((int(row["buf"]), int(row["buf_off"]), int(row["len"])))
+        row["digest"] += np.uint64(max(l for l, c in enumerate(chosen) if k in set(c.tolist())) << 32)
+    assert np.array_equal(staging, want_staging)
+    assert man.tolist() == want_man.tolist()
+    union = set().union(*[set(c.tolist()) for c in chosen])
+    assert counts == {"ndirty": len(union), "staged_bytes": want_staging.size, "overflow": 0}
+    assert stats == {"written": len(union), "superseded": sum(c.size for c in chosen) - len(union),
+                     "rejected": 0}
+    # offsets: exclusive prefix sum of the padded lengths, strictly increasing
+    pad = (man["len"].astype(np.uint64) + 15) // 16 * 16
+    assert np.array_equal(man["stage_off"], np.concatenate([[0], np.cumsum(pad)[:-1]]).astype(np.uint64))
+
+
+@pytest.mark.parametrize("seed", [5, 6])
+def test_merged_link_restores_to_what_the_chain_restores_to(seed):
+    """Applied to the same destination, the one merged link and the whole chain give the same
+    bytes (the destination is compared with the NumPy composition, not with the other call)."""
+    states, chosen = random_chain(seed, 4)
+    links = [link_of(s, CHUNK, c) for s, c in zip(states, chosen)]
+    staging, man, _, _ = oracle.merge_chain(SIZES, CHUNK, links)
+    start = [np.full(n, 0x42, np.uint8) for n in SIZES]
+    want = composed(start, states, chosen, CHUNK)
+    dst = [b.copy() for b in start]
+    assert oracle.restore(dst, CHUNK, staging, man) == 0
+    assert all(np.array_equal(d, w) for d, w in zip(dst, want))
+
+
+def test_merge_skips_what_the_chain_restore_skips_and_keeps_the_earlier_holder():
+    states, _ = random_chain(13, 2)
+    n = len(pieces(SIZES, CHUNK))
+    links = [link_of(s, CHUNK, np.arange(n)) for s in states]
+    links[1][1]["buf"][3] = 99                # no such buffer
+    links[1][1]["len"][5] -= 16               # not the whole chunk
+    links[1][1]["stage_off"][7] = links[1][0].size       # past its staging
+    staging, man, counts, stats = oracle.merge_chain(SIZES, CHUNK, links)
+    assert stats == {"written": n, "superseded": n - 3, "rejected": 3} and counts["ndirty"] == n
+    dst = [np.zeros(s, np.uint8) for s in SIZES]
+    assert oracle.restore(dst, CHUNK, staging, man) == 0
+    for k, (i, o, ln) in enumerate(pieces(SIZES, CHUNK)):
+        assert np.array_equal(dst[i][o:o + ln], states[0 if k in (3, 5, 7) else 1][i][o:o + ln])
+
+
+def test_merge_capacities_follow_the_compaction_rule():
+    """Entry e is written only if e < manifest_cap, its bytes only if they also end inside
+    staging_cap; every chunk not fully staged counts as overflow; the need is always reported."""
+    states, chosen = random_chain(3, 3)
+    links = [link_of(s, CHUNK, c) for s, c in zip(states, chosen)]
+    full_staging, full_man, full_counts, _ = oracle.merge_chain(SIZES, CHUNK, links)
+    m = full_man.size
+    assert m > 6
+    for mcap, scap in ((m - 2, full_staging.size), (m, int(full_man["stage_off"][4]) + 100),
+                       (3, int(full_man["stage_off"][5])), (0, 0)):
+        staging, man, counts, _ = oracle.merge_chain(SIZES, CHUNK, links, scap, mcap, fill=0xA5)
+        fit_e = min(m, mcap)
+        pad = (full_man["len"].astype(np.int64) + 15) // 16 * 16
+        fit_b = int(np.sum((full_man["stage_off"].astype(np.int64) + pad <= scap)[:fit_e]))
+        assert counts == {"ndirty": m, "staged_bytes": full_counts["staged_bytes"], "overflow": m - fit_b}
+        assert man[:fit_e].tolist() == full_man[:fit_e].tolist()
+        end = int(full_man["stage_off"][fit_b - 1] + pad[fit_b - 1]) if fit_b else 0
+        assert np.array_equal(staging[:end], full_staging[:end]) and np.all(staging[end:] == 0xA5)
+
+
+def test_merge_of_nothing_is_empty():
+    staging, man, counts, stats = oracle.merge_chain(SIZES, CHUNK, [])
+    assert staging.size == 0 and man.size == 0
+    assert counts == {"ndirty": 0, "staged_bytes": 0, "overflow": 0}
+    assert stats == {"written": 0, "superseded": 0, "rejected": 0}

@@ -88,6 +88,19 @@ MUTATIONS = [
      "stats[1] = applied;"),
     ("chain: skipped entries not counted", "        skipped += 1;\n        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]",
      "        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]"),
+    ("merge: entry of the first holder, bytes of the last", "      holder[k] = c;\n",
+     "      if (!holder[k]) holder[k] = c;\n"),
+    ("merge: bytes taken from the first link's staging",
+     "bytes_of[k] = (const uint8_t *)links[l].staging + c->stage_off;",
+     "bytes_of[k] = (const uint8_t *)links[0].staging + c->stage_off;"),
+    ("merge: entry keeps its old staging offset", "manifest[made].stage_off = at;", "(void)0;"),
+    ("merge: offsets unpadded", "    at += slot;\n", "    at += width;\n"),
+    ("merge: padding not zeroed", "memset(merged + at + width, 0, slot - width);", "(void)0;"),
+    ("merge: staging capacity ignored in the overflow count",
+     "int bytes_fit = entry_fits && at + slot <= staging_cap;",
+     "int bytes_fit = entry_fits && at <= staging_cap;"),
+    ("merge: shortened chunks accepted", "ok = c->len == (rest < chunk ? rest : chunk);",
+     "ok = c->len <= (rest < chunk ? rest : chunk);"),
     ("owner: row stride of gathered checksums", "if (gathered[(uint64_t)r * N + k] != mine) continue;",
      "if (gathered[(uint64_t)r * (N - 1) + k] != mine) continue;"),
 ]
