@@ -486,6 +486,30 @@ def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
     ms_chain = timed(lambda: ck.restore_chain(plan, links, ws, stats))
     written, superseded, rejected = (int(x) for x in stats.cpu().numpy().view(np.uint64))
     assert rejected == 0 and superseded == sum(int(l[4][0]) for l in links) - written
+
+    # the same chain folded into one link (ckpt_merge_chain), then that link restored
+    m_staging = torch.empty(max(staged), dtype=torch.uint8, device=dev)
+    m_manifest = torch.empty(written * 32, dtype=torch.uint8, device=dev)
+    m_counts = torch.zeros(3, dtype=torch.int64, device=dev)
+    m_ws = torch.empty(ck.merge_chain_workspace_bytes(n), dtype=torch.uint8, device=dev)
+
+    def merge():
+        ck.merge_chain(plan, links, m_staging, m_manifest, m_counts, m_ws)
+
+    merge()
+    e0, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+    e0.record()
+    for _ in range(5):
+        merge()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_merge = e0.elapsed_time(e1) / 5
+    mc = [int(x) for x in m_counts.cpu().numpy().view(np.uint64)]
+    assert mc == [written, staged[-1], 0], mc
+    image.copy_(replicas[0].arena)
+    ck.restore_counted(plan, m_staging, mc[1], m_manifest, written, m_counts)
+    torch.cuda.synchronize()
+    assert torch.equal(image, pairs[-1][1].arena)
     return {
         "workload": f"config{w.config}_{w.name}: chain of {len(links)} deltas restored into a copy "
                     "of the reference replica",
@@ -495,6 +519,9 @@ def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
         "restore_chain_ms": round(ms_chain, 3),
         "speedup": round(ms_each / ms_chain, 2),
         "restore_chain_hbm_GBps_read_plus_write": round(2 * staged[-1] / ms_chain / 1e6, 1),
+        "merge_chain_ms": round(ms_merge, 3),
+        "merge_chain_hbm_GBps_read_plus_write": round(2 * mc[1] / ms_merge / 1e6, 1),
+        "merged_link_bytes": mc[1],
         "image_equals_last_replica": True,
     }
 

@@ -95,8 +95,8 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  *               fingerprint runs at a fraction of the memory bandwidth
  *   out         receives the plan; destroy it with ckpt_plan_destroy
  * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
- * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_upload_owners, ckpt_swap_out
- * and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered
+ * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_merge_chain, ckpt_upload_owners,
+ * ckpt_swap_out and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered
  * (one stream, or events); issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
  * the other calls only read the plan and may overlap freely.
  * Two non-empty buffers that share a byte are refused (INVALID_ARG): restoring
@@ -376,6 +376,32 @@ uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks);
 int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
                        void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
                        void *stream);
+
+/* Folds a chain into ONE link that restores to the same result, so that a chain
+ * of increments (sec. 4.6) can be kept short: what a later link replaced is
+ * dropped.  The chunks any link holds (rule and order as ckpt_restore_chain: the
+ * last whole-chunk entry of the chain wins) are laid out exactly as
+ * ckpt_compact lays out a snapshot: ascending chunk id, entry e at
+ *   stage_off[0] = 0, stage_off[e+1] = stage_off[e] + pad16(len[e]),
+ * bytes followed by zeros up to a multiple of 16, the entry carrying the
+ * winning entry's digest.  The plan supplies the geometry only; its buffers are
+ * neither read nor written, so the state itself need not be resident.
+ *   d_staging, staging_cap     receives the merged bytes; 16-byte aligned, must
+ *                              not overlap a link's staging area
+ *   d_manifest, manifest_cap   receives the merged entries
+ *   d_counts     ndirty = chunks held, staged_bytes = bytes needed (both the
+ *                full need), overflow = chunks not fully staged; capacity rule
+ *                as ckpt_compact
+ *   d_workspace  at least ckpt_merge_chain_workspace_bytes(N) bytes, 16-byte
+ *                aligned
+ *   d_stats      optional, as ckpt_restore_chain (written = chunks held)
+ * Uses the plan's scan scratch like ckpt_compact.
+ * Errors: INVALID_ARG, ALIGNMENT, CAPACITY (workspace too small), DEVICE. */
+uint64_t ckpt_merge_chain_workspace_bytes(uint64_t nchunks);
+int ckpt_merge_chain(const ckpt_plan_t *plan, const ckpt_link_t *links, uint64_t nlinks,
+                     void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                     uint64_t manifest_cap, ckpt_counts_t *d_counts, void *d_workspace,
+                     uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats, void *stream);
 
 /* ---- content-addressed comparison (the paper's own rule) ------------------- */
 

@@ -27,6 +27,7 @@ EXPORTS = (
     "ckpt_plan_create", "ckpt_plan_destroy", "ckpt_plan_nchunks", "ckpt_plan_nbytes",
     "ckpt_plan_nbufs", "ckpt_plan_chunk_bytes", "ckpt_fingerprint", "ckpt_diff", "ckpt_compact", "ckpt_manifest", "ckpt_exchange",
     "ckpt_restore", "ckpt_restore_counted", "ckpt_restore_chain_workspace_bytes", "ckpt_restore_chain",
+    "ckpt_merge_chain_workspace_bytes", "ckpt_merge_chain",
     "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
@@ -100,6 +101,10 @@ def _lib():
         lib.ckpt_restore_chain_workspace_bytes.argtypes = [u64]
         lib.ckpt_restore_chain.restype = ci
         lib.ckpt_restore_chain.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_merge_chain_workspace_bytes.restype = u64
+        lib.ckpt_merge_chain_workspace_bytes.argtypes = [u64]
+        lib.ckpt_merge_chain.restype = ci
+        lib.ckpt_merge_chain.argtypes = [vp, vp, u64, vp, u64, vp, u64, vp, vp, u64, vp, vp]
         lib.ckpt_plan_split_threshold.restype = u64
         lib.ckpt_plan_split_threshold.argtypes = [vp]
         lib.ckpt_plan_set_split_threshold.restype = ci
@@ -356,13 +361,37 @@ def restore_chain_workspace_bytes(nchunks: int) -> int:
     return int(_lib().ckpt_restore_chain_workspace_bytes(nchunks))
 
 
+def _links(links):
+    arr = (_Link * max(1, len(links)))()
+    for i, (staging, staging_bytes, manifest, cap, counts) in enumerate(links):
+        arr[i] = _Link(_ptr(staging), staging_bytes, _ptr(manifest), cap, _ptr(counts))
+    return arr
+
+
+def merge_chain_workspace_bytes(nchunks: int) -> int:
+    return int(_lib().ckpt_merge_chain_workspace_bytes(nchunks))
+
+
+def merge_chain(plan: Plan, links, staging, manifest, counts, workspace, stats=None, stream=None,
+                staging_cap: Optional[int] = None, manifest_cap: Optional[int] = None) -> None:
+    """``ckpt_merge_chain``: links as for ``restore_chain``; staging / manifest / counts as for
+    ``compact``."""
+    if staging_cap is None:
+        staging_cap = 0 if staging is None else staging.numel() * staging.element_size()
+    if manifest_cap is None:
+        manifest_cap = 0 if manifest is None else \
+            manifest.numel() * manifest.element_size() // ENTRY_BYTES
+    _check(_lib().ckpt_merge_chain(plan._h, _links(links), len(links), _ptr(staging), staging_cap,
+                                   _ptr(manifest), manifest_cap, _ptr(counts), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _ptr(stats),
+                                   _stream(stream)), "ckpt_merge_chain")
+
+
 def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None) -> None:
     """``ckpt_restore_chain``: ``links`` is a sequence, oldest first, of
     (staging, staging_bytes, manifest, manifest_cap, counts or None); workspace is a uint8
     tensor, stats (optional) 3 x int64."""
-    arr = (_Link * max(1, len(links)))()
-    for i, (staging, staging_bytes, manifest, cap, counts) in enumerate(links):
-        arr[i] = _Link(_ptr(staging), staging_bytes, _ptr(manifest), cap, _ptr(counts))
+    arr = _links(links)
     _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _ptr(stats),
                                      _stream(stream)), "ckpt_restore_chain")

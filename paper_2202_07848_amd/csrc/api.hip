@@ -539,14 +539,15 @@ int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uin
 
 uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks) { return 16 * nchunks + 16; }
 
-int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
-                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
-                       void *stream) {
-  if (dst_plan == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+}  // extern "C"
+
+namespace {
+
+// Host checks of a chain and its translation into kernel arguments.
+int chain_args(const ckpt_link_t *links, uint64_t nlinks, ckpt::ChainArgs *a) {
   if (nlinks > CKPT_CHAIN_MAX || (nlinks != 0 && links == nullptr)) return CKPT_ERR_INVALID_ARG;
-  if (!aligned(d_workspace, 16) || !aligned(d_stats, 8)) return CKPT_ERR_ALIGNMENT;
-  ckpt::ChainArgs a{};
-  a.nlinks = (uint32_t)nlinks;
+  *a = ckpt::ChainArgs{};
+  a->nlinks = (uint32_t)nlinks;
   for (uint64_t l = 0; l < nlinks; ++l) {
     const ckpt_link_t &k = links[l];
     if (k.manifest_cap != 0 && k.d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
@@ -554,17 +555,59 @@ int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, ui
     if (k.manifest_cap >= (1ull << 40)) return CKPT_ERR_INVALID_ARG;
     if (!aligned(k.d_staging, 16) || !aligned(k.d_manifest, 8) || !aligned(k.d_counts, 8))
       return CKPT_ERR_ALIGNMENT;
-    a.staging[l] = static_cast<const uint8_t *>(k.d_staging);
-    a.staging_bytes[l] = k.staging_bytes;
-    a.manifest[l] = k.d_manifest;
-    a.cap[l] = k.manifest_cap;
-    a.counts[l] = k.d_counts;
+    a->staging[l] = static_cast<const uint8_t *>(k.d_staging);
+    a->staging_bytes[l] = k.staging_bytes;
+    a->manifest[l] = k.d_manifest;
+    a->cap[l] = k.manifest_cap;
+    a->counts[l] = k.d_counts;
   }
+  return CKPT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
+                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
+                       void *stream) {
+  if (dst_plan == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_workspace, 16) || !aligned(d_stats, 8)) return CKPT_ERR_ALIGNMENT;
+  ckpt::ChainArgs a;
+  const int rc = chain_args(links, nlinks, &a);
+  if (rc != CKPT_OK) return rc;
   if (workspace_bytes < ckpt_restore_chain_workspace_bytes(dst_plan->dev.nchunks))
     return CKPT_ERR_CAPACITY;
   hipError_t e = ckpt::launch_restore_chain(dst_plan->dev, a, static_cast<uint64_t *>(d_workspace),
                                             reinterpret_cast<uint64_t *>(d_stats),
                                             static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
+uint64_t ckpt_merge_chain_workspace_bytes(uint64_t nchunks) {
+  return 16 * nchunks + 16 + ((nchunks + 15) & ~15ull);
+}
+
+int ckpt_merge_chain(const ckpt_plan_t *plan, const ckpt_link_t *links, uint64_t nlinks,
+                     void *d_staging, uint64_t staging_cap, ckpt_entry_t *d_manifest,
+                     uint64_t manifest_cap, ckpt_counts_t *d_counts, void *d_workspace,
+                     uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats, void *stream) {
+  if (plan == nullptr || d_workspace == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (staging_cap != 0 && d_staging == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (manifest_cap != 0 && d_manifest == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_workspace, 16) || !aligned(d_stats, 8) || !aligned(d_staging, 16) ||
+      !aligned(d_manifest, 8) || !aligned(d_counts, 8))
+    return CKPT_ERR_ALIGNMENT;
+  ckpt::ChainArgs a;
+  const int rc = chain_args(links, nlinks, &a);
+  if (rc != CKPT_OK) return rc;
+  if (workspace_bytes < ckpt_merge_chain_workspace_bytes(plan->dev.nchunks))
+    return CKPT_ERR_CAPACITY;
+  hipError_t e = ckpt::launch_merge_chain(plan->dev, a, d_staging, staging_cap, d_manifest,
+                                          manifest_cap, d_counts,
+                                          static_cast<uint64_t *>(d_workspace), plan->d_blocksums,
+                                          reinterpret_cast<uint64_t *>(d_stats),
+                                          static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 

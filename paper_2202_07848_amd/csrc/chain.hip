@@ -148,6 +148,91 @@ __global__ __launch_bounds__(COPY_THREADS) void k_chain_move(
   }
 }
 
+// Merge, step one: mask[k] = chunk k has a holder; dig[k] = the holder's digest.  These two feed
+// the compaction scan, which lays the merged link out like a snapshot.
+__global__ __launch_bounds__(256) void k_chain_mask(ChainArgs a,
+                                                    const unsigned long long *__restrict__ last,
+                                                    uint64_t n, uint8_t *__restrict__ mask,
+                                                    uint64_t *__restrict__ dig) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) {
+    const unsigned long long key = last[k];
+    uint64_t d = 0;
+    if (key != 0) {
+      const uint32_t l = (uint32_t)(key >> CHAIN_ENTRY_BITS) - 1;
+      if (l < a.nlinks) d = a.manifest[l][key & ((1ull << CHAIN_ENTRY_BITS) - 1)].digest;
+    }
+    mask[k] = key != 0;
+    dig[k] = d;
+  }
+}
+
+// Merge, step two: the bytes.  Work item = one piece of one entry of the merged manifest (written
+// by the scan just before); the chunk's key names the link and entry that hold its bytes, which
+// go to the merged staging area zero padded to 16, if they fit below staging_cap.
+__global__ __launch_bounds__(COPY_THREADS) void k_chain_gather(
+    PlanDev p, ChainArgs a, const unsigned long long *__restrict__ last,
+    const ckpt_entry_t *__restrict__ merged, uint64_t manifest_cap,
+    const ckpt_counts_t *__restrict__ counts, uint8_t *__restrict__ staging, uint64_t staging_cap) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave_in_group = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t nwaves = (uint64_t)gridDim.x * (COPY_THREADS / 64);
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  const uint32_t ppc_log2 = p.chunk_log2 - piece_log2;
+  uint64_t nentries = counts->ndirty;
+  if (nentries > manifest_cap) nentries = manifest_cap;
+  const uint64_t nitems = nentries << ppc_log2;
+
+  for (uint64_t item = (uint64_t)blockIdx.x * (COPY_THREADS / 64) + wave_in_group; item < nitems;
+       item += nwaves) {
+    const ckpt_entry_t m = merged[item >> ppc_log2];
+    const uint32_t piece = (uint32_t)(item & ((1ull << ppc_log2) - 1));
+    const uint64_t padded = pad16(m.len);
+    if (m.buf >= p.nbufs || m.stage_off > staging_cap || padded > staging_cap - m.stage_off)
+      continue;                                              // does not fit: counted as overflow
+    const unsigned long long key = last[p.list_base[m.buf] + (m.buf_off >> p.chunk_log2)];
+    const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(key >> CHAIN_ENTRY_BITS)) - 1;
+    if (l >= a.nlinks) continue;                             // cannot happen: the mask came from the keys
+    const ckpt_entry_t t = a.manifest[l][key & ((1ull << CHAIN_ENTRY_BITS) - 1)];
+    uint64_t k;
+    if (!whole_chunk(p, t, a.staging_bytes[l], &k)) continue;   // the same test as in k_chain_mark
+    const uint32_t lo = piece << piece_log2;
+    uint32_t hi = lo + (1u << piece_log2);
+    if (hi > padded) hi = (uint32_t)padded;
+    move_piece<true>(a.staging[l] + t.stage_off, staging + m.stage_off, lo, hi, t.len, lane);
+  }
+}
+
+}  // namespace
+
+namespace {
+
+uint32_t groups_for(uint64_t n, uint64_t per_group, uint64_t most) {
+  const uint64_t g = (n + per_group - 1) / per_group;
+  return (uint32_t)(g > most ? most : (g == 0 ? 1 : g));
+}
+
+// clear + mark.  *entries receives the host bound on the entries of all links together; zero
+// means no link can hold anything.
+hipError_t launch_chain_keys(const PlanDev &p, const ChainArgs &a, unsigned long long *last,
+                             unsigned long long *count, unsigned long long *stats,
+                             uint64_t *entries, hipStream_t s) {
+  hipLaunchKernelGGL(k_chain_clear, dim3(groups_for(p.nchunks, 256 * 8, 4096)), dim3(256), 0, s,
+                     last, p.nchunks, count, stats);
+  hipError_t e = hipGetLastError();
+  uint64_t most = 0, sum = 0;
+  for (uint32_t l = 0; l < a.nlinks; ++l) {
+    most = a.cap[l] > most ? a.cap[l] : most;
+    sum += a.cap[l];
+  }
+  *entries = sum;
+  if (e != hipSuccess || most == 0) return e;
+  // with an empty destination this still counts every entry as skipped
+  hipLaunchKernelGGL(k_chain_mark, dim3(groups_for(most, 256, 2048), a.nlinks), dim3(256), 0, s, p,
+                     a, last, stats);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
@@ -156,26 +241,10 @@ hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *
   unsigned long long *last = reinterpret_cast<unsigned long long *>(d_workspace);
   unsigned long long *list = last + p.nchunks;
   unsigned long long *count = list + p.nchunks;
-  unsigned long long *stats = reinterpret_cast<unsigned long long *>(d_stats);
-  auto groups_for = [](uint64_t n, uint64_t per_group, uint64_t most) {
-    uint64_t g = (n + per_group - 1) / per_group;
-    return (uint32_t)(g > most ? most : (g == 0 ? 1 : g));
-  };
-  hipLaunchKernelGGL(k_chain_clear, dim3(groups_for(p.nchunks, 256 * 8, 4096)), dim3(256), 0, s,
-                     last, p.nchunks, count, stats);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || a.nlinks == 0) return e;
-
-  uint64_t most = 0, sum = 0;                      // host bounds on the entries of a link / of all
-  for (uint32_t l = 0; l < a.nlinks; ++l) {
-    most = a.cap[l] > most ? a.cap[l] : most;
-    sum += a.cap[l];
-  }
-  if (most == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_chain_mark, dim3(groups_for(most, 256, 2048), a.nlinks), dim3(256), 0, s, p,
-                     a, last, stats);
-  e = hipGetLastError();
-  if (e != hipSuccess || p.nchunks == 0) return e;   // an empty destination: entries counted, none applied
+  uint64_t entries = 0;
+  hipError_t e = launch_chain_keys(p, a, last, count, reinterpret_cast<unsigned long long *>(d_stats),
+                                   &entries, s);
+  if (e != hipSuccess || entries == 0 || p.nchunks == 0) return e;
 
   hipLaunchKernelGGL(k_chain_list, dim3(groups_for(p.nchunks, 256, 4096)), dim3(256), 0, s, last,
                      p.nchunks, list, count);
@@ -183,11 +252,43 @@ hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *
   if (e != hipSuccess) return e;
 
   const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
-  const uint64_t chunks = sum < p.nchunks ? sum : p.nchunks;        // at most this many are listed
+  const uint64_t chunks = entries < p.nchunks ? entries : p.nchunks;   // at most this many are listed
   const uint64_t items = chunks << (p.chunk_log2 - piece_log2);
   hipLaunchKernelGGL(k_chain_move,
                      dim3(groups_for(items, COPY_THREADS / 64, COPY_MAX_GROUPS)),
                      dim3(COPY_THREADS), 0, s, p, a, list, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_staging,
+                              uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                              ckpt_counts_t *d_counts, uint64_t *d_workspace, uint64_t *d_pairs,
+                              uint64_t *d_stats, hipStream_t s) {
+  // workspace: last[N], dig[N], one spare word, mask[N]
+  unsigned long long *last = reinterpret_cast<unsigned long long *>(d_workspace);
+  uint64_t *dig = d_workspace + p.nchunks;
+  unsigned long long *spare = last + 2 * p.nchunks;
+  uint8_t *mask = reinterpret_cast<uint8_t *>(spare + 2);
+  uint64_t entries = 0;
+  hipError_t e = launch_chain_keys(p, a, last, spare, reinterpret_cast<unsigned long long *>(d_stats),
+                                   &entries, s);
+  if (e != hipSuccess) return e;
+  if (p.nchunks != 0)
+    hipLaunchKernelGGL(k_chain_mask, dim3(groups_for(p.nchunks, 256, 4096)), dim3(256), 0, s, a,
+                       last, p.nchunks, mask, dig);
+  e = launch_compact_scan(p, mask, dig, staging_cap, d_manifest, manifest_cap, d_pairs, d_counts,
+                          nullptr, nullptr, false, s);
+  if (e != hipSuccess || entries == 0 || p.nchunks == 0) return e;
+
+  const uint32_t piece_log2 = p.chunk_log2 < COPY_PIECE_LOG2 ? p.chunk_log2 : COPY_PIECE_LOG2;
+  uint64_t chunks = entries < p.nchunks ? entries : p.nchunks;
+  if (chunks > manifest_cap) chunks = manifest_cap;
+  if (chunks == 0) return hipSuccess;
+  const uint64_t items = chunks << (p.chunk_log2 - piece_log2);
+  hipLaunchKernelGGL(k_chain_gather,
+                     dim3(groups_for(items, COPY_THREADS / 64, COPY_MAX_GROUPS)),
+                     dim3(COPY_THREADS), 0, s, p, a, last, d_manifest, manifest_cap, d_counts,
+                     reinterpret_cast<uint8_t *>(d_staging), staging_cap);
   return hipGetLastError();
 }
 

@@ -191,6 +191,12 @@ struct ChainArgs {
 // d_workspace: 2 N + 1 uint64 (scratch); d_stats (may be null): written, superseded, skipped.
 hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
                                 uint64_t *d_stats, hipStream_t s);
+// Folds the chain into one link laid out like a snapshot's.  d_workspace: 2 N + 2 uint64 and N
+// bytes (scratch); d_pairs: the plan's scan scratch.
+hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_staging,
+                              uint64_t staging_cap, ckpt_entry_t *d_manifest, uint64_t manifest_cap,
+                              ckpt_counts_t *d_counts, uint64_t *d_workspace, uint64_t *d_pairs,
+                              uint64_t *d_stats, hipStream_t s);
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);

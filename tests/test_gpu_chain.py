@@ -315,3 +315,167 @@ def test_chain_restore_replays_from_a_hip_graph_with_changing_entry_counts():
         assert dst.canaries_intact(img), replay
         v = stats.cpu().numpy().view(np.uint64)
         assert {"written": int(v[0]), "superseded": int(v[1]), "rejected": int(v[2])} == want_stats
+
+
+# ---- folding a chain into one link -----------------------------------------------------------
+
+def run_merge(plan, dev_links, staging_cap, manifest_cap, fill=0xA5, slack=256):
+    import torch
+    from paper_2202_07848_amd import binding as ck
+    staging = torch.full((staging_cap + slack,), fill, dtype=torch.uint8, device="cuda")
+    manifest = torch.full((manifest_cap * 32 + slack,), fill, dtype=torch.uint8, device="cuda")
+    counts = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    stats = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    ws = torch.full((ck.merge_chain_workspace_bytes(plan.nchunks) + 16,), 0xEE, dtype=torch.uint8,
+                    device="cuda")
+    ck.merge_chain(plan, dev_links, staging, manifest, counts, ws, stats, staging_cap=staging_cap,
+                   manifest_cap=manifest_cap)
+    torch.cuda.synchronize()
+    c = counts.cpu().numpy().view(np.uint64)
+    v = stats.cpu().numpy().view(np.uint64)
+    return (staging.cpu().numpy(), manifest.cpu().numpy(),
+            {"ndirty": int(c[0]), "staged_bytes": int(c[1]), "overflow": int(c[2])},
+            {"written": int(v[0]), "superseded": int(v[1]), "rejected": int(v[2])})
+
+
+def check_merge(sizes, chunk, links, caps=None, fill=0xA5):
+    """GPU merge against the oracle's: staging and manifest byte for byte including the untouched
+    fill behind what was written and the slack behind the capacities, counts and stats."""
+    from gpu_util import DeviceBuffers
+    if caps is None:
+        o_st, o_man, o_counts, o_stats = oracle.merge_chain(sizes, chunk, links, fill=fill)
+        caps = (o_st.size, o_man.size)
+    else:
+        o_st, o_man, o_counts, o_stats = oracle.merge_chain(sizes, chunk, links, caps[0], caps[1],
+                                                            fill=fill)
+    geometry = DeviceBuffers([np.full(n, 0x31, np.uint8) for n in sizes], chunk)
+    before = geometry.arena.clone()
+    st, man, counts, stats = run_merge(geometry.plan, upload(links), caps[0], caps[1], fill)
+    assert counts == o_counts and stats == o_stats
+    assert np.array_equal(st[:caps[0]], o_st) and np.all(st[caps[0]:] == fill)
+    assert np.array_equal(man[:caps[1] * 32], o_man.view(np.uint8).reshape(-1))
+    assert np.all(man[caps[1] * 32:] == fill)
+    import torch
+    assert torch.equal(before, geometry.arena)            # the plan's buffers are not touched
+    return o_st, o_man, o_counts, o_stats
+
+
+@pytest.mark.parametrize("chunk,sizes,span", [
+    (256, [5000, 256, 0, 1300, 77, 4096, 16, 100000], 700),
+    (4096, [40000, 4096, 123457, 0, 8192, 70001, 1, 4095, 4097], 3000),
+    (65536, [1 << 20, 65536, 200001, 0, 65535, 65537, 3 << 16, 48], 50000),
+    (1 << 20, [(3 << 20) + 4321, 1 << 20, 77777, (2 << 20) - 16], 300000),
+])
+@pytest.mark.parametrize("nlinks", [1, 3, 5])
+def test_merge_of_chains_from_the_snapshot_path(chunk, sizes, span, nlinks):
+    rng = np.random.default_rng(chunk % 1000 + 7 * nlinks)
+    states = [[rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]]
+    for s in range(nlinks):
+        states.append(evolve(rng, states[-1], 3 + 2 * s, span))
+    links = oracle_links(states, chunk, first_is_full=False)      # deltas only
+    st, man, counts, stats = check_merge(sizes, chunk, links)
+    assert stats["rejected"] == 0 and 0 < counts["ndirty"] < oracle.nchunks(states[0], chunk)
+    # the merged link, applied to the first state, gives the last one
+    dst = [b.copy() for b in states[0]]
+    assert oracle.restore(dst, chunk, st, man) == 0
+    assert all(np.array_equal(d, s) for d, s in zip(dst, states[-1]))
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_merge_of_random_subsets_in_sixteen_links(seed):
+    from paper_2202_07848_amd import binding as ck
+    sizes, chunk = [9000, 512, 0, 2600, 150, 8192, 33000], 512
+    rng = np.random.default_rng(seed)
+    n = sum((s + chunk - 1) // chunk for s in sizes)
+    links = []
+    for _ in range(ck.CHAIN_MAX):
+        state = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes]
+        chosen = np.sort(rng.choice(n, size=int(rng.integers(0, n // 3)), replace=False))
+        links.append(sliced_link(state, chunk, chosen.tolist()))
+    _, _, counts, stats = check_merge(sizes, chunk, links)
+    assert stats["superseded"] > 0 and counts["ndirty"] == stats["written"] < n
+
+
+def test_merge_with_bad_entries_unsorted_manifests_and_a_chunk_held_twice():
+    sizes, chunk = [5000, 256, 0, 1300, 77, 4096], 256
+    rng = np.random.default_rng(11)
+    a = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes]
+    b = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes]
+    n = sum((s + chunk - 1) // chunk for s in sizes)
+    sa, ma = sliced_link(a, chunk, list(range(0, n, 2))[::-1])           # descending
+    sb, mb = sliced_link(b, chunk, [3, 5, 3, 11, 5, 18, 7, 9, 21])
+    mb["len"][6] = 240                        # chunk 7: not the whole chunk
+    mb["buf_off"][7] += 16                    # chunk 9: inside a chunk
+    mb["buf"][8] = len(sizes)                 # no such buffer
+    again = ma[[0, 1]].copy()                 # two more holders inside link b, with a's bytes
+    again["stage_off"] += sb.size
+    twice = (np.concatenate([sb, sa]), np.concatenate([mb, again]))
+    _, _, _, stats = check_merge(sizes, chunk, [(sa, ma), twice])
+    assert stats["rejected"] == 3
+
+
+def test_merge_capacities():
+    sizes, chunk = [5000, 256, 1300, 4096, 77], 256
+    rng = np.random.default_rng(29)
+    states = [[rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes] for _ in range(3)]
+    n = sum((s + chunk - 1) // chunk for s in sizes)
+    links = [sliced_link(s, chunk, sorted(rng.choice(n, size=n // 2, replace=False).tolist()))
+             for s in states]
+    st, man, counts, _ = check_merge(sizes, chunk, links)
+    m = man.size
+    for caps in ((st.size, m - 2), (int(man["stage_off"][4]) + 100, m), (int(man["stage_off"][5]), 3),
+                 (st.size - 16, m), (0, 0), (st.size + 4096, m + 9)):
+        _, _, c, _ = check_merge(sizes, chunk, links, caps)
+        assert c["ndirty"] == m and c["staged_bytes"] == counts["staged_bytes"]
+
+
+def test_merge_of_nothing_and_argument_checks():
+    import torch
+    from gpu_util import DeviceBuffers
+    from paper_2202_07848_amd import binding as ck
+    sizes, chunk = [5000, 256], 256
+    _, _, counts, stats = check_merge(sizes, chunk, [])
+    assert counts == {"ndirty": 0, "staged_bytes": 0, "overflow": 0}
+    empty = (np.zeros(0, np.uint8), np.zeros(0, oracle.ENTRY_DTYPE))
+    check_merge(sizes, chunk, [empty, empty])
+    geometry = DeviceBuffers([np.zeros(n, np.uint8) for n in sizes], chunk)
+    link = upload([sliced_link([np.zeros(n, np.uint8) for n in sizes], chunk, [0, 1])])[0]
+    ws = torch.zeros(ck.merge_chain_workspace_bytes(geometry.plan.nchunks) + 16, dtype=torch.uint8,
+                     device="cuda")
+    out = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    man = torch.zeros(4 * 32, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    for args, status in (((geometry.plan, [link], out, man, None, ws), -1),
+                         ((geometry.plan, [link] * 17, out, man, counts, ws), -1),
+                         ((geometry.plan, [link], out, man, counts, ws[:64]), -5),
+                         ((geometry.plan, [link], out[8:], man, counts, ws), -2),
+                         ((geometry.plan, [link], out, man, counts, ws[8:]), -2)):
+        with pytest.raises(ck.CkptError) as e:
+            ck.merge_chain(*args)
+        assert e.value.status == status
+
+
+def test_merged_link_through_the_device_restore_equals_the_chain_restore():
+    """merge then ckpt_restore == ckpt_restore_chain, on the device, and both equal the last
+    state of the chain."""
+    import torch
+    from gpu_util import DeviceBuffers
+    from paper_2202_07848_amd import binding as ck
+    sizes, chunk = [300000, 65536, 0, 99999, 70000], 4096
+    rng = np.random.default_rng(37)
+    states = [[rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]]
+    for s in range(5):
+        states.append(evolve(rng, states[-1], 6 + s, 20000))
+    dev = upload(oracle_links(states, chunk, first_is_full=False))
+    one, two = (DeviceBuffers(states[0], chunk) for _ in range(2))
+    n = one.plan.nchunks
+    staging = torch.zeros(n * chunk, dtype=torch.uint8, device="cuda")
+    manifest = torch.zeros(n * 32, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    ws = torch.zeros(ck.merge_chain_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ck.merge_chain(one.plan, dev, staging, manifest, counts, ws)
+    ck.restore_counted(one.plan, staging, staging.numel(), manifest, n, counts)
+    run_chain(two, dev)
+    assert torch.equal(one.arena, two.arena)
+    got, _ = one.host()
+    assert all(np.array_equal(g, s) for g, s in zip(got, states[-1]))
