@@ -479,3 +479,42 @@ def test_merged_link_through_the_device_restore_equals_the_chain_restore():
     assert torch.equal(one.arena, two.arena)
     got, _ = one.host()
     assert all(np.array_equal(g, s) for g, s in zip(got, states[-1]))
+
+
+def test_links_and_merged_link_in_pinned_host_memory():
+    """The links of a chain live where checkpoints live: outside the device.  With their staging
+    areas in pinned host memory the kernels read the bytes over the host link themselves; the
+    merged link may be written to pinned host memory too."""
+    import torch
+    from gpu_util import DeviceBuffers
+    from paper_2202_07848_amd import binding as ck
+    sizes, chunk = [300000, 65536, 0, 99999, 70000], 4096
+    rng = np.random.default_rng(43)
+    states = [[rng.integers(0, 256, size=n, dtype=np.uint8) for n in sizes]]
+    for s in range(3):
+        states.append(evolve(rng, states[-1], 6 + s, 20000))
+    links = oracle_links(states, chunk, first_is_full=False)
+    dev = []
+    for staging, man in links:
+        host = torch.empty(max(16, staging.size), dtype=torch.uint8, pin_memory=True)
+        host[:staging.size] = torch.from_numpy(staging)
+        m = torch.from_numpy(man.view(np.uint8).reshape(-1).copy()).cuda()
+        dev.append((host, int(staging.size), m, int(man.size), None))
+    dst = DeviceBuffers(states[0], chunk)
+    want = [b.copy() for b in states[0]]
+    want_stats = oracle.restore_chain(want, chunk, links)
+    assert run_chain(dst, dev) == want_stats
+    got, img = dst.host()
+    assert all(np.array_equal(g, s) for g, s in zip(got, states[-1])) and dst.canaries_intact(img)
+
+    o_st, o_man, o_counts, _ = oracle.merge_chain(sizes, chunk, links)
+    out = torch.full((o_st.size + 64,), 0xA5, dtype=torch.uint8).pin_memory()
+    manifest = torch.zeros(o_man.size * 32, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    ws = torch.zeros(ck.merge_chain_workspace_bytes(dst.plan.nchunks), dtype=torch.uint8, device="cuda")
+    ck.merge_chain(dst.plan, dev, out, manifest, counts, ws, staging_cap=o_st.size)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.numpy()[:o_st.size], o_st) and np.all(out.numpy()[o_st.size:] == 0xA5)
+    assert np.array_equal(ck.manifest_to_numpy(manifest, o_man.size), o_man)
+    assert [int(x) for x in counts.cpu().numpy().view(np.uint64)] == [o_counts["ndirty"],
+                                                                      o_counts["staged_bytes"], 0]
