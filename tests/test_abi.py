@@ -113,3 +113,44 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(ck, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libckpt.so"))
     with pytest.raises(ImportError):
         ck.version()
+
+
+C_PROGRAM = r"""
+#include <stddef.h>
+#include <stdio.h>
+#include "ckpt.h"
+int main(void) {
+  /* host-only calls: no device is touched */
+  ckpt_plan_t *plan = (ckpt_plan_t *)0;
+  ckpt_buf_t one = {(void *)0x1000, 4096};
+  if (ckpt_plan_create(&one, 1, 1000, &plan) != CKPT_ERR_CHUNK || plan) return 1;
+  if (ckpt_restore_chain(0, 0, 0, 0, 0, 0, 0) != CKPT_ERR_INVALID_ARG) return 2;
+  if (ckpt_version() < 1 || !ckpt_strerror(CKPT_ERR_CAPACITY)[0]) return 3;
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %d\n", sizeof(ckpt_buf_t), sizeof(ckpt_entry_t),
+         offsetof(ckpt_entry_t, buf_off), offsetof(ckpt_entry_t, stage_off),
+         offsetof(ckpt_entry_t, digest), sizeof(ckpt_counts_t), sizeof(ckpt_link_t),
+         offsetof(ckpt_link_t, d_manifest), offsetof(ckpt_link_t, d_counts),
+         sizeof(ckpt_chain_stats_t), CKPT_CHAIN_MAX);
+  return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """include/ckpt.h under gcc -std=c11 -pedantic, a C caller linked against libckpt.so, and the
+    struct layouts the ctypes binding assumes against what the C compiler lays out."""
+    import subprocess
+    src, exe = tmp_path / "caller.c", tmp_path / "caller"
+    src.write_text(C_PROGRAM)
+    libdir = os.path.dirname(ck.LIB_PATH)
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I",
+                    os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir, "-lckpt",
+                    "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], stdout=subprocess.PIPE, text=True, check=True).stdout.split()
+    got = [int(x) for x in out]
+    entry = ck.ENTRY_DTYPE if hasattr(ck, "ENTRY_DTYPE") else None
+    assert got == [ctypes.sizeof(ck._Buf), 32, 8, 16, 24, 24, ctypes.sizeof(ck._Link),
+                   ck._Link.d_manifest.offset, ck._Link.d_counts.offset, 24, ck.CHAIN_MAX]
+    assert ck.ENTRY_BYTES == 32
+    if entry is not None:
+        assert entry.itemsize == 32 and entry.fields["stage_off"][1] == 16
