@@ -88,6 +88,8 @@ def _load():
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         lib.ora_restore_chain.restype = ctypes.c_int
         lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp]
+        lib.ora_buffer_verdicts.restype = None
+        lib.ora_buffer_verdicts.argtypes = [vp, u64, u64, vp, vp, vp]
         lib.ora_merge_chain.restype = ctypes.c_int
         lib.ora_merge_chain.argtypes = [vp, u64, u64, vp, u64, vp, u64, vp, u64, vp, vp]
         _lib = lib
@@ -309,3 +311,16 @@ def restore_chain(dst: List[np.ndarray], chunk: int,
     if _load().ora_restore_chain(_desc(dst), len(dst), chunk, arr, len(links), stats) != 0:
         raise MemoryError("ora_restore_chain")
     return {"written": int(stats[0]), "superseded": int(stats[1]), "rejected": int(stats[2])}
+
+
+def buffer_verdicts(sizes: Sequence[int], chunk: int, mask: np.ndarray) -> Tuple[np.ndarray, dict]:
+    """Per buffer: does any of its chunks carry a mark (the paper's per-buffer comparison,
+    sec. 5.2.1, derived from the chunk verdicts).  Returns (dirty[B] uint8, counts)."""
+    sz = np.ascontiguousarray(sizes, dtype=np.uint64)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.size != int(((sz + np.uint64(chunk - 1)) // np.uint64(chunk)).sum()):
+        raise ValueError("mask length does not match the buffer list")
+    dirty = np.full(sz.size, 0xA5, dtype=np.uint8)
+    res = (ctypes.c_uint64 * 2)()
+    _load().ora_buffer_verdicts(_p(sz), sz.size, chunk, _p(mask), _p(dirty), res)
+    return dirty, {"buffers": int(res[0]), "bytes": int(res[1])}

@@ -22,7 +22,9 @@
  *     a swap (ora_match, ora_apply_matches);
  *   - restore from a chain of incremental snapshots (sec. 4.6: de-dup across
  *     time), the links applied oldest first (ora_restore_chain), and the
- *     folding of such a chain into one link (ora_merge_chain).
+ *     folding of such a chain into one link (ora_merge_chain);
+ *   - the paper's own granularity, whole buffers, derived from the chunk
+ *     verdicts (ora_buffer_verdicts).
  *
  * Every function is the definition written out: one loop over buffers, one
  * over chunks, memcpy for copies.  No blocking, no fusion.  The only
@@ -643,6 +645,32 @@ uint64_t ora_apply_matches(const ora_buf_t *dst, uint64_t ndst, const ora_buf_t 
     }
   }
   return rejected;
+}
+
+/* -------------------------------------------------------- buffer verdicts */
+/* The paper compares checksums per buffer (sec. 5.2.1): a buffer is swapped as
+ * a whole if its content differs.  At chunk granularity the same verdict is:
+ * buffer i differs if any of its chunks is marked.  dirty[i] = 1 for such a
+ * buffer, else 0 (a buffer without bytes has no chunk and never differs).
+ *   result[0] = buffers that differ
+ *   result[1] = their total size in bytes: what a swap at buffer granularity
+ *               would have to move, to set against the marked chunks' bytes */
+void ora_buffer_verdicts(const uint64_t *sizes, uint64_t nbufs, uint64_t chunk, const uint8_t *mask,
+                         uint8_t *dirty, uint64_t *result) {
+  uint64_t k = 0, differing = 0, bytes = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = (sizes[i] + chunk - 1) / chunk;
+    uint8_t any = 0;
+    for (uint64_t j = 0; j < n; ++j, ++k)
+      if (mask[k]) any = 1;
+    dirty[i] = any;
+    if (any) {
+      differing += 1;
+      bytes += sizes[i];
+    }
+  }
+  result[0] = differing;
+  result[1] = bytes;
 }
 
 /* ----------------------------------------------------- mutation validation */

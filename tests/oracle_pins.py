@@ -66,6 +66,7 @@ def pins_hold() -> bool:
         owner_pins()
         widened_pins()
         chain_pins()
+        verdict_pins()
         return True
     except AssertionError:
         return False
@@ -111,6 +112,16 @@ def chain_pins():
     tc.test_merge_skips_what_the_chain_restore_skips_and_keeps_the_earlier_holder()
     tc.test_merge_capacities_follow_the_compaction_rule()
     tc.test_merge_of_nothing_is_empty()
+
+
+def verdict_pins():
+    """The pins of the per-buffer verdicts, as tests/test_oracle_buffer_verdicts.py states them."""
+    import test_oracle_buffer_verdicts as tb
+    for seed in (1, 2, 3, 4, 5):
+        tb.test_random_masks_against_a_numpy_reduction(seed)
+    tb.test_verdict_equals_byte_inequality_of_the_buffers()
+    tb.test_each_single_chunk_marks_exactly_its_buffer()
+    tb.test_empty_list_and_only_empty_buffers()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -184,8 +195,8 @@ def use_library(path):
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
                "ora_compact", "ora_restore", "ora_restore_chain", "ora_merge_chain",
-               "ora_upload_owners", "ora_match",
-               "ora_apply_matches", "ora_validate_mutations"):
+               "ora_buffer_verdicts", "ora_upload_owners", "ora_match", "ora_apply_matches",
+               "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     oracle._lib = other

@@ -101,6 +101,12 @@ MUTATIONS = [
      "int bytes_fit = entry_fits && at <= staging_cap;"),
     ("merge: shortened chunks accepted", "ok = c->len == (rest < chunk ? rest : chunk);",
      "ok = c->len <= (rest < chunk ? rest : chunk);"),
+    ("verdicts: only the first chunk of a buffer looked at", "      if (mask[k]) any = 1;",
+     "      if (mask[k] && j == 0) any = 1;"),
+    ("verdicts: chunk counter not advanced over clean buffers",
+     "    for (uint64_t j = 0; j < n; ++j, ++k)\n      if (mask[k]) any = 1;",
+     "    for (uint64_t j = 0; j < n; ++j) {\n      if (mask[k]) any = 1;\n      if (any) ++k;\n    }"),
+    ("verdicts: bytes counted in chunks", "      bytes += sizes[i];", "      bytes += n * chunk;"),
     ("owner: row stride of gathered checksums", "if (gathered[(uint64_t)r * N + k] != mine) continue;",
      "if (gathered[(uint64_t)r * (N - 1) + k] != mine) continue;"),
 ]
