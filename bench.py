@@ -875,6 +875,25 @@ def main():
         out["hint_cases"] = hint_cases_leg(w, pairs[0][1], ref, staged[0], ndirty[0], ck, torch, np,
                                            args)
 
+    # the paper's granularity next to ours: what a swap of whole differing buffers would move
+    bdirty = torch.zeros(max(1, len(w.bufs)), dtype=torch.uint8, device=dev)
+    bcounts = torch.zeros(2, dtype=torch.int64, device=dev)
+    ck.buffer_verdicts(pairs[0][1].plan, masks[0], bdirty, bcounts)
+    e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        ck.buffer_verdicts(pairs[0][1].plan, masks[0], bdirty, bcounts)
+    e1.record()
+    torch.cuda.synchronize()
+    nb_diff, nb_bytes = (int(x) for x in bcounts.cpu().numpy().view(np.uint64))
+    out["buffer_granularity"] = {
+        "buffers_that_differ": nb_diff, "of_buffers": len(w.bufs),
+        "bytes_if_whole_buffers_were_swapped": nb_bytes,
+        "bytes_staged_at_chunk_granularity": staged[0],
+        "chunking_saves": round(1.0 - staged[0] / nb_bytes, 4) if nb_bytes else 0.0,
+        "verdicts_ms": round(e0.elapsed_time(e1) / 5, 4),
+    }
+
     if args.graph:
         out["hip_graph"] = graph_leg(step_calls, restore_calls, bytes_fp, args, torch)
 

@@ -511,6 +511,25 @@ int ckpt_swap_in(ckpt_swapper_t *swapper, const ckpt_plan_t *dst_plan, const voi
                  uint64_t staged_bytes, const ckpt_entry_t *d_manifest, uint64_t nentries,
                  uint64_t *h_rejected, void *stream);
 
+/* ---- the paper's granularity: whole buffers -------------------------------- */
+
+/* Sec. 5.2.1 compares checksums per buffer and swaps a buffer as a whole.  The
+ * same verdict from the chunk marks: buffer i differs when any of its chunks
+ * has d_mask[k] != 0 (d_mask from ckpt_diff, ckpt_snapshot, ckpt_match or
+ * ckpt_upload_owners).
+ *   d_buf_dirty  device array of B bytes, indexed like the plan's buffer list:
+ *                1 = differs, 0 = identical (also for a buffer without bytes)
+ *   d_counts     buffers that differ and the sum of their sizes: what a swap at
+ *                buffer granularity moves, to set against ckpt_counts_t's
+ *                staged_bytes for the marked chunks alone
+ * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
+typedef struct ckpt_buffer_counts {
+  uint64_t buffers; /* buffers with at least one marked chunk */
+  uint64_t bytes;   /* sum of nbytes over those buffers */
+} ckpt_buffer_counts_t;
+int ckpt_buffer_verdicts(const ckpt_plan_t *plan, const uint8_t *d_mask, uint8_t *d_buf_dirty,
+                         ckpt_buffer_counts_t *d_counts, void *stream);
+
 /* ---- squashing validation -------------------------------------------------- */
 
 /* Sec. 5.2.3 validates operation squashing by inferring mutations from

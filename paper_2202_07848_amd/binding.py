@@ -31,7 +31,7 @@ EXPORTS = (
     "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
-    "ckpt_validate_mutations", "ckpt_upload_owners",
+    "ckpt_validate_mutations", "ckpt_upload_owners", "ckpt_buffer_verdicts",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_bw_streams", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -129,6 +129,8 @@ def _lib():
         lib.ckpt_moves_workspace_bytes.argtypes = [u64]
         lib.ckpt_apply_moves_inplace.restype = ci
         lib.ckpt_apply_moves_inplace.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp]
+        lib.ckpt_buffer_verdicts.restype = ci
+        lib.ckpt_buffer_verdicts.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_validate_mutations.restype = ci
         lib.ckpt_validate_mutations.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         lib.ckpt_swapper_create.restype = ci
@@ -395,6 +397,13 @@ def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None) -> 
     _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _ptr(stats),
                                      _stream(stream)), "ckpt_restore_chain")
+
+
+def buffer_verdicts(plan: Plan, mask, buf_dirty, counts, stream=None) -> None:
+    """``ckpt_buffer_verdicts``: buf_dirty (uint8, one per buffer of the plan's list), counts
+    (2 x int64: buffers that differ, their bytes)."""
+    _check(_lib().ckpt_buffer_verdicts(plan._h, _ptr(mask), _ptr(buf_dirty), _ptr(counts),
+                                       _stream(stream)), "ckpt_buffer_verdicts")
 
 
 MATCH_COUNT_FIELDS = ("nsame", "nmoved", "ndup", "nnew", "staged_bytes", "table_full")

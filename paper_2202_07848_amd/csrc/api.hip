@@ -663,6 +663,18 @@ int ckpt_apply_moves_inplace(const ckpt_plan_t *plan, const int64_t *d_src, void
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+int ckpt_buffer_verdicts(const ckpt_plan_t *plan, const uint8_t *d_mask, uint8_t *d_buf_dirty,
+                         ckpt_buffer_counts_t *d_counts, void *stream) {
+  if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nchunks != 0 && d_mask == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nbufs != 0 && d_buf_dirty == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (!aligned(d_counts, 8)) return CKPT_ERR_ALIGNMENT;
+  hipError_t e = ckpt::launch_buffer_verdicts(plan->dev, d_mask, d_buf_dirty,
+                                              reinterpret_cast<uint64_t *>(d_counts),
+                                              static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_validate_mutations(const ckpt_plan_t *plan, const uint64_t *d_before_a,
                             const uint64_t *d_after_a, const uint64_t *d_before_b,
                             const uint64_t *d_after_b, ckpt_validation_t *d_result, void *stream) {

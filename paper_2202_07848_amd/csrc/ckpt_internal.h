@@ -200,6 +200,9 @@ hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_stag
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);
+// d_dirty: one byte per buffer of the caller's list; d_counts: buffers that differ, their bytes.
+hipError_t launch_buffer_verdicts(const PlanDev &p, const uint8_t *d_mask, uint8_t *d_dirty,
+                                  uint64_t *d_counts, hipStream_t s);
 hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a, const uint64_t *b_b,
                            const uint64_t *a_b, ckpt_validation_t *d_result, hipStream_t s);
 uint64_t match_workspace_bytes(uint64_t n_ref, uint64_t n);

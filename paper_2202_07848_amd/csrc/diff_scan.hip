@@ -466,6 +466,61 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_validate(uint64_t n,
   }
 }
 
+// Per-buffer verdicts (the paper compares whole buffers, sec. 5.2.1): a buffer differs when any
+// of its chunks is marked.  k_verdict_clear zeroes the flags and the counts; k_verdict_mark has
+// every thread look at its four consecutive chunks and set the flag of each marked chunk's
+// buffer (all writers of a flag store the same 1); k_verdict_count adds up the buffers that
+// differ and their sizes.
+__global__ __launch_bounds__(256) void k_verdict_clear(uint8_t *__restrict__ dirty, uint64_t nbufs,
+                                                       unsigned long long *counts) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < nbufs; i += stride) dirty[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 2) counts[threadIdx.x] = 0;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_verdict_mark(PlanDev p,
+                                                               const uint8_t *__restrict__ mask,
+                                                               uint8_t *__restrict__ dirty) {
+  const uint64_t k0 = thread_first_chunk();
+  uint8_t m[SCAN_PER_THREAD];
+  int n = 0;
+  bool any = false;
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    const uint64_t k = k0 + i;
+    m[i] = 0;
+    if (k < p.nchunks) {
+      m[i] = mask[k];
+      any = any || m[i] != 0;
+      n = i + 1;
+    }
+  }
+  if (!any) return;
+  ChunkRef refs[SCAN_PER_THREAD];
+  locate_run(p, k0, n, refs);
+  for (int i = 0; i < n; ++i)
+    if (m[i] != 0) dirty[p.dense_orig[refs[i].row]] = 1;
+}
+
+__global__ __launch_bounds__(256) void k_verdict_count(PlanDev p, const uint8_t *__restrict__ dirty,
+                                                       unsigned long long *counts) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  unsigned long long differing = 0, bytes = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < p.nbufs; i += stride) {
+    if (dirty[i] != 0) {
+      differing += 1;
+      bytes += p.list_nbytes[i];
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    differing += __shfl_down(differing, o, 64);
+    bytes += __shfl_down(bytes, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0 && differing != 0) {
+    atomicAdd(&counts[0], differing);
+    atomicAdd(&counts[1], bytes);
+  }
+}
+
 inline uint32_t scan_blocks(uint64_t nchunks) {
   return (uint32_t)((nchunks + SCAN_BLOCK - 1) / SCAN_BLOCK);
 }
@@ -567,6 +622,23 @@ hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a,
     if (groups > 4096) groups = 4096;
     hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
                        b_b, a_b, d_result);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_buffer_verdicts(const PlanDev &p, const uint8_t *d_mask, uint8_t *d_dirty,
+                                  uint64_t *d_counts, hipStream_t s) {
+  ull *counts = reinterpret_cast<ull *>(d_counts);
+  uint64_t groups = (p.nbufs + 255) / 256;
+  if (groups > 4096) groups = 4096;
+  if (groups == 0) groups = 1;
+  hipLaunchKernelGGL(k_verdict_clear, dim3((uint32_t)groups), dim3(256), 0, s, d_dirty, p.nbufs,
+                     counts);
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  if (nblocks != 0) {
+    hipLaunchKernelGGL(k_verdict_mark, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_mask, d_dirty);
+    hipLaunchKernelGGL(k_verdict_count, dim3((uint32_t)groups), dim3(256), 0, s, p,
+                       (const uint8_t *)d_dirty, counts);
   }
   return hipGetLastError();
 }
