@@ -568,7 +568,7 @@ def probe_leg(w, rep, ref, staging, staged, ndirty, ck, torch, np, args):
     out["hinted_pass_launch_shape"] = shapes
 
     # (b) access patterns; the copy goes from the replica's arena into the staging buffer
-    stream_bytes = max(512, w.chunk)
+    stream_bytes = max(2048, w.chunk)
     nstreams = min(staged, rep.arena.numel()) // stream_bytes // 16 * 16
     if nstreams:
         nb = nstreams * stream_bytes
@@ -580,7 +580,11 @@ def probe_leg(w, rep, ref, staging, staged, ndirty, ck, torch, np, args):
                                                       sink), 2),
                 ("sweep_read", lambda: ck.bw_read(rep.arena, nb, sink), 1),
                 ("stream_read", lambda: ck.bw_streams(None, rep.arena, nstreams, stream_bytes,
-                                                      sink), 1)):
+                                                      sink), 1),
+                ("stream_copy_1KiB_tiles", lambda: ck.bw_streams(
+                    staging, rep.arena, nstreams, stream_bytes, sink, tile_bytes=1024), 2),
+                ("stream_read_1KiB_tiles", lambda: ck.bw_streams(
+                    None, rep.arena, nstreams, stream_bytes, sink, tile_bytes=1024), 1)):
             ms = timed(fn)
             pat[name] = {"ms": round(ms, 4), "GBps_read_plus_write": round(factor * nb / ms / 1e6, 1)}
         out["access_patterns"] = pat

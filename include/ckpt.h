@@ -562,16 +562,19 @@ int ckpt_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, void *stream);
 int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *stream);
 
 /* The same two yardsticks with the fingerprint pass's access pattern: nstreams
- * (multiple of 16) streams of stream_bytes (multiple of 512) bytes each, stream
- * i at d_src + i * stream_bytes; every wavefront walks 16 streams front to back,
- * 256 bytes of each per step -- as it walks 16 chunks when it hashes.  With
- * d_dst each tile is stored to the same offset of d_dst (the staging writes of
- * ckpt_snapshot with a hint); with d_dst == NULL the streams are only read.
- * d_sink: at least 16 KiB.  The caller provides nstreams * stream_bytes
- * readable (and writable) bytes.
+ * (multiple of 16) streams of stream_bytes bytes each (a multiple of
+ * 2 * tile_bytes), stream i at d_src + i * stream_bytes; every wavefront walks
+ * 16 streams front to back, tile_bytes of each per step -- as it walks 16
+ * chunks when it hashes.  tile_bytes is 256 (the fingerprint kernel's tile: one
+ * load instruction takes 256 bytes from each of four streams) or 1024 (one load
+ * instruction takes one kibibyte of one stream; the comparison shows what a
+ * larger tile could gain).  With d_dst each tile is stored to the same offset
+ * of d_dst (the staging writes of ckpt_snapshot with a hint); with d_dst == NULL
+ * the streams are only read.  d_sink: at least 16 KiB.  The caller provides
+ * nstreams * stream_bytes readable (and writable) bytes.
  * Errors: INVALID_ARG, ALIGNMENT, DEVICE. */
 int ckpt_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams, uint64_t stream_bytes,
-                    uint64_t *d_sink, void *stream);
+                    uint64_t tile_bytes, uint64_t *d_sink, void *stream);
 
 /* The other yardstick: the XXH64 accumulator arithmetic alone, on words made
  * up in registers, no memory traffic -- what the integer units allow the

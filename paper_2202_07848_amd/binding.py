@@ -146,7 +146,7 @@ def _lib():
         lib.ckpt_bw_read.restype = ci
         lib.ckpt_bw_read.argtypes = [vp, u64, vp, vp]
         lib.ckpt_bw_streams.restype = ci
-        lib.ckpt_bw_streams.argtypes = [vp, vp, u64, u64, vp, vp]
+        lib.ckpt_bw_streams.argtypes = [vp, vp, u64, u64, u64, vp, vp]
         lib.ckpt_alu_xxh64.restype = u64
         lib.ckpt_alu_xxh64.argtypes = [u64, vp, vp]
         lib.ckpt_strerror.restype = ctypes.c_char_p
@@ -516,11 +516,12 @@ def bw_read(src, nbytes: int, sink, stream=None) -> None:
     _check(_lib().ckpt_bw_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "ckpt_bw_read")
 
 
-def bw_streams(dst, src, nstreams: int, stream_bytes: int, sink, stream=None) -> None:
+def bw_streams(dst, src, nstreams: int, stream_bytes: int, sink, stream=None,
+               tile_bytes: int = 256) -> None:
     """``ckpt_bw_streams``: copy (or, with dst None, read) nstreams streams of stream_bytes bytes
-    with the fingerprint pass's access pattern."""
-    _check(_lib().ckpt_bw_streams(_ptr(dst), _ptr(src), nstreams, stream_bytes, _ptr(sink),
-                                  _stream(stream)), "ckpt_bw_streams")
+    with the fingerprint pass's access pattern, tile_bytes (256 or 1024) of a stream per step."""
+    _check(_lib().ckpt_bw_streams(_ptr(dst), _ptr(src), nstreams, stream_bytes, tile_bytes,
+                                  _ptr(sink), _stream(stream)), "ckpt_bw_streams")
 
 
 def alu_xxh64(rounds_per_lane: int, sink, stream=None) -> int:

@@ -708,15 +708,17 @@ int ckpt_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, void *str
 }
 
 int ckpt_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams, uint64_t stream_bytes,
-                    uint64_t *d_sink, void *stream) {
+                    uint64_t tile_bytes, uint64_t *d_sink, void *stream) {
+  if (tile_bytes != 256 && tile_bytes != 1024) return CKPT_ERR_INVALID_ARG;
   if (nstreams == 0) return CKPT_OK;
   if (d_src == nullptr || d_sink == nullptr) return CKPT_ERR_INVALID_ARG;
-  if ((nstreams & 15) != 0 || (stream_bytes & 511) != 0 || stream_bytes == 0 ||
+  if ((nstreams & 15) != 0 || stream_bytes % (2 * tile_bytes) != 0 || stream_bytes == 0 ||
       nstreams / 16 > 0x7FFFFFFFull || stream_bytes > (1ull << 40) ||
       nstreams > (~0ull) / stream_bytes)
     return CKPT_ERR_INVALID_ARG;
   if (!aligned(d_dst, 16) || !aligned(d_src, 16) || !aligned(d_sink, 8)) return CKPT_ERR_ALIGNMENT;
-  hipError_t e = ckpt::launch_bw_streams(d_dst, d_src, nstreams, stream_bytes, d_sink,
+  hipError_t e = ckpt::launch_bw_streams(d_dst, d_src, nstreams, stream_bytes,
+                                         (uint32_t)tile_bytes, d_sink,
                                          static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }

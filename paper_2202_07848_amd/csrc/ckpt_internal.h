@@ -222,7 +222,8 @@ hipError_t launch_zero_u64(uint64_t *d_value, hipStream_t s);
 hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipStream_t s);
 hipError_t launch_bw_read(const void *d_src, uint64_t nbytes, uint64_t *d_sink, hipStream_t s);
 hipError_t launch_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams,
-                             uint64_t stream_bytes, uint64_t *d_sink, hipStream_t s);
+                             uint64_t stream_bytes, uint32_t tile_bytes, uint64_t *d_sink,
+                             hipStream_t s);
 constexpr uint32_t ALU_PROBE_GROUPS = 2048;   // workgroups of 256 lanes in the hash-only probe
 hipError_t launch_alu_xxh64(uint64_t rounds_per_lane, uint64_t *d_sink, hipStream_t s);
 

@@ -138,51 +138,56 @@ __global__ __launch_bounds__(256) void k_bw_read(const uint4 *__restrict__ src, 
 }
 
 // The fingerprint kernel's memory access pattern without its arithmetic: single-wavefront
-// workgroups, 16 streams per wavefront (stream i = bytes [i, i+1) * stream_bytes of src), each
-// load instruction fetching one 256-byte tile from each of four streams, two tiles per stream
-// prefetched in registers.  COPY: every tile is stored to the same offset of dst (what the fused
-// snapshot pass does with staged chunks); otherwise the tiles are XOR-ed into one word per
-// wavefront.  Its rate is the ceiling this access pattern leaves the fingerprint pass.
-template <bool COPY>
+// workgroups, 16 streams per wavefront (stream i = bytes [i, i+1) * stream_bytes of src), two
+// tiles per stream prefetched in registers.  TILE = bytes of one stream fetched per step: with
+// 256 (the fingerprint kernel's tile) each load instruction takes 256 bytes from each of four
+// streams, with 1024 one kibibyte of a single stream.  COPY: every tile is stored to the same
+// offset of dst (what the fused snapshot pass does with staged chunks); otherwise the tiles are
+// XOR-ed into one word per wavefront.  Its rate is the ceiling this access pattern leaves the
+// fingerprint pass.
+template <int TILE, bool COPY>
 __global__ __launch_bounds__(64) void k_bw_streams(const uint8_t *__restrict__ src,
                                                    uint8_t *__restrict__ dst,
                                                    uint64_t stream_bytes,
                                                    uint64_t *__restrict__ sink) {
+  constexpr int LANES = TILE / 16;        // lanes that share one stream in a load instruction
+  constexpr int PER_LOAD = 64 / LANES;    // streams one load instruction serves
+  constexpr int NLOADS = 16 / PER_LOAD;   // load instructions per step
   const uint32_t lane = threadIdx.x;
   const uint64_t first = (uint64_t)blockIdx.x * 16;
-  const uint8_t *lp[4];
-  uint8_t *sp[4];
+  const uint8_t *lp[NLOADS];
+  uint8_t *sp[NLOADS];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint64_t off = (first + 4 * i + (lane >> 4)) * stream_bytes + 16 * (lane & 15);
+  for (int i = 0; i < NLOADS; ++i) {
+    const uint64_t off = (first + PER_LOAD * i + lane / LANES) * stream_bytes + 16 * (lane % LANES);
     lp[i] = src + off;
     sp[i] = dst + off;
   }
-  const uint64_t tiles = stream_bytes >> 8;        // even and >= 2 (checked on the host)
-  uint4 q0[4], q1[4], acc = make_uint4(0, 0, 0, 0);
+  const uint64_t tiles = stream_bytes / TILE;      // even and >= 2 (checked on the host)
+  uint4 q0[NLOADS], q1[NLOADS], acc = make_uint4(0, 0, 0, 0);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NLOADS; ++i) {
     q0[i] = stream_load16(lp[i]);
-    q1[i] = stream_load16(lp[i] + 256);
+    q1[i] = stream_load16(lp[i] + TILE);
   }
   for (uint64_t t = 0; t < tiles; t += 2) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NLOADS; ++i) {
       if (COPY) {
-        stream_store16(sp[i] + (t << 8), q0[i]);
+        stream_store16(sp[i] + t * TILE, q0[i]);
       } else {
         acc.x ^= q0[i].x; acc.y ^= q0[i].y; acc.z ^= q0[i].z; acc.w ^= q0[i].w;
       }
-      if (t + 2 < tiles) q0[i] = stream_load16(lp[i] + ((t + 2) << 8));
+      if (t + 2 < tiles) q0[i] = stream_load16(lp[i] + (t + 2) * TILE);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NLOADS; ++i) {
       if (COPY) {
-        stream_store16(sp[i] + ((t + 1) << 8), q1[i]);
+        stream_store16(sp[i] + (t + 1) * TILE, q1[i]);
       } else {
         acc.x ^= q1[i].x; acc.y ^= q1[i].y; acc.z ^= q1[i].z; acc.w ^= q1[i].w;
       }
-      if (t + 3 < tiles) q1[i] = stream_load16(lp[i] + ((t + 3) << 8));
+      if (t + 3 < tiles) q1[i] = stream_load16(lp[i] + (t + 3) * TILE);
     }
   }
   if (!COPY) {
@@ -283,16 +288,27 @@ hipError_t launch_bw_copy(void *d_dst, const void *d_src, uint64_t nbytes, hipSt
 }
 
 hipError_t launch_bw_streams(void *d_dst, const void *d_src, uint64_t nstreams,
-                             uint64_t stream_bytes, uint64_t *d_sink, hipStream_t s) {
+                             uint64_t stream_bytes, uint32_t tile_bytes, uint64_t *d_sink,
+                             hipStream_t s) {
   const uint32_t groups = (uint32_t)(nstreams / 16);
   if (groups == 0) return hipSuccess;
   const uint8_t *src = reinterpret_cast<const uint8_t *>(d_src);
-  if (d_dst != nullptr)
-    hipLaunchKernelGGL(k_bw_streams<true>, dim3(groups), dim3(64), 0, s, src,
-                       reinterpret_cast<uint8_t *>(d_dst), stream_bytes, d_sink);
+  uint8_t *dst = reinterpret_cast<uint8_t *>(d_dst);
+  const bool copy = d_dst != nullptr;
+  if (tile_bytes == 256 && copy)
+    hipLaunchKernelGGL((k_bw_streams<256, true>), dim3(groups), dim3(64), 0, s, src, dst,
+                       stream_bytes, d_sink);
+  else if (tile_bytes == 256)
+    hipLaunchKernelGGL((k_bw_streams<256, false>), dim3(groups), dim3(64), 0, s, src, dst,
+                       stream_bytes, d_sink);
+  else if (tile_bytes == 1024 && copy)
+    hipLaunchKernelGGL((k_bw_streams<1024, true>), dim3(groups), dim3(64), 0, s, src, dst,
+                       stream_bytes, d_sink);
+  else if (tile_bytes == 1024)
+    hipLaunchKernelGGL((k_bw_streams<1024, false>), dim3(groups), dim3(64), 0, s, src, dst,
+                       stream_bytes, d_sink);
   else
-    hipLaunchKernelGGL(k_bw_streams<false>, dim3(groups), dim3(64), 0, s, src,
-                       (uint8_t *)nullptr, stream_bytes, d_sink);
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

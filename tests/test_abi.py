@@ -78,7 +78,8 @@ def test_host_side_argument_checks_need_no_device():
                                     None) == -1
     assert lib.ckpt_snapshot_static_max_chunks() == 1 << 18
     assert lib.ckpt_snapshot_stats_offset(1000) == 8000
-    assert lib.ckpt_bw_streams(None, None, 16, 512, None, None) == -1
+    assert lib.ckpt_bw_streams(None, None, 16, 512, 256, None, None) == -1
+    assert lib.ckpt_bw_streams(None, None, 16, 4096, 512, None, None) == -1     # no such tile
     assert lib.ckpt_plan_destroy(None) == 0
     assert lib.ckpt_plan_nchunks(None) == 0
 

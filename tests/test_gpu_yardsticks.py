@@ -67,18 +67,26 @@ def test_alu_probe_runs_the_xxh64_accumulator_step():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("nstreams,stream_bytes", [(16, 512), (48, 4096), (32, 1 << 20)])
-def test_bw_streams_copies_every_stream_and_nothing_else(nstreams, stream_bytes):
+@pytest.mark.parametrize("tile", [256, 1024])
+@pytest.mark.parametrize("nstreams,stream_bytes", [(16, 2048), (48, 4096), (32, 1 << 20)])
+def test_bw_streams_copies_every_stream_and_nothing_else(nstreams, stream_bytes, tile):
     n = nstreams * stream_bytes
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
     dst = torch.full((n + 4096,), 0x6B, dtype=torch.uint8, device="cuda")
     sink = torch.zeros(4096, dtype=torch.int64, device="cuda")
-    ck.bw_streams(dst, src, nstreams, stream_bytes, sink)
+    ck.bw_streams(dst, src, nstreams, stream_bytes, sink, tile_bytes=tile)
     torch.cuda.synchronize()
     assert torch.equal(dst[:n], src) and bool((dst[n:] == 0x6B).all())
-    ck.bw_streams(None, src, nstreams, stream_bytes, sink)        # read only
+    ck.bw_streams(None, src, nstreams, stream_bytes, sink, tile_bytes=tile)        # read only
     torch.cuda.synchronize()
-    for bad in ((15, stream_bytes), (nstreams, stream_bytes + 256), (nstreams, 0)):
+    for bad in ((15, stream_bytes), (nstreams, stream_bytes + tile), (nstreams, 0)):
         with pytest.raises(ck.CkptError) as e:
-            ck.bw_streams(dst, src, bad[0], bad[1], sink)
+            ck.bw_streams(dst, src, bad[0], bad[1], sink, tile_bytes=tile)
         assert e.value.status == -1
+    if tile == 256:
+        ck.bw_streams(dst[:16 * 512], src, 16, 512, sink)            # the smallest stream: two tiles
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:16 * 512], src[:16 * 512])
+    with pytest.raises(ck.CkptError) as e:
+        ck.bw_streams(dst, src, nstreams, stream_bytes, sink, tile_bytes=512)
+    assert e.value.status == -1
