@@ -69,9 +69,9 @@ def parse_args():
                          "ranks that share one device image (swap-out of the outgoing rank's delta "
                          "to pinned host memory, swap-in of the incoming rank's, no host read)")
     ap.add_argument("--chain", action="store_true",
-                    help="configs with three or more replicas (--config 4): also restore the chain "
-                         "of the replicas' deltas, one ckpt_restore_counted per link against one "
-                         "ckpt_restore_chain over all of them")
+                    help="--config 4 or --config 3: also restore a chain of three deltas, one "
+                         "ckpt_restore_counted per link against one ckpt_restore_chain over all of "
+                         "them, and fold the chain into one link (ckpt_merge_chain)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in HIP graphs (snapshot part, restore part) and "
                          "time their replays: what a launch-bound small state gains")
@@ -438,26 +438,52 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
     }
 
 
-def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
-    """Restore from a chain of incremental snapshots (paper sec. 4.6).  The links are the
-    deltas of replicas 1, 2, ... against the reference: every link holds the same chunks (the
-    per-replica gradients and activations), as the steps of one job do.  Applied link by link
-    each of those chunks is written once per link; ckpt_restore_chain writes it once."""
+def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, wl, torch, np, args):
+    """Restore from a chain of incremental snapshots (paper sec. 4.6), link by link against
+    ckpt_restore_chain, which writes every chunk once, and ckpt_merge_chain.
+    Replica configurations: the links are the deltas of replicas 1, 2, ... against the reference;
+    every link holds the same chunks (the per-replica gradients and activations), as the steps
+    of one job do.  Config 3: three more rounds of scattered rewrites (--dirty of the chunks each,
+    a fresh seeded set per round) on a copy of the rewritten state; every link is the delta
+    against the state before it, so the links hold different, partly overlapping chunk sets."""
     dev = ref.device
     n = w.nchunks
     dig = torch.zeros(n, dtype=torch.int64, device=dev)
     mask = torch.zeros(n, dtype=torch.uint8, device=dev)
     links, staged = [], []
-    for (_, rep), staging, manifest in zip(pairs, stagings, manifests):
-        cnt = torch.zeros(3, dtype=torch.int64, device=dev)
-        ck.fingerprint(rep.plan, dig)
-        ck.diff(rep.plan, dig, ref, mask, cnt)
-        ck.compact(rep.plan, mask, dig, staging, manifest, cnt, staging_cap=staging.numel(),
-                   manifest_cap=manifest.numel() // 32)
-        torch.cuda.synchronize()
-        assert int(cnt[2]) == 0
-        staged.append(int(cnt[1]))
-        links.append((staging, int(cnt[1]), manifest, manifest.numel() // 32, cnt))
+    if w.nreplicas >= 3:
+        final = pairs[-1][1].arena
+        for (_, rep), staging, manifest in zip(pairs, stagings, manifests):
+            cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+            ck.fingerprint(rep.plan, dig)
+            ck.diff(rep.plan, dig, ref, mask, cnt)
+            ck.compact(rep.plan, mask, dig, staging, manifest, cnt, staging_cap=staging.numel(),
+                       manifest_cap=manifest.numel() // 32)
+            torch.cuda.synchronize()
+            assert int(cnt[2]) == 0
+            staged.append(int(cnt[1]))
+            links.append((staging, int(cnt[1]), manifest, manifest.numel() // 32, cnt))
+    else:
+        final = replicas[0].arena.clone()
+        state = Replica(w, final, replicas[0].offs, ck)
+        prev = ref.clone()
+        for rnd in range(3):
+            step = int(args.dirty * 100) + 1000 * (rnd + 1)
+            ids = wl.dirty_chunk_ids(w, args.dirty, step)
+            wl.torch_rewrite_chunks(w, final, replicas[0].offs, ids, step)
+            cnt = torch.zeros(3, dtype=torch.int64, device=dev)
+            ck.fingerprint(state.plan, dig)
+            ck.diff(state.plan, dig, prev, mask, cnt)
+            torch.cuda.synchronize()
+            nd, nb = int(cnt[0]), int(cnt[1])
+            assert nd == ids.size
+            staging = torch.empty(max(16, nb), dtype=torch.uint8, device=dev)
+            manifest = torch.empty(max(1, nd) * 32, dtype=torch.uint8, device=dev)
+            ck.compact(state.plan, mask, dig, staging, manifest, cnt, staging_cap=nb, manifest_cap=nd)
+            torch.cuda.synchronize()
+            staged.append(nb)
+            links.append((staging, nb, manifest, nd, cnt))
+            prev.copy_(dig)
     image = replicas[0].arena.clone()
     plan = ck.Plan([(image.data_ptr() + int(o), b.nbytes) for o, b in zip(replicas[0].offs, w.bufs)],
                    w.chunk)
@@ -471,7 +497,7 @@ def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
     def timed(fn, reps=5):
         fn()
         torch.cuda.synchronize()
-        assert torch.equal(image, pairs[-1][1].arena)
+        assert torch.equal(image, final)
         image.copy_(replicas[0].arena)
         fn()
         e0, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
@@ -488,7 +514,7 @@ def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
     assert rejected == 0 and superseded == sum(int(l[4][0]) for l in links) - written
 
     # the same chain folded into one link (ckpt_merge_chain), then that link restored
-    m_staging = torch.empty(max(staged), dtype=torch.uint8, device=dev)
+    m_staging = torch.empty(sum(staged), dtype=torch.uint8, device=dev)
     m_manifest = torch.empty(written * 32, dtype=torch.uint8, device=dev)
     m_counts = torch.zeros(3, dtype=torch.int64, device=dev)
     m_ws = torch.empty(ck.merge_chain_workspace_bytes(n), dtype=torch.uint8, device=dev)
@@ -505,24 +531,24 @@ def chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np):
     torch.cuda.synchronize()
     ms_merge = e0.elapsed_time(e1) / 5
     mc = [int(x) for x in m_counts.cpu().numpy().view(np.uint64)]
-    assert mc == [written, staged[-1], 0], mc
+    assert mc[0] == written and mc[2] == 0 and mc[1] <= sum(staged), mc
     image.copy_(replicas[0].arena)
     ck.restore_counted(plan, m_staging, mc[1], m_manifest, written, m_counts)
     torch.cuda.synchronize()
-    assert torch.equal(image, pairs[-1][1].arena)
+    assert torch.equal(image, final)
     return {
         "workload": f"config{w.config}_{w.name}: chain of {len(links)} deltas restored into a copy "
-                    "of the reference replica",
+                    "of the reference state",
         "links": len(links), "bytes_per_link": staged,
         "chunks_written": written, "entries_superseded": superseded,
         "one_restore_per_link_ms": round(ms_each, 3),
         "restore_chain_ms": round(ms_chain, 3),
         "speedup": round(ms_each / ms_chain, 2),
-        "restore_chain_hbm_GBps_read_plus_write": round(2 * staged[-1] / ms_chain / 1e6, 1),
+        "restore_chain_hbm_GBps_read_plus_write": round(2 * mc[1] / ms_chain / 1e6, 1),
         "merge_chain_ms": round(ms_merge, 3),
         "merge_chain_hbm_GBps_read_plus_write": round(2 * mc[1] / ms_merge / 1e6, 1),
         "merged_link_bytes": mc[1],
-        "image_equals_last_replica": True,
+        "image_equals_last_state": True,
     }
 
 
@@ -943,9 +969,10 @@ def main():
         out["context_switch"] = context_switch_leg(w, replicas, ref, ck, wl, torch, np, args)
 
     if args.chain:
-        if len(pairs) < 2:
-            raise SystemExit("--chain needs a configuration with three or more replicas (--config 4)")
-        out["restore_chain"] = chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, torch, np)
+        if w.nreplicas == 2:
+            raise SystemExit("--chain needs three or more replicas (--config 4) or config 3")
+        out["restore_chain"] = chain_leg(w, replicas, pairs, ref, stagings, manifests, ck, wl, torch,
+                                         np, args)
 
     if args.match and w.nreplicas == 1:
         out["content_addressed"] = content_addressed_leg(w, pairs[0][0], pairs[0][1], ref, ck, torch,

@@ -13,7 +13,7 @@
 //                  entry names; the entry that finds 0 there is the first for its
 //                  chunk, which gives the number of chunks written
 //   k_chain_list   the keys that are left, one per chunk that any link holds, as a
-//                  dense list
+//                  dense list (one atomic add per 16 384 chunks)
 //   k_chain_move   every listed key copies its entry's bytes
 // The maximum over (link, entry index) is the entry a one-by-one restore would
 // apply last, so the result is the same for any manifests, including ones that
@@ -82,7 +82,9 @@ __global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
     ++applied;
     first += old == 0;
   }
-  if (stats == nullptr) return;
+  if (stats == nullptr) return;                 // uniform: a kernel argument
+  // one atomic per counter and workgroup: all workgroups add to the same three words
+  __shared__ uint32_t s_sum[3][256 / 64];
   uint32_t again = applied - first;
   for (int o = 32; o > 0; o >>= 1) {
     first += __shfl_down(first, o, 64);
@@ -90,30 +92,62 @@ __global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
     skipped += __shfl_down(skipped, o, 64);
   }
   if ((threadIdx.x & 63) == 0) {
-    if (first) atomicAdd(&stats[0], (unsigned long long)first);
-    if (again) atomicAdd(&stats[1], (unsigned long long)again);
-    if (skipped) atomicAdd(&stats[2], (unsigned long long)skipped);
+    s_sum[0][threadIdx.x >> 6] = first;
+    s_sum[1][threadIdx.x >> 6] = again;
+    s_sum[2][threadIdx.x >> 6] = skipped;
+  }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    unsigned long long v = 0;
+    for (int wv = 0; wv < 256 / 64; ++wv) v += s_sum[threadIdx.x][wv];
+    if (v != 0) atomicAdd(&stats[threadIdx.x], v);
   }
 }
 
-// The keys of the chunks that have one, gathered into list[0 .. *count): a wavefront looks at 64
-// consecutive chunk ids and appends its keys in chunk order behind one atomic add, so the list
-// is in ascending chunk order inside every run of 64 and roughly so overall (the order decides
-// nothing but which waves of k_chain_move run side by side).
+// The keys of the chunks that have one, gathered into list[0 .. *count).  A workgroup owns
+// LIST_SPAN consecutive chunk ids: it counts its keys, reserves that many list slots with ONE
+// atomic add (every wave of a large plan adding to the same word costs a millisecond at six
+// million chunks), and then writes its keys in chunk order.  The list is therefore in ascending
+// chunk order inside every span; which span lands where decides nothing but which waves of
+// k_chain_move run side by side.
+constexpr int LIST_SPAN = 16384;
 __global__ __launch_bounds__(256) void k_chain_list(const unsigned long long *__restrict__ last,
                                                     uint64_t n, unsigned long long *__restrict__ list,
                                                     unsigned long long *count) {
-  const uint32_t lane = threadIdx.x & 63;
-  const uint64_t stride = (uint64_t)gridDim.x * 256;
-  for (uint64_t k0 = (uint64_t)blockIdx.x * 256 + (threadIdx.x & ~63u); k0 < n; k0 += stride) {
-    const uint64_t k = k0 + lane;
-    const unsigned long long key = k < n ? last[k] : 0;
+  __shared__ uint32_t s_wave[256 / 64];
+  __shared__ unsigned long long s_base;
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t lo = (uint64_t)blockIdx.x * LIST_SPAN;
+  const uint64_t hi = lo + LIST_SPAN < n ? lo + LIST_SPAN : n;
+
+  uint32_t mine = 0;
+  for (uint64_t k = lo + threadIdx.x; k < hi; k += 256) mine += last[k] != 0;
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_down(mine, o, 64);
+  if (lane == 0) s_wave[wave] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t total = 0;
+    for (int v = 0; v < 256 / 64; ++v) total += s_wave[v];
+    s_base = total != 0 ? atomicAdd(count, (unsigned long long)total) : 0;
+  }
+  __syncthreads();
+  unsigned long long at = s_base;
+  __syncthreads();                               // s_wave is reused below
+
+  for (uint64_t row = lo; row < hi; row += 256) {          // uniform trip count for the workgroup
+    const uint64_t k = row + threadIdx.x;
+    const unsigned long long key = k < hi ? last[k] : 0;
     const uint64_t holders = __ballot(key != 0);
-    if (holders == 0) continue;
-    unsigned long long base = 0;
-    if (lane == 0) base = atomicAdd(count, (unsigned long long)__popcll(holders));
-    base = __shfl(base, 0, 64);
-    if (key != 0) list[base + __popcll(holders & ((1ull << lane) - 1))] = key;
+    if (lane == 0) s_wave[wave] = (uint32_t)__popcll(holders);
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (uint32_t v = 0; v < 256 / 64; ++v) {
+      if (v < wave) before += s_wave[v];
+      all += s_wave[v];
+    }
+    if (key != 0) list[at + before + __popcll(holders & ((1ull << lane) - 1))] = key;
+    at += all;
+    __syncthreads();
   }
 }
 
@@ -246,8 +280,10 @@ hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *
                                    &entries, s);
   if (e != hipSuccess || entries == 0 || p.nchunks == 0) return e;
 
-  hipLaunchKernelGGL(k_chain_list, dim3(groups_for(p.nchunks, 256, 4096)), dim3(256), 0, s, last,
-                     p.nchunks, list, count);
+  const uint64_t spans = (p.nchunks + LIST_SPAN - 1) / LIST_SPAN;
+  if (spans > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_chain_list, dim3((uint32_t)spans), dim3(256), 0, s, last, p.nchunks, list,
+                     count);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
