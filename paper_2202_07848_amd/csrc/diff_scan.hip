@@ -455,7 +455,23 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_validate(uint64_t n,
     const uint64_t f = __shfl_down(first, o, 64);
     first = f < first ? f : first;
   }
+  // one set of atomics per workgroup: every workgroup adds to the same four words
+  __shared__ uint32_t s_ca[SCAN_THREADS / 64], s_cb[SCAN_THREADS / 64], s_bad[SCAN_THREADS / 64];
+  __shared__ uint64_t s_first[SCAN_THREADS / 64];
   if ((threadIdx.x & 63) == 0) {
+    s_ca[threadIdx.x >> 6] = ca;
+    s_cb[threadIdx.x >> 6] = cb;
+    s_bad[threadIdx.x >> 6] = bad;
+    s_first[threadIdx.x >> 6] = first;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int v = 1; v < SCAN_THREADS / 64; ++v) {
+      ca += s_ca[v];
+      cb += s_cb[v];
+      bad += s_bad[v];
+      first = s_first[v] < first ? s_first[v] : first;
+    }
     if (ca) atomicAdd(reinterpret_cast<unsigned long long *>(&r->changed_a), (unsigned long long)ca);
     if (cb) atomicAdd(reinterpret_cast<unsigned long long *>(&r->changed_b), (unsigned long long)cb);
     if (bad) {
@@ -619,7 +635,7 @@ hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a,
   hipLaunchKernelGGL(k_validate_init, dim3(1), dim3(1), 0, s, d_result);
   if (n) {
     uint64_t groups = (n + SCAN_THREADS - 1) / SCAN_THREADS;
-    if (groups > 4096) groups = 4096;
+    if (groups > 2048) groups = 2048;
     hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
                        b_b, a_b, d_result);
   }
