@@ -87,7 +87,7 @@ def _load():
         lib.ora_restore.restype = ctypes.c_uint64
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         lib.ora_restore_chain.restype = ctypes.c_int
-        lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp]
+        lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp, vp]
         lib.ora_buffer_verdicts.restype = None
         lib.ora_buffer_verdicts.argtypes = [vp, u64, u64, vp, vp, vp]
         lib.ora_merge_chain.restype = ctypes.c_int
@@ -298,17 +298,23 @@ def merge_chain(sizes: Sequence[int], chunk: int, links: Sequence[Tuple[np.ndarr
 
 
 def restore_chain(dst: List[np.ndarray], chunk: int,
-                  links: Sequence[Tuple[np.ndarray, np.ndarray]]) -> dict:
+                  links: Sequence[Tuple[np.ndarray, np.ndarray]],
+                  only: Optional[np.ndarray] = None) -> dict:
     """Apply a chain of incremental snapshots, oldest first, to ``dst`` (modified in
     place): ``links`` holds one (staging, manifest) pair per snapshot (sec. 4.6).
-    Only entries that are whole chunks of ``dst`` are applied.  Returns the numbers
-    of chunks written, of applied entries a later one overwrote, and of entries skipped."""
+    Only entries that are whole chunks of ``dst`` are applied, and with ``only`` (one
+    byte per chunk) only those of chunks it marks.  Returns the numbers of chunks
+    written, of applied entries a later one overwrote, and of entries skipped."""
+    if only is not None:
+        only = np.ascontiguousarray(only, dtype=np.uint8)
+        if only.size != nchunks(dst, chunk):
+            raise ValueError("one byte per chunk of the destination is needed")
     for b in dst:
         if not b.flags["WRITEABLE"]:
             raise TypeError("destination buffers must be writable")
     arr, keep = _links(links)
     stats = (ctypes.c_uint64 * 3)()
-    if _load().ora_restore_chain(_desc(dst), len(dst), chunk, arr, len(links), stats) != 0:
+    if _load().ora_restore_chain(_desc(dst), len(dst), chunk, arr, len(links), _p(only), stats) != 0:
         raise MemoryError("ora_restore_chain")
     return {"written": int(stats[0]), "superseded": int(stats[1]), "rejected": int(stats[2])}
 

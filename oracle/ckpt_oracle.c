@@ -370,6 +370,11 @@ uint64_t ora_restore(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const
  * whole chunk of the destination: besides what ora_restore asks, buf_off is a
  * multiple of the chunk size and len is that chunk's length (the chunk size,
  * or what is left of the buffer).  Other entries are skipped and counted.
+ * only (may be NULL) restricts the restore to some chunks: with only[k] == 0
+ * chunk k keeps its bytes whatever the links hold, and the entries that name it
+ * are not counted anywhere.  (At a context switch between time-sliced ranks,
+ * sec. 5.2.1, only the chunks whose checksum differs between the resident and
+ * the incoming rank have to come in.)
  *   stats[0] = chunks of the destination written at least once
  *   stats[1] = applied entries whose chunk a later entry wrote again
  *   stats[2] = entries skipped
@@ -382,7 +387,7 @@ typedef struct {
 } ora_link_t;
 
 int ora_restore_chain(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, const ora_link_t *links,
-                      uint64_t nlinks, uint64_t *stats) {
+                      uint64_t nlinks, const uint8_t *only, uint64_t *stats) {
   uint64_t n = 0;
   uint64_t *base = (uint64_t *)malloc((nbufs + 1) * sizeof(uint64_t));
   if (!base) return -1;
@@ -412,8 +417,9 @@ int ora_restore_chain(const ora_buf_t *dst, uint64_t nbufs, uint64_t chunk, cons
         skipped += 1;
         continue;
       }
-      memcpy((uint8_t *)dst[t->buf].ptr + t->buf_off, from + t->stage_off, t->len);
       uint64_t k = base[t->buf] + t->buf_off / chunk;
+      if (only && !only[k]) continue;
+      memcpy((uint8_t *)dst[t->buf].ptr + t->buf_off, from + t->stage_off, t->len);
       applied += 1;
       if (!written[k]) {
         written[k] = 1;

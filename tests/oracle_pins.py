@@ -112,6 +112,10 @@ def chain_pins():
     tc.test_merge_skips_what_the_chain_restore_skips_and_keeps_the_earlier_holder()
     tc.test_merge_capacities_follow_the_compaction_rule()
     tc.test_merge_of_nothing_is_empty()
+    for seed in (1, 2, 3):
+        tc.test_restricted_chain_writes_only_marked_chunks(seed)
+    tc.test_restriction_to_nothing_and_to_everything()
+    tc.test_a_switch_between_ranks_that_changed_different_chunks()
 
 
 def verdict_pins():

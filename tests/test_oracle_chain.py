@@ -271,3 +271,70 @@ def test_merge_of_nothing_is_empty():
     assert staging.size == 0 and man.size == 0
     assert counts == {"ndirty": 0, "staged_bytes": 0, "overflow": 0}
     assert stats == {"written": 0, "superseded": 0, "rejected": 0}
+
+
+# ---- a restore restricted to some chunks --------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_restricted_chain_writes_only_marked_chunks(seed):
+    """With `only`, an unmarked chunk keeps its bytes whatever the links hold; a marked one gets
+    the bytes of its latest holder; the counts are those of the chain cut down to marked chunks."""
+    rng = np.random.default_rng(100 + seed)
+    states, chosen = random_chain(seed, 4)
+    links = [link_of(s, CHUNK, c) for s, c in zip(states, chosen)]
+    n = len(pieces(SIZES, CHUNK))
+    only = (rng.random(n) < 0.5).astype(np.uint8)
+    only[only != 0] = rng.integers(1, 256, size=int(only.sum()), dtype=np.uint8)
+    start = [np.full(s, 0xA5, np.uint8) for s in SIZES]
+    dst = [b.copy() for b in start]
+    stats = oracle.restore_chain(dst, CHUNK, links, only)
+    kept = [np.array([k for k in c.tolist() if only[k]], dtype=np.int64) for c in chosen]
+    want = composed(start, states, kept, CHUNK)
+    assert all(np.array_equal(d, w) for d, w in zip(dst, want))
+    union = set().union(*[set(c.tolist()) for c in kept])
+    assert stats == {"written": len(union), "superseded": sum(c.size for c in kept) - len(union),
+                     "rejected": 0}
+
+
+def test_restriction_to_nothing_and_to_everything():
+    states, chosen = random_chain(8, 3)
+    links = [link_of(s, CHUNK, c) for s, c in zip(states, chosen)]
+    n = len(pieces(SIZES, CHUNK))
+    dst = [np.full(s, 0x3C, np.uint8) for s in SIZES]
+    assert oracle.restore_chain(dst, CHUNK, links, np.zeros(n, np.uint8)) == \
+        {"written": 0, "superseded": 0, "rejected": 0}
+    assert all(np.all(d == 0x3C) for d in dst)
+    a = [np.full(s, 0x3C, np.uint8) for s in SIZES]
+    b = [np.full(s, 0x3C, np.uint8) for s in SIZES]
+    assert oracle.restore_chain(a, CHUNK, links, np.ones(n, np.uint8)) == oracle.restore_chain(b, CHUNK, links)
+    assert all(np.array_equal(x, y) for x, y in zip(a, composed(b, states, chosen, CHUNK)))
+
+
+def test_a_switch_between_ranks_that_changed_different_chunks():
+    """What the restriction is for (sec. 5.2.1): the device holds rank A, rank B comes in.  Both
+    are kept as deltas against a base of which a full copy exists.  B may equal the base where A
+    does not, so B's delta alone would leave A's bytes behind; the chain [full base, B's delta]
+    restricted to the chunks whose checksums differ between A and B gives B exactly, and reads the
+    base only where B does not hold the chunk itself."""
+    rng = np.random.default_rng(21)
+    base = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in SIZES]
+    a, b = [x.copy() for x in base], [x.copy() for x in base]
+    a[0][300:900] ^= 0x11          # A alone changes chunks 1..3 of buffer 0
+    b[0][2060:2100] ^= 0x22        # B alone changes chunk 8
+    a[3][0:50] ^= 0x33             # both change chunk 0 of buffer 3, differently
+    b[3][0:50] ^= 0x44
+    a[5][1000:1100] ^= 0x55        # both change a chunk of buffer 5 to the same bytes
+    b[5][1000:1100] ^= 0x55
+    dig = {name: oracle.fingerprint(st, CHUNK) for name, st in (("base", base), ("a", a), ("b", b))}
+    full_mask, _ = oracle.diff(base, CHUNK, dig["base"], None)
+    base_link = oracle.compact(base, CHUNK, full_mask, dig["base"])[:2]
+    b_mask, _ = oracle.diff(b, CHUNK, dig["b"], dig["base"])
+    b_link = oracle.compact(b, CHUNK, b_mask, dig["b"])[:2]
+    incoming, _ = oracle.diff(b, CHUNK, dig["b"], dig["a"])       # where the resident rank differs
+    dst = [x.copy() for x in a]
+    stats = oracle.restore_chain(dst, CHUNK, [base_link, b_link], incoming)
+    assert all(np.array_equal(d, x) for d, x in zip(dst, b))
+    assert stats["written"] == int(incoming.sum()) == 3 + 1 + 1    # not the chunk both set alike
+    wrong = [x.copy() for x in a]                                  # B's delta alone is not enough
+    oracle.restore(wrong, CHUNK, *b_link)
+    assert not all(np.array_equal(d, x) for d, x in zip(wrong, b))

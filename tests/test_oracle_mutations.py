@@ -86,8 +86,14 @@ MUTATIONS = [
      "uint64_t k = t->buf_off / chunk;"),
     ("chain: every applied entry counted as superseded", "stats[1] = applied - distinct;",
      "stats[1] = applied;"),
-    ("chain: skipped entries not counted", "        skipped += 1;\n        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]",
-     "        continue;\n      }\n      memcpy((uint8_t *)dst[t->buf]"),
+    ("chain: skipped entries not counted",
+     "        skipped += 1;\n        continue;\n      }\n      uint64_t k = base[t->buf]",
+     "        continue;\n      }\n      uint64_t k = base[t->buf]"),
+    ("chain: restriction ignored", "      if (only && !only[k]) continue;", "      (void)only;"),
+    ("chain: restriction inverted", "      if (only && !only[k]) continue;",
+     "      if (only && only[k]) continue;"),
+    ("chain: restriction looked up by entry index", "      if (only && !only[k]) continue;",
+     "      if (only && !only[e]) continue;"),
     ("merge: entry of the first holder, bytes of the last", "      holder[k] = c;\n",
      "      if (!holder[k]) holder[k] = c;\n"),
     ("merge: bytes taken from the first link's staging",
