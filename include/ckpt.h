@@ -353,6 +353,16 @@ int ckpt_restore_counted(const ckpt_plan_t *dst_plan, const void *d_staging, uin
  *                NULL: manifest_cap entries
  *   nlinks       at most CKPT_CHAIN_MAX; a longer chain is restored by
  *                consecutive calls, oldest links first
+ *   d_only       optional device array of N bytes that restricts the restore:
+ *                a chunk with d_only[k] == 0 keeps its bytes whatever the links
+ *                hold, and entries naming it are counted nowhere.  At a context
+ *                switch (sec. 5.2.1 skips the swap-in of what the device already
+ *                holds) this is ckpt_diff of the incoming rank's digests against
+ *                the resident rank's, and the chain is [a full copy of the
+ *                common base, the incoming rank's delta]: exactly the chunks in
+ *                which the two ranks differ come in, from the delta where it has
+ *                them and from the base where the incoming rank never changed
+ *                what the resident one did
  *   d_workspace  device scratch of at least
  *                ckpt_restore_chain_workspace_bytes(N) bytes, 16-byte aligned
  *   d_stats      optional device ckpt_chain_stats_t, 8-byte aligned
@@ -374,8 +384,8 @@ typedef struct ckpt_chain_stats {
 } ckpt_chain_stats_t;
 uint64_t ckpt_restore_chain_workspace_bytes(uint64_t nchunks);
 int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
-                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
-                       void *stream);
+                       const uint8_t *d_only, void *d_workspace, uint64_t workspace_bytes,
+                       ckpt_chain_stats_t *d_stats, void *stream);
 
 /* Folds a chain into ONE link that restores to the same result, so that a chain
  * of increments (sec. 4.6) can be kept short: what a later link replaced is

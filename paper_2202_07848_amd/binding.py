@@ -100,7 +100,7 @@ def _lib():
         lib.ckpt_restore_chain_workspace_bytes.restype = u64
         lib.ckpt_restore_chain_workspace_bytes.argtypes = [u64]
         lib.ckpt_restore_chain.restype = ci
-        lib.ckpt_restore_chain.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        lib.ckpt_restore_chain.argtypes = [vp, vp, u64, vp, vp, u64, vp, vp]
         lib.ckpt_merge_chain_workspace_bytes.restype = u64
         lib.ckpt_merge_chain_workspace_bytes.argtypes = [u64]
         lib.ckpt_merge_chain.restype = ci
@@ -389,12 +389,12 @@ def merge_chain(plan: Plan, links, staging, manifest, counts, workspace, stats=N
                                    _stream(stream)), "ckpt_merge_chain")
 
 
-def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None) -> None:
+def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None, only=None) -> None:
     """``ckpt_restore_chain``: ``links`` is a sequence, oldest first, of
     (staging, staging_bytes, manifest, manifest_cap, counts or None); workspace is a uint8
-    tensor, stats (optional) 3 x int64."""
+    tensor, stats (optional) 3 x int64, only (optional) one uint8 per chunk: 0 = leave alone."""
     arr = _links(links)
-    _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(workspace),
+    _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(only), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _ptr(stats),
                                      _stream(stream)), "ckpt_restore_chain")
 

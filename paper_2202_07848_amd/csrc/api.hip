@@ -569,8 +569,8 @@ int chain_args(const ckpt_link_t *links, uint64_t nlinks, ckpt::ChainArgs *a) {
 extern "C" {
 
 int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, uint64_t nlinks,
-                       void *d_workspace, uint64_t workspace_bytes, ckpt_chain_stats_t *d_stats,
-                       void *stream) {
+                       const uint8_t *d_only, void *d_workspace, uint64_t workspace_bytes,
+                       ckpt_chain_stats_t *d_stats, void *stream) {
   if (dst_plan == nullptr || d_workspace == nullptr) return CKPT_ERR_INVALID_ARG;
   if (!aligned(d_workspace, 16) || !aligned(d_stats, 8)) return CKPT_ERR_ALIGNMENT;
   ckpt::ChainArgs a;
@@ -578,7 +578,8 @@ int ckpt_restore_chain(const ckpt_plan_t *dst_plan, const ckpt_link_t *links, ui
   if (rc != CKPT_OK) return rc;
   if (workspace_bytes < ckpt_restore_chain_workspace_bytes(dst_plan->dev.nchunks))
     return CKPT_ERR_CAPACITY;
-  hipError_t e = ckpt::launch_restore_chain(dst_plan->dev, a, static_cast<uint64_t *>(d_workspace),
+  hipError_t e = ckpt::launch_restore_chain(dst_plan->dev, a, d_only,
+                                            static_cast<uint64_t *>(d_workspace),
                                             reinterpret_cast<uint64_t *>(d_stats),
                                             static_cast<hipStream_t>(stream));
   return e == hipSuccess ? CKPT_OK : device_error(e);

@@ -62,6 +62,7 @@ __global__ __launch_bounds__(256) void k_chain_clear(unsigned long long *__restr
 
 // grid = (workgroups per link, links)
 __global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
+                                                    const uint8_t *__restrict__ only,
                                                     unsigned long long *__restrict__ last,
                                                     unsigned long long *stats) {
   const uint32_t l = blockIdx.y;
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(256) void k_chain_mark(PlanDev p, ChainArgs a,
       ++skipped;
       continue;
     }
+    if (only != nullptr && only[k] == 0) continue;          // the caller keeps this chunk as it is
     const unsigned long long key = ((unsigned long long)(l + 1) << CHAIN_ENTRY_BITS) | e;
     const unsigned long long old = atomicMax(&last[k], key);
     ++applied;
@@ -248,9 +250,9 @@ uint32_t groups_for(uint64_t n, uint64_t per_group, uint64_t most) {
 
 // clear + mark.  *entries receives the host bound on the entries of all links together; zero
 // means no link can hold anything.
-hipError_t launch_chain_keys(const PlanDev &p, const ChainArgs &a, unsigned long long *last,
-                             unsigned long long *count, unsigned long long *stats,
-                             uint64_t *entries, hipStream_t s) {
+hipError_t launch_chain_keys(const PlanDev &p, const ChainArgs &a, const uint8_t *only,
+                             unsigned long long *last, unsigned long long *count,
+                             unsigned long long *stats, uint64_t *entries, hipStream_t s) {
   hipLaunchKernelGGL(k_chain_clear, dim3(groups_for(p.nchunks, 256 * 8, 4096)), dim3(256), 0, s,
                      last, p.nchunks, count, stats);
   hipError_t e = hipGetLastError();
@@ -263,21 +265,21 @@ hipError_t launch_chain_keys(const PlanDev &p, const ChainArgs &a, unsigned long
   if (e != hipSuccess || most == 0) return e;
   // with an empty destination this still counts every entry as skipped
   hipLaunchKernelGGL(k_chain_mark, dim3(groups_for(most, 256, 2048), a.nlinks), dim3(256), 0, s, p,
-                     a, last, stats);
+                     a, only, last, stats);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
-                                uint64_t *d_stats, hipStream_t s) {
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, const uint8_t *d_only,
+                                uint64_t *d_workspace, uint64_t *d_stats, hipStream_t s) {
   // workspace: last[N], list[N], one counter
   unsigned long long *last = reinterpret_cast<unsigned long long *>(d_workspace);
   unsigned long long *list = last + p.nchunks;
   unsigned long long *count = list + p.nchunks;
   uint64_t entries = 0;
-  hipError_t e = launch_chain_keys(p, a, last, count, reinterpret_cast<unsigned long long *>(d_stats),
-                                   &entries, s);
+  hipError_t e = launch_chain_keys(p, a, d_only, last, count,
+                                   reinterpret_cast<unsigned long long *>(d_stats), &entries, s);
   if (e != hipSuccess || entries == 0 || p.nchunks == 0) return e;
 
   const uint64_t spans = (p.nchunks + LIST_SPAN - 1) / LIST_SPAN;
@@ -306,8 +308,8 @@ hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_stag
   unsigned long long *spare = last + 2 * p.nchunks;
   uint8_t *mask = reinterpret_cast<uint8_t *>(spare + 2);
   uint64_t entries = 0;
-  hipError_t e = launch_chain_keys(p, a, last, spare, reinterpret_cast<unsigned long long *>(d_stats),
-                                   &entries, s);
+  hipError_t e = launch_chain_keys(p, a, nullptr, last, spare,
+                                   reinterpret_cast<unsigned long long *>(d_stats), &entries, s);
   if (e != hipSuccess) return e;
   if (p.nchunks != 0)
     hipLaunchKernelGGL(k_chain_mask, dim3(groups_for(p.nchunks, 256, 4096)), dim3(256), 0, s, a,

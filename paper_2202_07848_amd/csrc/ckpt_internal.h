@@ -188,9 +188,10 @@ struct ChainArgs {
   const ckpt_counts_t *counts[CKPT_CHAIN_MAX];  // null: cap entries; else min(cap, ndirty)
   uint32_t nlinks;
 };
-// d_workspace: 2 N + 1 uint64 (scratch); d_stats (may be null): written, superseded, skipped.
-hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, uint64_t *d_workspace,
-                                uint64_t *d_stats, hipStream_t s);
+// d_only (may be null): chunks with d_only[k] == 0 are left alone; d_workspace: 2 N + 1 uint64
+// (scratch); d_stats (may be null): written, superseded, skipped.
+hipError_t launch_restore_chain(const PlanDev &p, const ChainArgs &a, const uint8_t *d_only,
+                                uint64_t *d_workspace, uint64_t *d_stats, hipStream_t s);
 // Folds the chain into one link laid out like a snapshot's.  d_workspace: 2 N + 2 uint64 and N
 // bytes (scratch); d_pairs: the plan's scan scratch.
 hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_staging,

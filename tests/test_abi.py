@@ -67,7 +67,7 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.ckpt_restore(None, None, 0, None, 0, None, None) == -1
     assert lib.ckpt_manifest(None, None, None, 0, None, 0, None, None) == -1
     assert lib.ckpt_buffer_verdicts(None, None, None, None, None) == -1
-    assert lib.ckpt_restore_chain(None, None, 0, None, 0, None, None) == -1
+    assert lib.ckpt_restore_chain(None, None, 0, None, None, 0, None, None) == -1
     assert lib.ckpt_restore_chain_workspace_bytes(1000) == 16016
     assert lib.ckpt_merge_chain(None, None, 0, None, 0, None, 0, None, None, 0, None, None) == -1
     assert lib.ckpt_merge_chain_workspace_bytes(1000) == 16016 + 1008
@@ -126,7 +126,7 @@ int main(void) {
   ckpt_plan_t *plan = (ckpt_plan_t *)0;
   ckpt_buf_t one = {(void *)0x1000, 4096};
   if (ckpt_plan_create(&one, 1, 1000, &plan) != CKPT_ERR_CHUNK || plan) return 1;
-  if (ckpt_restore_chain(0, 0, 0, 0, 0, 0, 0) != CKPT_ERR_INVALID_ARG) return 2;
+  if (ckpt_restore_chain(0, 0, 0, 0, 0, 0, 0, 0) != CKPT_ERR_INVALID_ARG) return 2;
   if (ckpt_version() < 1 || !ckpt_strerror(CKPT_ERR_CAPACITY)[0]) return 3;
   printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %d\n", sizeof(ckpt_buf_t), sizeof(ckpt_entry_t),
          offsetof(ckpt_entry_t, buf_off), offsetof(ckpt_entry_t, stage_off),

@@ -44,13 +44,15 @@ def upload(links, slack=64):
     return out
 
 
-def run_chain(dst, dev_links, with_stats=True):
+def run_chain(dst, dev_links, with_stats=True, only=None):
     import torch
     from paper_2202_07848_amd import binding as ck
     ws = torch.full((ck.restore_chain_workspace_bytes(dst.plan.nchunks) + 16,), 0xEE,
                     dtype=torch.uint8, device="cuda")
     stats = torch.full((3,), -7, dtype=torch.int64, device="cuda") if with_stats else None
-    ck.restore_chain(dst.plan, dev_links, ws, stats)
+    d_only = None if only is None else torch.from_numpy(
+        np.concatenate([only, np.full(16, 0xFF, np.uint8)])).cuda()
+    ck.restore_chain(dst.plan, dev_links, ws, stats, only=d_only)
     torch.cuda.synchronize()
     if stats is None:
         return None
@@ -58,13 +60,13 @@ def run_chain(dst, dev_links, with_stats=True):
     return {"written": int(v[0]), "superseded": int(v[1]), "rejected": int(v[2])}
 
 
-def check(sizes, chunk, links, start_byte=0x5A):
+def check(sizes, chunk, links, start_byte=0x5A, only=None):
     from gpu_util import DeviceBuffers
     start = [np.full(n, start_byte, np.uint8) for n in sizes]
     want = [b.copy() for b in start]
-    want_stats = oracle.restore_chain(want, chunk, links)
+    want_stats = oracle.restore_chain(want, chunk, links, only)
     dst = DeviceBuffers(start, chunk)
-    got_stats = run_chain(dst, upload(links))
+    got_stats = run_chain(dst, upload(links), only=only)
     got, img = dst.host()
     for i, (g, w) in enumerate(zip(got, want)):
         assert np.array_equal(g, w), f"buffer {i} differs"
@@ -119,6 +121,26 @@ def test_random_subsets_in_sixteen_links(seed):
         links.append(sliced_link(state, chunk, chosen.tolist()))
     stats = check(sizes, chunk, links)
     assert stats["superseded"] > 0 and stats["written"] < n
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("density", [0.0, 0.1, 0.6, 1.0])
+def test_restore_restricted_to_marked_chunks(seed, density):
+    """d_only: unmarked chunks keep their bytes and their entries are counted nowhere; bad
+    entries are still counted."""
+    sizes, chunk = [9000, 512, 0, 2600, 150, 8192, 33000], 512
+    rng = np.random.default_rng(50 + seed)
+    n = sum((s + chunk - 1) // chunk for s in sizes)
+    links = []
+    for _ in range(5):
+        state = [rng.integers(0, 256, size=s, dtype=np.uint8) for s in sizes]
+        chosen = np.sort(rng.choice(n, size=int(rng.integers(1, n)), replace=False))
+        links.append(sliced_link(state, chunk, chosen.tolist()))
+    links[2][1]["buf"][0] = 77                 # one entry that fits nowhere
+    only = (rng.random(n) < density).astype(np.uint8)
+    only[only != 0] = rng.integers(1, 256, size=int(only.sum()), dtype=np.uint8)
+    stats = check(sizes, chunk, links, only=only)
+    assert stats["rejected"] == 1 and stats["written"] <= int((only != 0).sum())
 
 
 def test_a_chunk_held_twice_by_one_link_and_unsorted_entries():

@@ -305,3 +305,87 @@ def test_exchange_skips_entries_that_do_not_fit_and_checks_its_arguments():
     with pytest.raises(ck.CkptError) as e:
         ck.exchange(dev.plan, man_out, counts, out[8:], need, man_in, counts, inn, need, n)
     assert e.value.status == -2
+
+
+def chunk_differences(w, a, b):
+    """Number of chunks in which two states differ, by comparing their bytes."""
+    count = 0
+    for x, y in zip(a, b):
+        for o in range(0, x.size, w.chunk):
+            count += not np.array_equal(x[o:o + w.chunk], y[o:o + w.chunk])
+    return count
+
+
+def test_exact_switch_between_ranks_that_changed_different_chunks():
+    """Ranks that differ from the base in different chunks: one changes shared state on its own,
+    one has a per-rank buffer that equals the base, and every mini-batch rewrites a few chunks
+    anywhere.  `switch_exact` must leave exactly the incoming rank's state on the device after
+    every switch, having written exactly the chunks in which the two ranks differ; the oracle's
+    restricted chain restore, replayed on the host, must agree."""
+    w = wl.config(4, 8)
+    base = wl.numpy_replica(w, 0)
+    state = [wl.numpy_replica(w, r) for r in range(1, NRANKS + 1)]
+    shared = [i for i, b in enumerate(w.bufs) if b.shared and b.nbytes >= 4 * w.chunk]
+    own = [i for i, b in enumerate(w.bufs) if not b.shared and b.nbytes >= 64]
+    state[1][shared[0]][w.chunk:w.chunk + 100] ^= 0x5A           # rank 1 changes shared state alone
+    state[2][own[0]][:] = base[own[0]]                            # rank 2 equals the base there
+    state[3][shared[1]][5:50] ^= 0x21
+    state[3][own[1]][:] = base[own[1]]
+
+    dev = DeviceBuffers(base, w.chunk)                            # the base is resident first
+    n = dev.plan.nchunks
+    o_ref = oracle.fingerprint(base, w.chunk, 8)
+    ref = torch.from_numpy(o_ref.view(np.int64)).cuda()
+    cap_bytes, cap_entries = 2 * w.distinct_bytes + 16 * n, n
+    sw = TimeSlicedRanks(dev.plan, ref, NRANKS, cap_bytes, cap_entries, exact=True)
+    sw.capture_base(max_slice_bytes=w.nbytes // 3)                # the base copy in several slices
+    full_mask, _ = oracle.diff(base, w.chunk, o_ref, None)
+    base_link = oracle.compact(base, w.chunk, full_mask, o_ref)[:2]
+    assert len(sw.base_links) >= 3 and sw.base_bytes == base_link[0].size
+    assert np.array_equal(np.concatenate([l[0].numpy()[:l[1]] for l in sw.base_links]), base_link[0])
+
+    def put(r):                                                   # the rank's state onto the device
+        for i, b in enumerate(state[r]):
+            dev.arena[dev.offs[i]:dev.offs[i] + b.size] = torch.from_numpy(b).cuda()
+
+    swapped = [None] * NRANKS                                     # each rank's state at its last swap-out
+    for r in range(NRANKS):                                       # every rank has been resident once
+        put(r)
+        sw.swap_out(r)
+        torch.cuda.synchronize()
+        swapped[r] = [b.copy() for b in state[r]]
+    resident = NRANKS - 1
+
+    rng = np.random.default_rng(12)
+    everywhere = [i for i, b in enumerate(w.bufs) if b.nbytes >= 64]
+    for step in range(2 * NRANKS + 1):
+        # a mini-batch of the resident rank: fresh bytes in a few chunks of ANY buffer
+        for i in rng.choice(everywhere, size=5, replace=False).tolist():
+            nb = w.bufs[i].nbytes
+            lo = int(rng.integers(0, nb - 32))
+            hi = min(nb, lo + int(rng.integers(1, 2 * w.chunk)))
+            fresh = rng.integers(0, 256, size=hi - lo, dtype=np.uint8)
+            state[resident][i][lo:hi] = fresh
+            dev.arena[dev.offs[i] + lo:dev.offs[i] + hi] = torch.from_numpy(fresh).cuda()
+        nxt = (resident + 2) % NRANKS if step % 3 == 2 else (resident + 1) % NRANKS
+        sw.switch_exact(resident, nxt)
+        torch.cuda.synchronize()
+        swapped[resident] = [b.copy() for b in state[resident]]
+        got, img = dev.host()
+        assert all(np.array_equal(g, s) for g, s in zip(got, state[nxt])), step
+        assert dev.canaries_intact(img)
+        stats = [int(x) for x in sw.chain_stats.cpu().numpy().view(np.uint64)]
+        assert stats[0] == chunk_differences(w, state[resident], state[nxt]) and stats[2] == 0
+
+        # the same switch replayed on the host with the oracle
+        dig_out = oracle.fingerprint(state[resident], w.chunk, 8)
+        dig_in = oracle.fingerprint(swapped[nxt], w.chunk, 8)
+        m_in, _ = oracle.diff(swapped[nxt], w.chunk, dig_in, o_ref)
+        delta = oracle.compact(swapped[nxt], w.chunk, m_in, dig_in)[:2]
+        only, _ = oracle.diff(swapped[nxt], w.chunk, dig_in, dig_out)
+        host_image = [b.copy() for b in state[resident]]
+        o_stats = oracle.restore_chain(host_image, w.chunk, [base_link, delta], only)
+        assert all(np.array_equal(h, s) for h, s in zip(host_image, state[nxt]))
+        assert [o_stats["written"], o_stats["superseded"], o_stats["rejected"]] == stats
+        assert np.array_equal(sw.incoming[:n].cpu().numpy(), only)
+        resident = nxt
