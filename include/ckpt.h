@@ -51,8 +51,9 @@ typedef enum ckpt_status {
   CKPT_ERR_ALIGNMENT = -2,   /* a buffer / staging / digest / manifest pointer is misaligned */
   CKPT_ERR_CHUNK = -3,       /* chunk size not a power of two in [256 B, 1 GiB], or two plans differ */
   CKPT_ERR_GEOMETRY = -4,    /* reference digest count differs from the plan's N */
-  CKPT_ERR_CAPACITY = -5,    /* workspace too small (ckpt_match); also free for callers that turn
-                                counts.overflow into a status */
+  CKPT_ERR_CAPACITY = -5,    /* workspace too small (ckpt_match, ckpt_restore_chain,
+                                ckpt_merge_chain), plan too large (ckpt_snapshot_static); also
+                                free for callers that turn counts.overflow into a status */
   CKPT_ERR_DEVICE = -6,      /* a HIP call failed (see ckpt_last_device_error) */
   CKPT_ERR_NOMEM = -7        /* host or device allocation failed in ckpt_plan_create */
 } ckpt_status;
@@ -95,10 +96,12 @@ typedef struct ckpt_plan ckpt_plan_t; /* opaque, library-owned */
  *               fingerprint runs at a fraction of the memory bandwidth
  *   out         receives the plan; destroy it with ckpt_plan_destroy
  * A plan also owns a small scan scratch that ckpt_diff, ckpt_compact,
- * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_merge_chain, ckpt_upload_owners,
- * ckpt_swap_out and ckpt_apply_moves_inplace write: calls of these on ONE plan must be ordered
- * (one stream, or events); issued on two streams at once they race.  ckpt_fingerprint, ckpt_restore and
- * the other calls only read the plan and may overlap freely.
+ * ckpt_snapshot, ckpt_manifest, ckpt_exchange, ckpt_merge_chain,
+ * ckpt_upload_owners, ckpt_swap_out and ckpt_apply_moves_inplace write: calls of
+ * these on ONE plan must be ordered (one stream, or events); issued on two
+ * streams at once they race.  ckpt_fingerprint, ckpt_restore,
+ * ckpt_restore_chain and the other calls only read the plan and may overlap
+ * freely.
  * Two non-empty buffers that share a byte are refused (INVALID_ARG): restoring
  * into such a list has no defined result, and an allocator never hands out
  * overlapping live buffers.
