@@ -389,3 +389,63 @@ def test_exact_switch_between_ranks_that_changed_different_chunks():
         assert [o_stats["written"], o_stats["superseded"], o_stats["rejected"]] == stats
         assert np.array_equal(sw.incoming[:n].cpu().numpy(), only)
         resident = nxt
+
+
+def test_exact_switches_replay_from_hip_graphs():
+    """switch_exact enqueues kernels only (the chain restore takes its links as kernel
+    arguments and reads counts and the restriction on the device), so it replays from a graph:
+    two ranks ping-pong through two graphs while the resident rank rewrites chunks anywhere,
+    shared state included; after every replay the image is the incoming rank's state."""
+    w = wl.config(4, 12)
+    base = wl.numpy_replica(w, 0)
+    state = [wl.numpy_replica(w, r) for r in (1, 2)]
+    dev = DeviceBuffers(base, w.chunk)
+    n = dev.plan.nchunks
+    ref = torch.from_numpy(oracle.fingerprint(base, w.chunk, 8).view(np.int64)).cuda()
+    sw = TimeSlicedRanks(dev.plan, ref, 2, 2 * w.distinct_bytes + 16 * n, n, exact=True)
+    sw.capture_base(max_slice_bytes=w.nbytes // 2)
+
+    def put(r):
+        for i, b in enumerate(state[r]):
+            dev.arena[dev.offs[i]:dev.offs[i] + b.size] = torch.from_numpy(b).cuda()
+
+    for r in (0, 1):
+        put(r)
+        sw.swap_out(r)
+        torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = {}
+    with torch.cuda.stream(side):
+        for a, b in ((1, 0), (0, 1)):                   # eager round trip on the capture stream
+            sw.switch_exact(a, b, stream=side)
+        side.synchronize()
+        for a, b in ((1, 0), (0, 1)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                sw.switch_exact(a, b, stream=side)
+            graphs[(a, b)] = g
+    torch.cuda.synchronize()
+    got, _ = dev.host()
+    assert all(np.array_equal(x, y) for x, y in zip(got, state[1]))
+
+    rng = np.random.default_rng(19)
+    everywhere = [i for i, b in enumerate(w.bufs) if b.nbytes >= 64]
+    resident = 1
+    for step in range(6):
+        for i in rng.choice(everywhere, size=4, replace=False).tolist():
+            nb = w.bufs[i].nbytes
+            lo = int(rng.integers(0, nb - 32))
+            hi = min(nb, lo + int(rng.integers(1, 2 * w.chunk)))
+            fresh = rng.integers(0, 256, size=hi - lo, dtype=np.uint8)
+            state[resident][i][lo:hi] = fresh
+            dev.arena[dev.offs[i] + lo:dev.offs[i] + hi] = torch.from_numpy(fresh).cuda()
+        nxt = 1 - resident
+        graphs[(resident, nxt)].replay()
+        torch.cuda.synchronize()
+        got, img = dev.host()
+        assert all(np.array_equal(x, y) for x, y in zip(got, state[nxt])), step
+        assert dev.canaries_intact(img)
+        stats = [int(x) for x in sw.chain_stats.cpu().numpy().view(np.uint64)]
+        assert stats[0] == chunk_differences(w, state[resident], state[nxt]) and stats[2] == 0
+        resident = nxt
