@@ -88,6 +88,8 @@ def _load():
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         lib.ora_restore_chain.restype = ctypes.c_int
         lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp, vp]
+        lib.ora_mask_andnot.restype = None
+        lib.ora_mask_andnot.argtypes = [u64, vp, vp, vp]
         lib.ora_buffer_verdicts.restype = None
         lib.ora_buffer_verdicts.argtypes = [vp, u64, u64, vp, vp, vp]
         lib.ora_merge_chain.restype = ctypes.c_int
@@ -330,3 +332,14 @@ def buffer_verdicts(sizes: Sequence[int], chunk: int, mask: np.ndarray) -> Tuple
     res = (ctypes.c_uint64 * 2)()
     _load().ora_buffer_verdicts(_p(sz), sz.size, chunk, _p(mask), _p(dirty), res)
     return dirty, {"buffers": int(res[0]), "bytes": int(res[1])}
+
+
+def mask_andnot(mask: np.ndarray, without: np.ndarray) -> np.ndarray:
+    """1 where ``mask`` is set and ``without`` is not (any non-zero byte counts as set)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    without = np.ascontiguousarray(without, dtype=np.uint8)
+    if mask.size != without.size:
+        raise ValueError("the two masks must have one byte per chunk each")
+    out = np.full(mask.size, 0xA5, dtype=np.uint8)
+    _load().ora_mask_andnot(mask.size, _p(mask), _p(without), _p(out))
+    return out

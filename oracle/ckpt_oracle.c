@@ -679,6 +679,16 @@ void ora_buffer_verdicts(const uint64_t *sizes, uint64_t nbufs, uint64_t chunk, 
   result[1] = bytes;
 }
 
+/* ---------------------------------------------------------- mask and-not */
+/* out[k] = 1 where mask[k] is set and without[k] is not, else 0.  At a context
+ * switch (sec. 5.2.1) with mask = the chunks in which the outgoing rank differs
+ * from the common base and without = those of the incoming rank, these are the
+ * chunks the incoming rank's own delta does not bring back: the outgoing rank
+ * changed them, the incoming one never did, so the base's bytes have to return. */
+void ora_mask_andnot(uint64_t n, const uint8_t *mask, const uint8_t *without, uint8_t *out) {
+  for (uint64_t k = 0; k < n; ++k) out[k] = (mask[k] != 0 && without[k] == 0) ? 1 : 0;
+}
+
 /* ----------------------------------------------------- mutation validation */
 /* Squashing validation (sec. 5.2.3): the mutations a rank performed between
  * two points are the chunks whose checksum changed; two ranks sharing a GPU

@@ -126,6 +126,7 @@ def verdict_pins():
     tb.test_verdict_equals_byte_inequality_of_the_buffers()
     tb.test_each_single_chunk_marks_exactly_its_buffer()
     tb.test_empty_list_and_only_empty_buffers()
+    tb.test_mask_andnot_truth_table_and_random()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -199,7 +200,7 @@ def use_library(path):
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
                "ora_compact", "ora_restore", "ora_restore_chain", "ora_merge_chain",
-               "ora_buffer_verdicts", "ora_upload_owners", "ora_match", "ora_apply_matches",
+               "ora_buffer_verdicts", "ora_mask_andnot", "ora_upload_owners", "ora_match", "ora_apply_matches",
                "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes

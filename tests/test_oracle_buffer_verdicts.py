@@ -59,3 +59,14 @@ def test_empty_list_and_only_empty_buffers():
     assert dirty.size == 0 and counts == {"buffers": 0, "bytes": 0}
     dirty, counts = oracle.buffer_verdicts([0, 0], CHUNK, np.zeros(0, np.uint8))
     assert dirty.tolist() == [0, 0] and counts == {"buffers": 0, "bytes": 0}
+
+
+def test_mask_andnot_truth_table_and_random():
+    a = np.array([0, 0, 1, 1, 7, 0, 255, 3], np.uint8)
+    b = np.array([0, 1, 0, 1, 0, 9, 255, 0], np.uint8)
+    assert oracle.mask_andnot(a, b).tolist() == [0, 0, 1, 0, 1, 0, 0, 1]
+    rng = np.random.default_rng(3)
+    a = rng.integers(0, 3, size=5000, dtype=np.uint8)
+    b = rng.integers(0, 3, size=5000, dtype=np.uint8)
+    assert np.array_equal(oracle.mask_andnot(a, b), ((a != 0) & (b == 0)).astype(np.uint8))
+    assert oracle.mask_andnot(np.zeros(0, np.uint8), np.zeros(0, np.uint8)).size == 0

@@ -113,6 +113,10 @@ MUTATIONS = [
      "    for (uint64_t j = 0; j < n; ++j, ++k)\n      if (mask[k]) any = 1;",
      "    for (uint64_t j = 0; j < n; ++j) {\n      if (mask[k]) any = 1;\n      if (any) ++k;\n    }"),
     ("verdicts: bytes counted in chunks", "      bytes += sizes[i];", "      bytes += n * chunk;"),
+    ("andnot: second mask not negated", "(mask[k] != 0 && without[k] == 0) ? 1 : 0",
+     "(mask[k] != 0 && without[k] != 0) ? 1 : 0"),
+    ("andnot: only the value 1 counts as set", "(mask[k] != 0 && without[k] == 0) ? 1 : 0",
+     "(mask[k] == 1 && without[k] == 0) ? 1 : 0"),
     ("owner: row stride of gathered checksums", "if (gathered[(uint64_t)r * N + k] != mine) continue;",
      "if (gathered[(uint64_t)r * (N - 1) + k] != mine) continue;"),
 ]
