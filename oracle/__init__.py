@@ -50,9 +50,13 @@ class _Counts(ctypes.Structure):
 def build(force: bool = False) -> str:
     """Compile ckpt_oracle.c with gcc.  Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        # built under a private name and renamed into place, so that a process loading the
+        # library while another one rebuilds it never sees a half-written file
+        tmp = "%s.%d.tmp" % (_LIB, os.getpid())
         cmd = ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread",
-               _SRC, "-o", _LIB]
+               _SRC, "-o", tmp]
         subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
     return _LIB
 
 
