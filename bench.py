@@ -402,7 +402,8 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
     ev = torch.cuda.Event
     rounds, ok, modes = 2, True, {}
     for mode, exchange in (("swap_out_then_swap_in", False), ("exchange_pass", True),
-                           ("exact_for_any_change_sets", None)):
+                           ("exact_for_any_change_sets", None),
+                           ("exact_exchange_then_repair", "exact")):
         ms, wall_ms, enq_ms, serial = [], [], [], 0
         resident = 0
         for step in range(rounds * nranks):
@@ -413,6 +414,8 @@ def context_switch_leg(w, replicas, ref, ck, wl, torch, np, args):
             e0.record()
             if exchange is None:
                 sw.switch_exact(resident, nxt)
+            elif exchange == "exact":
+                sw.switch_exact(resident, nxt, exchange=True)
             else:
                 sw.switch(resident, nxt, exchange=exchange)
             e1.record()

@@ -543,6 +543,17 @@ typedef struct ckpt_buffer_counts {
 int ckpt_buffer_verdicts(const ckpt_plan_t *plan, const uint8_t *d_mask, uint8_t *d_buf_dirty,
                          ckpt_buffer_counts_t *d_counts, void *stream);
 
+/* d_out[k] = 1 where d_mask[k] != 0 and d_without[k] == 0, else 0, for the N
+ * chunks of the plan.  With d_mask the chunks in which the outgoing rank of a
+ * context switch differs from the common base and d_without those of the
+ * incoming rank (sec. 5.2.1), the result marks what the incoming rank's own
+ * delta does not bring back -- the chunks only the outgoing rank changed -- and
+ * is the d_only of a ckpt_restore_chain over a copy of the base.  d_out may be
+ * d_mask or d_without.  No alignment requirement.
+ * Errors: INVALID_ARG, DEVICE. */
+int ckpt_mask_andnot(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint8_t *d_without,
+                     uint8_t *d_out, void *stream);
+
 /* ---- squashing validation -------------------------------------------------- */
 
 /* Sec. 5.2.3 validates operation squashing by inferring mutations from

@@ -31,7 +31,7 @@ EXPORTS = (
     "ckpt_snapshot_workspace_bytes", "ckpt_snapshot_stats_offset", "ckpt_snapshot",
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
-    "ckpt_validate_mutations", "ckpt_upload_owners", "ckpt_buffer_verdicts",
+    "ckpt_validate_mutations", "ckpt_upload_owners", "ckpt_buffer_verdicts", "ckpt_mask_andnot",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_bw_streams", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -129,6 +129,8 @@ def _lib():
         lib.ckpt_moves_workspace_bytes.argtypes = [u64]
         lib.ckpt_apply_moves_inplace.restype = ci
         lib.ckpt_apply_moves_inplace.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp]
+        lib.ckpt_mask_andnot.restype = ci
+        lib.ckpt_mask_andnot.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_buffer_verdicts.restype = ci
         lib.ckpt_buffer_verdicts.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_validate_mutations.restype = ci
@@ -397,6 +399,12 @@ def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None, onl
     _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(only), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _ptr(stats),
                                      _stream(stream)), "ckpt_restore_chain")
+
+
+def mask_andnot(plan: Plan, mask, without, out, stream=None) -> None:
+    """``ckpt_mask_andnot``: out[k] = 1 where mask[k] is set and without[k] is not (uint8, N)."""
+    _check(_lib().ckpt_mask_andnot(plan._h, _ptr(mask), _ptr(without), _ptr(out), _stream(stream)),
+           "ckpt_mask_andnot")
 
 
 def buffer_verdicts(plan: Plan, mask, buf_dirty, counts, stream=None) -> None:

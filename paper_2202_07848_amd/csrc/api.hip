@@ -664,6 +664,16 @@ int ckpt_apply_moves_inplace(const ckpt_plan_t *plan, const int64_t *d_src, void
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+int ckpt_mask_andnot(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint8_t *d_without,
+                     uint8_t *d_out, void *stream) {
+  if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nchunks != 0 && (d_mask == nullptr || d_without == nullptr || d_out == nullptr))
+    return CKPT_ERR_INVALID_ARG;
+  hipError_t e = ckpt::launch_mask_andnot(plan->dev.nchunks, d_mask, d_without, d_out,
+                                          static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_buffer_verdicts(const ckpt_plan_t *plan, const uint8_t *d_mask, uint8_t *d_buf_dirty,
                          ckpt_buffer_counts_t *d_counts, void *stream) {
   if (plan == nullptr || d_counts == nullptr) return CKPT_ERR_INVALID_ARG;

@@ -537,6 +537,35 @@ __global__ __launch_bounds__(256) void k_verdict_count(PlanDev p, const uint8_t 
   }
 }
 
+// out[k] = 1 where mask[k] is set and without[k] is not.  Sixteen chunks per thread when the
+// three arrays allow 16-byte accesses, else one.
+__global__ __launch_bounds__(256) void k_mask_andnot(uint64_t n, const uint8_t *mask,
+                                                     const uint8_t *without, uint8_t *out,
+                                                     bool wide) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  const uint64_t tid = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  uint64_t done = 0;
+  if (wide) {
+    const uint64_t n16 = n / 16;
+    for (uint64_t i = tid; i < n16; i += stride) {
+      const uint4 a = reinterpret_cast<const uint4 *>(mask)[i];
+      const uint4 b = reinterpret_cast<const uint4 *>(without)[i];
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+      uint32_t r[4];
+      for (int w = 0; w < 4; ++w) {
+        r[w] = 0;
+        for (int byte = 0; byte < 4; ++byte) {
+          const uint32_t m = (aw[w] >> (8 * byte)) & 0xFF, x = (bw[w] >> (8 * byte)) & 0xFF;
+          r[w] |= (uint32_t)(m != 0 && x == 0) << (8 * byte);
+        }
+      }
+      reinterpret_cast<uint4 *>(out)[i] = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+    done = n16 * 16;
+  }
+  for (uint64_t k = done + tid; k < n; k += stride) out[k] = (mask[k] != 0 && without[k] == 0) ? 1 : 0;
+}
+
 inline uint32_t scan_blocks(uint64_t nchunks) {
   return (uint32_t)((nchunks + SCAN_BLOCK - 1) / SCAN_BLOCK);
 }
@@ -639,6 +668,18 @@ hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a,
     hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
                        b_b, a_b, d_result);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_andnot(uint64_t n, const uint8_t *d_mask, const uint8_t *d_without,
+                              uint8_t *d_out, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const bool wide = ((reinterpret_cast<uintptr_t>(d_mask) | reinterpret_cast<uintptr_t>(d_without) |
+                      reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
+  uint64_t groups = ((wide ? n / 16 + 16 : n) + 255) / 256;
+  if (groups > 4096) groups = 4096;
+  hipLaunchKernelGGL(k_mask_andnot, dim3((uint32_t)groups), dim3(256), 0, s, n, d_mask, d_without,
+                     d_out, wide);
   return hipGetLastError();
 }
 

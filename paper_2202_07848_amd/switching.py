@@ -33,7 +33,9 @@ the incoming rank's delta where it has the chunk, else from the base copy
 (``ckpt_restore_chain`` over [base slices..., delta], restricted to the chunks that
 differ).
 Ranks may differ from the base in any chunks; when they differ in the same ones the
-base copy is never read and the traffic is that of `switch(exchange=False)`.
+base copy is never read.  With exchange=True the exchange pass runs first and only
+the chunks the outgoing rank alone changed are then repaired from the base copy,
+so the usual case costs what `switch(exchange=True)` costs.
 """
 from __future__ import annotations
 
@@ -121,13 +123,29 @@ class TimeSlicedRanks:
             self.base_links.append((host, nbytes, manifest, hi - lo, None))
         self.base_bytes = total
 
-    def switch_exact(self, outgoing: int, incoming: int, stream=None) -> None:
+    def switch_exact(self, outgoing: int, incoming: int, stream=None,
+                     exchange: bool = False) -> None:
         """Enqueue one context switch that is exact whatever chunks the two ranks changed;
-        nothing is read on the host.  The outgoing rank's delta against the base goes out; then
-        the chunks whose checksum differs between the incoming rank (at its last swap-out) and
-        what is resident come in, from the incoming rank's delta or, where that rank never
-        changed the chunk, from the base copy."""
+        nothing is read on the host.
+
+        exchange=False: the outgoing rank's delta against the base goes out; then the chunks
+        whose checksum differs between the incoming rank (at its last swap-out) and what is
+        resident come in, from the incoming rank's delta or, where that rank never changed the
+        chunk, from the base copy.  Chunks both ranks changed to the same content stay.
+
+        exchange=True: `switch` with the exchange pass first (one pass over both directions of
+        the host link when the two deltas cover the same chunks, else swap-out then swap-in of
+        the incoming delta); afterwards the chunks only the outgoing rank changed -- marked for
+        it, not for the incoming rank -- get the base's bytes back.  When the deltas line up
+        there are none, and the switch costs what the exchange pass costs."""
         assert self.exact and self.base_links is not None, "exact mode needs capture_base()"
+        if exchange:
+            self.switch(outgoing, incoming, stream, exchange=True)
+            ck.mask_andnot(self.plan, self.mask[outgoing], self.mask[incoming], self.incoming,
+                           stream)
+            ck.restore_chain(self.plan, self.base_links, self.chain_ws, self.chain_stats, stream,
+                             only=self.incoming)
+            return
         self.swap_out(outgoing, stream)
         ck.diff(self.plan, self.rank_digests[incoming], self.rank_digests[outgoing], self.incoming,
                 self.incoming_counts, stream)

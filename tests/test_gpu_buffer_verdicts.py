@@ -104,3 +104,29 @@ def test_empty_plan_and_argument_checks():
         with pytest.raises(ck.CkptError) as e:
             ck.buffer_verdicts(*args)
         assert e.value.status == -1
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 4096, 100003])
+@pytest.mark.parametrize("shift", [0, 1])
+def test_mask_andnot_against_the_oracle(n, shift):
+    """Every byte value counts as set; odd addresses take the bytewise path; the result may
+    overwrite either input; nothing is written past N."""
+    rng = np.random.default_rng(n + shift)
+    dev = DeviceBuffers([np.zeros(n * 256, np.uint8)], 256)
+    assert dev.plan.nchunks == n
+    a = rng.integers(0, 3, size=n, dtype=np.uint8) * rng.integers(1, 128, size=n, dtype=np.uint8)
+    b = rng.integers(0, 3, size=n, dtype=np.uint8) * rng.integers(1, 128, size=n, dtype=np.uint8)
+    want = oracle.mask_andnot(a, b)
+    pad = np.full(32, 0x77, np.uint8)
+    da = torch.from_numpy(np.concatenate([pad, a, pad])).cuda()[32 - shift:]
+    db = torch.from_numpy(np.concatenate([pad, b, pad])).cuda()[32 - shift:]
+    out = torch.full((n + 64,), 0x55, dtype=torch.uint8, device="cuda")
+    ck.mask_andnot(dev.plan, da[shift:], db[shift:], out[shift:])
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[shift:shift + n], want)
+    assert np.all(got[:shift] == 0x55) and np.all(got[shift + n:] == 0x55)
+    ck.mask_andnot(dev.plan, da[shift:], db[shift:], da[shift:])          # in place
+    torch.cuda.synchronize()
+    assert np.array_equal(da.cpu().numpy()[shift:shift + n], want)
+    assert np.all(da.cpu().numpy()[shift + n:] == 0x77)

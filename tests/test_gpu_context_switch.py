@@ -316,7 +316,8 @@ def chunk_differences(w, a, b):
     return count
 
 
-def test_exact_switch_between_ranks_that_changed_different_chunks():
+@pytest.mark.parametrize("exchange", [False, True], ids=["by_checksums", "exchange_then_repair"])
+def test_exact_switch_between_ranks_that_changed_different_chunks(exchange):
     """Ranks that differ from the base in different chunks: one changes shared state on its own,
     one has a per-rank buffer that equals the base, and every mini-batch rewrites a few chunks
     anywhere.  `switch_exact` must leave exactly the incoming rank's state on the device after
@@ -368,23 +369,31 @@ def test_exact_switch_between_ranks_that_changed_different_chunks():
             state[resident][i][lo:hi] = fresh
             dev.arena[dev.offs[i] + lo:dev.offs[i] + hi] = torch.from_numpy(fresh).cuda()
         nxt = (resident + 2) % NRANKS if step % 3 == 2 else (resident + 1) % NRANKS
-        sw.switch_exact(resident, nxt)
+        sw.switch_exact(resident, nxt, exchange=exchange)
         torch.cuda.synchronize()
         swapped[resident] = [b.copy() for b in state[resident]]
         got, img = dev.host()
         assert all(np.array_equal(g, s) for g, s in zip(got, state[nxt])), step
-        assert dev.canaries_intact(img)
+        assert dev.canaries_intact(img) and int(sw.rejected.item()) == 0
         stats = [int(x) for x in sw.chain_stats.cpu().numpy().view(np.uint64)]
-        assert stats[0] == chunk_differences(w, state[resident], state[nxt]) and stats[2] == 0
 
         # the same switch replayed on the host with the oracle
         dig_out = oracle.fingerprint(state[resident], w.chunk, 8)
         dig_in = oracle.fingerprint(swapped[nxt], w.chunk, 8)
+        m_out, _ = oracle.diff(state[resident], w.chunk, dig_out, o_ref)
         m_in, _ = oracle.diff(swapped[nxt], w.chunk, dig_in, o_ref)
         delta = oracle.compact(swapped[nxt], w.chunk, m_in, dig_in)[:2]
-        only, _ = oracle.diff(swapped[nxt], w.chunk, dig_in, dig_out)
         host_image = [b.copy() for b in state[resident]]
-        o_stats = oracle.restore_chain(host_image, w.chunk, [base_link, delta], only)
+        if exchange:
+            # the incoming delta whole, then the base's bytes where only the outgoing rank differs
+            assert oracle.restore(host_image, w.chunk, *delta) == 0
+            only = oracle.mask_andnot(m_out, m_in)
+            o_stats = oracle.restore_chain(host_image, w.chunk, [base_link], only)
+            assert stats[0] == int(only.sum())
+        else:
+            only, _ = oracle.diff(swapped[nxt], w.chunk, dig_in, dig_out)
+            o_stats = oracle.restore_chain(host_image, w.chunk, [base_link, delta], only)
+            assert stats[0] == chunk_differences(w, state[resident], state[nxt])
         assert all(np.array_equal(h, s) for h, s in zip(host_image, state[nxt]))
         assert [o_stats["written"], o_stats["superseded"], o_stats["rejected"]] == stats
         assert np.array_equal(sw.incoming[:n].cpu().numpy(), only)
