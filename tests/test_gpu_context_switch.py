@@ -400,7 +400,8 @@ def test_exact_switch_between_ranks_that_changed_different_chunks(exchange):
         resident = nxt
 
 
-def test_exact_switches_replay_from_hip_graphs():
+@pytest.mark.parametrize("exchange", [False, True], ids=["by_checksums", "exchange_then_repair"])
+def test_exact_switches_replay_from_hip_graphs(exchange):
     """switch_exact enqueues kernels only (the chain restore takes its links as kernel
     arguments and reads counts and the restriction on the device), so it replays from a graph:
     two ranks ping-pong through two graphs while the resident rank rewrites chunks anywhere,
@@ -427,12 +428,12 @@ def test_exact_switches_replay_from_hip_graphs():
     graphs = {}
     with torch.cuda.stream(side):
         for a, b in ((1, 0), (0, 1)):                   # eager round trip on the capture stream
-            sw.switch_exact(a, b, stream=side)
+            sw.switch_exact(a, b, stream=side, exchange=exchange)
         side.synchronize()
         for a, b in ((1, 0), (0, 1)):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                sw.switch_exact(a, b, stream=side)
+                sw.switch_exact(a, b, stream=side, exchange=exchange)
             graphs[(a, b)] = g
     torch.cuda.synchronize()
     got, _ = dev.host()
@@ -456,5 +457,7 @@ def test_exact_switches_replay_from_hip_graphs():
         assert all(np.array_equal(x, y) for x, y in zip(got, state[nxt])), step
         assert dev.canaries_intact(img)
         stats = [int(x) for x in sw.chain_stats.cpu().numpy().view(np.uint64)]
-        assert stats[0] == chunk_differences(w, state[resident], state[nxt]) and stats[2] == 0
+        assert stats[2] == 0 and int(sw.rejected.item()) == 0
+        if not exchange:
+            assert stats[0] == chunk_differences(w, state[resident], state[nxt])
         resident = nxt
