@@ -92,6 +92,8 @@ def _load():
         lib.ora_restore.argtypes = [vp, u64, u64, vp, u64, vp, u64]
         lib.ora_restore_chain.restype = ctypes.c_int
         lib.ora_restore_chain.argtypes = [vp, u64, u64, vp, u64, vp, vp]
+        lib.ora_marks_from_buffers.restype = None
+        lib.ora_marks_from_buffers.argtypes = [vp, u64, u64, vp, vp]
         lib.ora_mask_andnot.restype = None
         lib.ora_mask_andnot.argtypes = [u64, vp, vp, vp]
         lib.ora_buffer_verdicts.restype = None
@@ -347,3 +349,15 @@ def mask_andnot(mask: np.ndarray, without: np.ndarray) -> np.ndarray:
     out = np.full(mask.size, 0xA5, dtype=np.uint8)
     _load().ora_mask_andnot(mask.size, _p(mask), _p(without), _p(out))
     return out
+
+
+def marks_from_buffers(sizes: Sequence[int], chunk: int, flags: np.ndarray) -> np.ndarray:
+    """One mark per chunk: 1 for every chunk of a buffer whose flag is non-zero."""
+    sz = np.ascontiguousarray(sizes, dtype=np.uint64)
+    flags = np.ascontiguousarray(flags, dtype=np.uint8)
+    if flags.size != sz.size:
+        raise ValueError("one flag per buffer is needed")
+    n = int(((sz + np.uint64(chunk - 1)) // np.uint64(chunk)).sum())
+    marks = np.full(n, 0xA5, dtype=np.uint8)
+    _load().ora_marks_from_buffers(_p(sz), sz.size, chunk, _p(flags), _p(marks))
+    return marks

@@ -679,6 +679,21 @@ void ora_buffer_verdicts(const uint64_t *sizes, uint64_t nbufs, uint64_t chunk, 
   result[1] = bytes;
 }
 
+/* --------------------------------------------------- marks from buffers */
+/* The reverse of ora_buffer_verdicts: every chunk of a flagged buffer is marked.
+ * Which buffers hold per-replica state (gradients, activations, sec. 5.2.1) is
+ * stable from switch to switch and known per buffer, so a prediction of the
+ * chunk marks -- the hint of the single-pass snapshot -- can be kept as one
+ * byte per buffer. */
+void ora_marks_from_buffers(const uint64_t *sizes, uint64_t nbufs, uint64_t chunk,
+                            const uint8_t *flags, uint8_t *marks) {
+  uint64_t k = 0;
+  for (uint64_t i = 0; i < nbufs; ++i) {
+    uint64_t n = (sizes[i] + chunk - 1) / chunk;
+    for (uint64_t j = 0; j < n; ++j) marks[k++] = flags[i] ? 1 : 0;
+  }
+}
+
 /* ---------------------------------------------------------- mask and-not */
 /* out[k] = 1 where mask[k] is set and without[k] is not, else 0.  At a context
  * switch (sec. 5.2.1) with mask = the chunks in which the outgoing rank differs

@@ -127,6 +127,9 @@ def verdict_pins():
     tb.test_each_single_chunk_marks_exactly_its_buffer()
     tb.test_empty_list_and_only_empty_buffers()
     tb.test_mask_andnot_truth_table_and_random()
+    for seed in (1, 2, 3):
+        tb.test_marks_from_buffers_is_a_numpy_repeat_and_inverts_the_verdicts(seed)
+    tb.test_marks_from_buffers_predict_the_diff_when_whole_buffers_differ()
 
 
 def worker_states(world, seed, sizes=(5000, 256, 0, 1300, 77), chunk=256):
@@ -200,8 +203,8 @@ def use_library(path):
     other = ctypes.CDLL(path)
     for fn in ("ora_xxh64", "ora_nchunks", "ora_chunk_lens", "ora_fingerprint", "ora_diff",
                "ora_compact", "ora_restore", "ora_restore_chain", "ora_merge_chain",
-               "ora_buffer_verdicts", "ora_mask_andnot", "ora_upload_owners", "ora_match", "ora_apply_matches",
-               "ora_validate_mutations"):
+               "ora_buffer_verdicts", "ora_mask_andnot", "ora_marks_from_buffers",
+               "ora_upload_owners", "ora_match", "ora_apply_matches", "ora_validate_mutations"):
         getattr(other, fn).restype = getattr(good, fn).restype
         getattr(other, fn).argtypes = getattr(good, fn).argtypes
     oracle._lib = other

@@ -70,3 +70,30 @@ def test_mask_andnot_truth_table_and_random():
     b = rng.integers(0, 3, size=5000, dtype=np.uint8)
     assert np.array_equal(oracle.mask_andnot(a, b), ((a != 0) & (b == 0)).astype(np.uint8))
     assert oracle.mask_andnot(np.zeros(0, np.uint8), np.zeros(0, np.uint8)).size == 0
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_marks_from_buffers_is_a_numpy_repeat_and_inverts_the_verdicts(seed):
+    rng = np.random.default_rng(seed)
+    flags = rng.integers(0, 2, size=len(SIZES), dtype=np.uint8) * rng.integers(1, 256, size=len(SIZES), dtype=np.uint8)
+    marks = oracle.marks_from_buffers(SIZES, CHUNK, flags)
+    counts = [(n + CHUNK - 1) // CHUNK for n in SIZES]
+    assert np.array_equal(marks, np.repeat((flags != 0).astype(np.uint8), counts))
+    # verdicts of those marks give the flags back, for buffers that have chunks at all
+    dirty, _ = oracle.buffer_verdicts(SIZES, CHUNK, marks)
+    assert dirty.tolist() == [int(f != 0 and n > 0) for f, n in zip(flags, SIZES)]
+
+
+def test_marks_from_buffers_predict_the_diff_when_whole_buffers_differ():
+    """The use: buffers 1 and 5 are per-replica state; flagged, their chunks are exactly what
+    the comparison of two replicas marks."""
+    rng = np.random.default_rng(4)
+    ref = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in SIZES]
+    new = [b.copy() for b in ref]
+    for i in (1, 5):
+        new[i][:] = rng.integers(0, 256, size=new[i].size, dtype=np.uint8)
+    mask, _ = oracle.diff(new, CHUNK, oracle.fingerprint(new, CHUNK), oracle.fingerprint(ref, CHUNK))
+    flags = np.zeros(len(SIZES), np.uint8)
+    flags[[1, 5]] = 1
+    assert np.array_equal(oracle.marks_from_buffers(SIZES, CHUNK, flags), mask)
+    assert oracle.marks_from_buffers([], CHUNK, np.zeros(0, np.uint8)).size == 0

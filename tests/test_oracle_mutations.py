@@ -113,6 +113,8 @@ MUTATIONS = [
      "    for (uint64_t j = 0; j < n; ++j, ++k)\n      if (mask[k]) any = 1;",
      "    for (uint64_t j = 0; j < n; ++j) {\n      if (mask[k]) any = 1;\n      if (any) ++k;\n    }"),
     ("verdicts: bytes counted in chunks", "      bytes += sizes[i];", "      bytes += n * chunk;"),
+    ("marks: flag of the wrong buffer", "marks[k++] = flags[i] ? 1 : 0;", "marks[k++] = flags[j < nbufs ? j : i] ? 1 : 0;"),
+    ("marks: flag value copied instead of 0 / 1", "marks[k++] = flags[i] ? 1 : 0;", "marks[k++] = flags[i];"),
     ("andnot: second mask not negated", "(mask[k] != 0 && without[k] == 0) ? 1 : 0",
      "(mask[k] != 0 && without[k] != 0) ? 1 : 0"),
     ("andnot: only the value 1 counts as set", "(mask[k] != 0 && without[k] == 0) ? 1 : 0",
