@@ -543,6 +543,16 @@ typedef struct ckpt_buffer_counts {
 int ckpt_buffer_verdicts(const ckpt_plan_t *plan, const uint8_t *d_mask, uint8_t *d_buf_dirty,
                          ckpt_buffer_counts_t *d_counts, void *stream);
 
+/* The reverse of ckpt_buffer_verdicts: d_marks[k] = 1 for every chunk of a
+ * buffer with d_buf_flags[i] != 0, else 0.  Which buffers hold per-replica state
+ * is stable from switch to switch (sec. 5.2.1), so the prediction ckpt_snapshot
+ * takes as d_hint can be kept as one byte per buffer -- the d_buf_dirty of the
+ * previous switch, or what the allocator's owner knows -- and expanded here.
+ *   d_buf_flags  device array of B bytes;  d_marks  device array of N bytes
+ * Errors: INVALID_ARG, DEVICE. */
+int ckpt_marks_from_buffers(const ckpt_plan_t *plan, const uint8_t *d_buf_flags, uint8_t *d_marks,
+                            void *stream);
+
 /* d_out[k] = 1 where d_mask[k] != 0 and d_without[k] == 0, else 0, for the N
  * chunks of the plan.  With d_mask the chunks in which the outgoing rank of a
  * context switch differs from the common base and d_without those of the

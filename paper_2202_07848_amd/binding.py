@@ -32,6 +32,7 @@ EXPORTS = (
     "ckpt_snapshot_static", "ckpt_snapshot_static_max_chunks",
     "ckpt_plan_split_threshold", "ckpt_plan_set_split_threshold", "ckpt_match_workspace_bytes", "ckpt_match", "ckpt_apply_matches", "ckpt_moves_workspace_bytes", "ckpt_apply_moves_inplace",
     "ckpt_validate_mutations", "ckpt_upload_owners", "ckpt_buffer_verdicts", "ckpt_mask_andnot",
+    "ckpt_marks_from_buffers",
     "ckpt_swapper_create", "ckpt_swapper_destroy", "ckpt_swap_out", "ckpt_swap_in",
     "ckpt_bw_copy", "ckpt_bw_read", "ckpt_bw_streams", "ckpt_alu_xxh64", "ckpt_strerror", "ckpt_last_device_error",
     "ckpt_version",
@@ -129,6 +130,8 @@ def _lib():
         lib.ckpt_moves_workspace_bytes.argtypes = [u64]
         lib.ckpt_apply_moves_inplace.restype = ci
         lib.ckpt_apply_moves_inplace.argtypes = [vp, vp, vp, u64, vp, u64, vp, vp, vp]
+        lib.ckpt_marks_from_buffers.restype = ci
+        lib.ckpt_marks_from_buffers.argtypes = [vp, vp, vp, vp]
         lib.ckpt_mask_andnot.restype = ci
         lib.ckpt_mask_andnot.argtypes = [vp, vp, vp, vp, vp]
         lib.ckpt_buffer_verdicts.restype = ci
@@ -399,6 +402,12 @@ def restore_chain(dst_plan: Plan, links, workspace, stats=None, stream=None, onl
     _check(_lib().ckpt_restore_chain(dst_plan._h, arr, len(links), _ptr(only), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _ptr(stats),
                                      _stream(stream)), "ckpt_restore_chain")
+
+
+def marks_from_buffers(plan: Plan, buf_flags, marks, stream=None) -> None:
+    """``ckpt_marks_from_buffers``: marks (uint8, N) = 1 for every chunk of a flagged buffer."""
+    _check(_lib().ckpt_marks_from_buffers(plan._h, _ptr(buf_flags), _ptr(marks), _stream(stream)),
+           "ckpt_marks_from_buffers")
 
 
 def mask_andnot(plan: Plan, mask, without, out, stream=None) -> None:

@@ -664,6 +664,16 @@ int ckpt_apply_moves_inplace(const ckpt_plan_t *plan, const int64_t *d_src, void
   return e == hipSuccess ? CKPT_OK : device_error(e);
 }
 
+int ckpt_marks_from_buffers(const ckpt_plan_t *plan, const uint8_t *d_buf_flags, uint8_t *d_marks,
+                            void *stream) {
+  if (plan == nullptr) return CKPT_ERR_INVALID_ARG;
+  if (plan->dev.nchunks != 0 && (d_buf_flags == nullptr || d_marks == nullptr))
+    return CKPT_ERR_INVALID_ARG;
+  hipError_t e = ckpt::launch_marks_from_buffers(plan->dev, d_buf_flags, d_marks,
+                                                 static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? CKPT_OK : device_error(e);
+}
+
 int ckpt_mask_andnot(const ckpt_plan_t *plan, const uint8_t *d_mask, const uint8_t *d_without,
                      uint8_t *d_out, void *stream) {
   if (plan == nullptr) return CKPT_ERR_INVALID_ARG;

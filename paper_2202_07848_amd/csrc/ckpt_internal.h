@@ -201,6 +201,9 @@ hipError_t launch_merge_chain(const PlanDev &p, const ChainArgs &a, void *d_stag
 hipError_t launch_upload_owners(const PlanDev &p, const uint64_t *d_gathered, uint32_t world,
                                 uint32_t rank, uint8_t *d_mask, uint64_t *d_blocksums,
                                 ckpt_counts_t *d_counts, hipStream_t s);
+// d_flags: one byte per buffer of the caller's list; d_marks: one per chunk.
+hipError_t launch_marks_from_buffers(const PlanDev &p, const uint8_t *d_flags, uint8_t *d_marks,
+                                     hipStream_t s);
 // d_out may be d_mask or d_without itself.
 hipError_t launch_mask_andnot(uint64_t n, const uint8_t *d_mask, const uint8_t *d_without,
                               uint8_t *d_out, hipStream_t s);

@@ -537,6 +537,19 @@ __global__ __launch_bounds__(256) void k_verdict_count(PlanDev p, const uint8_t 
   }
 }
 
+// marks[k] = 1 for every chunk of a buffer whose flag is set: the reverse of the verdicts, one
+// thread per four consecutive chunks.
+__global__ __launch_bounds__(SCAN_THREADS) void k_marks_from_buffers(
+    PlanDev p, const uint8_t *__restrict__ flags, uint8_t *__restrict__ marks) {
+  const uint64_t k0 = thread_first_chunk();
+  if (k0 >= p.nchunks) return;
+  const uint64_t left = p.nchunks - k0;
+  const int n = left < SCAN_PER_THREAD ? (int)left : SCAN_PER_THREAD;
+  ChunkRef refs[SCAN_PER_THREAD];
+  locate_run(p, k0, n, refs);
+  for (int i = 0; i < n; ++i) marks[k0 + i] = flags[p.dense_orig[refs[i].row]] != 0 ? 1 : 0;
+}
+
 // out[k] = 1 where mask[k] is set and without[k] is not.  Sixteen chunks per thread when the
 // three arrays allow 16-byte accesses, else one.
 __global__ __launch_bounds__(256) void k_mask_andnot(uint64_t n, const uint8_t *mask,
@@ -668,6 +681,15 @@ hipError_t launch_validate(uint64_t n, const uint64_t *b_a, const uint64_t *a_a,
     hipLaunchKernelGGL(k_validate, dim3((uint32_t)groups), dim3(SCAN_THREADS), 0, s, n, b_a, a_a,
                        b_b, a_b, d_result);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_marks_from_buffers(const PlanDev &p, const uint8_t *d_flags, uint8_t *d_marks,
+                                     hipStream_t s) {
+  const uint32_t nblocks = scan_blocks(p.nchunks);
+  if (nblocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_marks_from_buffers, dim3(nblocks), dim3(SCAN_THREADS), 0, s, p, d_flags,
+                     d_marks);
   return hipGetLastError();
 }
 

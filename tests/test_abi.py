@@ -68,6 +68,7 @@ def test_host_side_argument_checks_need_no_device():
     assert lib.ckpt_manifest(None, None, None, 0, None, 0, None, None) == -1
     assert lib.ckpt_buffer_verdicts(None, None, None, None, None) == -1
     assert lib.ckpt_mask_andnot(None, None, None, None, None) == -1
+    assert lib.ckpt_marks_from_buffers(None, None, None, None) == -1
     assert lib.ckpt_restore_chain(None, None, 0, None, None, 0, None, None) == -1
     assert lib.ckpt_restore_chain_workspace_bytes(1000) == 16016
     assert lib.ckpt_merge_chain(None, None, 0, None, 0, None, 0, None, None, 0, None, None) == -1

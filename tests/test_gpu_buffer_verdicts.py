@@ -130,3 +130,56 @@ def test_mask_andnot_against_the_oracle(n, shift):
     torch.cuda.synchronize()
     assert np.array_equal(da.cpu().numpy()[shift:shift + n], want)
     assert np.all(da.cpu().numpy()[shift + n:] == 0x77)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_marks_from_buffers_against_the_oracle(seed):
+    rng = np.random.default_rng(70 + seed)
+    chunk = int(rng.choice([256, 512, 4096]))
+    sizes = [int(x) for x in rng.integers(0, 40 * chunk, size=200)]
+    sizes += [0, 0, 1, chunk - 1, chunk, chunk + 1] + [int(x) for x in rng.integers(1, 64, size=100)]
+    rng.shuffle(sizes)
+    flags = (rng.random(len(sizes)) < 0.4).astype(np.uint8) * rng.integers(1, 256, size=len(sizes), dtype=np.uint8)
+    dev = DeviceBuffers([np.zeros(n, np.uint8) for n in sizes], chunk)
+    n = dev.plan.nchunks
+    marks = torch.full((n + 64,), 0x77, dtype=torch.uint8, device="cuda")
+    ck.marks_from_buffers(dev.plan, torch.from_numpy(flags).cuda(), marks)
+    torch.cuda.synchronize()
+    got = marks.cpu().numpy()
+    assert np.array_equal(got[:n], oracle.marks_from_buffers(sizes, chunk, flags))
+    assert np.all(got[n:] == 0x77)
+
+
+def test_buffer_flags_as_the_hint_of_the_first_snapshot():
+    """The use: per-replica buffers flagged by whoever owns the allocator, expanded to the hint
+    of ckpt_snapshot -- exact when whole buffers differ, so no chunk is gathered afterwards and
+    every output equals the oracle's."""
+    w = wl.config(4, 16)
+    a0, offs = wl.torch_replica(w, 0, "cuda")
+    a1, _ = wl.torch_replica(w, 1, "cuda", shared_from=a0)
+    p0, p1 = (ck.Plan([(a.data_ptr() + int(o), b.nbytes) for o, b in zip(offs, w.bufs)], w.chunk)
+              for a in (a0, a1))
+    n = p1.nchunks
+    ref = run_fingerprint(p0)
+    flags = torch.tensor([0 if b.shared else 1 for b in w.bufs], dtype=torch.uint8, device="cuda")
+    hint = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    ck.marks_from_buffers(p1, flags, hint)
+    dig = torch.zeros(n, dtype=torch.int64, device="cuda")
+    mask = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    misses = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    staging = torch.zeros(w.distinct_bytes, dtype=torch.uint8, device="cuda")
+    manifest = torch.zeros(w.distinct_chunks * 32, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(ck.snapshot_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ck.snapshot(p1, ref, hint, dig, mask, staging, manifest, counts, misses, ws)
+    torch.cuda.synchronize()
+    assert int(misses.item()) == 0 and ck.snapshot_stats(ws, n)["regathered_chunks"] == 0
+    host0, host1 = ([a[int(o):int(o) + b.nbytes].cpu().numpy() for o, b in zip(offs, w.bufs)]
+                    for a in (a0, a1))
+    o_dig = oracle.fingerprint(host1, w.chunk, 8)
+    o_mask, _ = oracle.diff(host1, w.chunk, o_dig, oracle.fingerprint(host0, w.chunk, 8))
+    o_st, o_man, o_cnt = oracle.compact(host1, w.chunk, o_mask, o_dig)
+    assert np.array_equal(dig.cpu().numpy().view(np.uint64), o_dig)
+    assert np.array_equal(mask.cpu().numpy(), o_mask) and np.array_equal(hint.cpu().numpy(), o_mask)
+    assert np.array_equal(staging.cpu().numpy(), o_st)
+    assert np.array_equal(ck.manifest_to_numpy(manifest, o_cnt["ndirty"]), o_man)
