@@ -346,3 +346,51 @@ def test_config4_chain_restore_full_size():
     total = int(sum(s.sum() for s in sets))
     assert [int(x) for x in stats.cpu().numpy().view(np.uint64)] == [union, total - union, 0]
     print(f"config 4 chain: {len(links)} links, {total} entries, {union} chunks written once")
+
+
+@pytest.mark.parametrize("chunk", [1 << 20, 4096], ids=["1MiB_chunks", "4KiB_chunks"])
+def test_one_buffer_larger_than_4_gib_every_element(chunk):
+    """Offsets inside a buffer beyond 2^32: one 4.5 GiB + 4 321 byte buffer (and a small second
+    one), as 4 613 chunks of 1 MiB or as 1.18 million chunks of 4 KiB in ONE buffer; reference = a copy that differs in a few chunks on both sides of the
+    4 GiB line and in the ragged tail.  Every digest, mask byte, manifest entry and staged byte
+    against the oracle, both call shapes, then the restore."""
+    sizes = [(9 << 29) + 4321, 3 * (1 << 20) + 17]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    offs = [0, (sizes[0] + 255) // 256 * 256]
+    arena_ref = torch.randint(0, 256, (offs[1] + sizes[1],), dtype=torch.uint8, device="cuda",
+                              generator=g)
+    arena_new = arena_ref.clone()
+    for off in (5, (1 << 32) - 3, (1 << 32) + chunk + 9, sizes[0] - 1, offs[1] + 2 * chunk + 1):
+        arena_new[off] ^= 0x5A
+    plans = [ck.Plan([(a.data_ptr() + o, n) for o, n in zip(offs, sizes)], chunk)
+             for a in (arena_ref, arena_new)]
+    n = plans[1].nchunks
+    assert n == sum(-(-x // chunk) for x in sizes)
+    host_ref, host_new = ([a[o:o + s].cpu().numpy() for o, s in zip(offs, sizes)]
+                          for a in (arena_ref, arena_new))
+    o_ref = oracle.fingerprint(host_ref, chunk, THREADS)
+    o_dig = oracle.fingerprint(host_new, chunk, THREADS)
+    o_mask, o_cnt = oracle.diff(host_new, chunk, o_dig, o_ref)
+    o_st, o_man, _ = oracle.compact(host_new, chunk, o_mask, o_dig)
+    assert o_cnt["ndirty"] == 5
+    ref = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ck.fingerprint(plans[0], ref)
+    torch.cuda.synchronize()
+    assert np.array_equal(ref.cpu().numpy().view(np.uint64), o_ref)
+
+    class View:                                   # what Snapshot() needs of a replica
+        def __init__(self, plan):
+            self.plan = plan
+
+    prev = None
+    for path in PATHS:
+        s = Snapshot(View(plans[1]), ref, path, prev)
+        assert np.array_equal(s.h_dig, o_dig) and np.array_equal(s.h_mask, o_mask)
+        assert s.h_man.tolist() == o_man.tolist()
+        assert np.array_equal(s.staging.cpu().numpy()[:s.staged], o_st)
+        prev = s
+    rejected = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ck.restore(plans[0], prev.staging, prev.staged, prev.manifest, prev.ndirty, rejected)
+    torch.cuda.synchronize()
+    assert int(rejected.item()) == 0 and torch.equal(arena_ref, arena_new)
